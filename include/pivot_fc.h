@@ -1,0 +1,237 @@
+/*
+ * pivot_fc.h - C ABI of the pruned fully-connected inference library for
+ * AMD MI355X (gfx950).
+ *
+ * A pruned FC layer is kept in permutation-block-permutation (PBP) form,
+ *     M_sparse = P_row * M_block * P_col                       (paper Eq. 1)
+ * and applied as
+ *     a_out = P_row (M_block (P_col a_in))                     (paper Eq. 2)
+ * plus a bias and a point-wise activation:
+ *     y = act(P_r^T * BSR(W') * (P_c x) + b).
+ *
+ * Conventions used by every entry point
+ * -------------------------------------
+ *  - A permutation is an index array that acts as a gather,
+ *    out[i] = in[idx[i]] (Section 4.1.4: the index array of "cab" relative to
+ *    "abc" is [2,0,1]).  With W' the pivoted (block-space) matrix:
+ *        W'[r][c] = W[prow[r]][pcol[c]],   xg[c] = x[pcol[c]],   y[prow[r]] = v[r]
+ *    (Listing 1 gathers the input through P_col and scatters the output
+ *    through P_row).
+ *  - The tile mask lives in block space: tile (i,j) covers block-space rows
+ *    [i*bh,(i+1)*bh) and columns [j*bw,(j+1)*bw).  nbr = ceil(M/bh),
+ *    nbc = ceil(K/bw); rows >= M and columns >= K of the last tiles are zero
+ *    padding and are never gathered or scattered (Section 4.1.5 allows
+ *    irregular shapes; padding is the form used here).
+ *  - Several kept tiles may share a block row; their partial results are
+ *    summed in a fixed order (Section 4.1.5), so repeated runs give identical
+ *    bits.
+ *  - "host" pointers are ordinary CPU memory, borrowed for the duration of the
+ *    call.  "device" pointers are HIP device memory on the plan's device,
+ *    borrowed until the work enqueued on `stream` has finished.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Run calls are asynchronous: they enqueue kernels, never allocate, never
+ *    synchronise.
+ *  - Every function returns PIVOT_OK (0) or a negative PIVOT_E_* code and
+ *    never throws or aborts; pivot_last_error() gives a thread-local text.
+ */
+#ifndef PIVOT_FC_H
+#define PIVOT_FC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PIVOT_VERSION 100
+
+#define PIVOT_OK                  0
+#define PIVOT_E_NULL             -1   /* a required pointer is NULL */
+#define PIVOT_E_SHAPE            -2   /* sizes are not positive / do not match */
+#define PIVOT_E_NOT_PERMUTATION  -3   /* prow or pcol is not a bijection of its range */
+#define PIVOT_E_UNSUPPORTED      -4   /* tile shape / dtype / layout / batch not supported on the device path */
+#define PIVOT_E_ALLOC            -5   /* host or device allocation failed */
+#define PIVOT_E_HIP              -6   /* a HIP call failed */
+#define PIVOT_E_WORKSPACE        -7   /* workspace missing or too small */
+#define PIVOT_E_NO_DEVICE        -8   /* a host-only plan was given to a run call */
+
+/* weight storage type; x has the same type, accumulation is fp32 */
+#define PIVOT_F32 0
+#define PIVOT_F16 1
+
+/* physical layout of the kept tiles (Section 4.1.1), rightmost axis fastest */
+#define PIVOT_BRC 0   /* block, row, column : row-major inside a tile    */
+#define PIVOT_BCR 1   /* block, column, row : column-major inside a tile */
+#define PIVOT_CBR 2   /* column, block, row : one column position of all tiles together */
+
+#define PIVOT_ACT_NONE 0
+#define PIVOT_ACT_RELU 1
+
+/* coordinate space of the weight matrix handed to pivot_fc_plan */
+#define PIVOT_W_NATURAL 0   /* W[M][K] as trained; entries outside kept tiles are ignored */
+#define PIVOT_W_PIVOTED 1   /* W'[M][K] already in block space */
+
+typedef struct pivot_fc_desc {
+    int32_t M;            /* outputs (rows of the weight matrix)                         */
+    int32_t K;            /* inputs  (columns)                                           */
+    int32_t bh;           /* tile rows                                                   */
+    int32_t bw;           /* tile columns                                                */
+    int32_t wdtype;       /* PIVOT_F32 or PIVOT_F16                                      */
+    int32_t layout;       /* PIVOT_BRC / BCR / CBR                                       */
+    int32_t act;          /* PIVOT_ACT_*                                                 */
+    int32_t chunk_tiles;  /* max tiles per work item; 0 = the library chooses            */
+    int32_t device;       /* HIP device ordinal, or -1 for a host-only plan (no GPU use) */
+    int32_t flags;        /* reserved, must be 0                                         */
+} pivot_fc_desc;
+
+typedef struct pivot_fc_plan pivot_fc_plan_t;
+typedef struct pivot_mlp_plan pivot_mlp_plan_t;
+
+/* Read-only view of a plan's canonical host arrays (valid until the plan is
+ * destroyed).  Tiles are numbered by (block row, block column) ascending.
+ * Offsets of element (r,c) of tile t in `vals`:
+ *   BRC ((t*bh)+r)*bw+c     BCR ((t*bw)+c)*bh+r     CBR ((c*T)+t)*bh+r
+ * `chunks` holds nchunks rows of (block_row, tile_begin, tile_end, slot):
+ * every block row's tile list cut into consecutive pieces of at most
+ * chunk_tiles tiles (an empty block row gives one empty piece), `slot` =
+ * ordinal in (block_row, tile_begin) order, rows then stably sorted by
+ * descending length (launch order).  part_base[i] = first slot of block row i.
+ * Partials of a split block row are added in ascending slot order. */
+typedef struct pivot_plan_view {
+    int32_t M, K, bh, bw, wdtype, layout, act;
+    int32_t nbr, nbc, M_pad, K_pad;
+    int32_t T;                 /* kept tiles */
+    int32_t chunk_tiles;       /* resolved value */
+    int32_t nchunks;
+    const int32_t* row_ptr;    /* [nbr+1] */
+    const int32_t* col_idx;    /* [T]     */
+    const void*    vals;       /* [T*bh*bw] of wdtype */
+    const float*   bias_p;     /* [M_pad]  bias_p[r] = bias[prow[r]], 0 in padding */
+    const int32_t* invprow;    /* [M]      invprow[prow[r]] = r */
+    const int32_t* invpcol;    /* [K]      invpcol[pcol[c]] = c */
+    const int32_t* prow_pad;   /* [M_pad]  prow, -1 in padding */
+    const int32_t* pcol_pad;   /* [K_pad]  pcol, -1 in padding */
+    const int32_t* chunks;     /* [nchunks][4] */
+    const int32_t* part_base;  /* [nbr+1] */
+} pivot_plan_view;
+
+int         pivot_version(void);
+const char* pivot_last_error(void);
+
+/*
+ * pivot_fc_plan - the static, data-independent "compile" step (Eq. 1: the
+ * permutations depend on the sparsity pattern only; Section 4.2.1: done at
+ * network implementation time).  Validates the permutations, builds the
+ * block-sparse index, packs the kept tiles of W' in the requested layout,
+ * permutes the bias, cuts the load-balance schedule and (device >= 0) uploads
+ * everything in one device allocation owned by the plan.
+ *
+ *   W         host, M*K elements of wdtype, row-major, in the space `w_space`
+ *   tile_mask host, nbr*nbc bytes, row-major, non-zero = tile kept
+ *   prow      host, M int32;  pcol host, K int32
+ *   bias      host, M floats in natural output coordinates, or NULL (= 0)
+ *   out       receives the plan; NULL on error (nothing is leaked)
+ *
+ * The device path supports BRC plans with power-of-two tiles,
+ * 8 <= bh <= 64 and 8 <= bw <= 64 (wdtype F16: bw >= 8; F32: bw >= 4 also
+ * holds).  Other shapes/layouts still build host-only plans (device = -1).
+ */
+int  pivot_fc_plan(const pivot_fc_desc* desc, const void* W, int w_space,
+                   const uint8_t* tile_mask, const int32_t* prow, const int32_t* pcol,
+                   const float* bias, pivot_fc_plan_t** out);
+int  pivot_fc_plan_host_view(const pivot_fc_plan_t* plan, pivot_plan_view* view);
+/* A second plan with its own copy of all device arrays (used to rotate
+ * through cache-cold copies when measuring). */
+int  pivot_fc_plan_clone(const pivot_fc_plan_t* plan, pivot_fc_plan_t** out);
+void pivot_fc_plan_destroy(pivot_fc_plan_t* plan);   /* NULL-safe */
+
+/* Scratch a run needs for `batch` rows (partials of split block rows and
+ * their arrival counters).  The buffer has to be cleared once with
+ * pivot_workspace_init before its first use; every run leaves it ready for
+ * the next one.  Two runs that overlap in time must not share a workspace. */
+size_t pivot_fc_workspace_bytes(const pivot_fc_plan_t* plan, int batch);
+int    pivot_workspace_init(void* ws_dev, size_t ws_bytes, void* stream);
+
+/*
+ * pivot_fc_run - one application of the layer (Listing 1, generalised to
+ * tiles that share rows): gather x through pcol into LDS, stream the kept
+ * tiles, reduce, add bias, activate, scatter through prow.
+ *
+ *   x_dev  device, [batch][K] of wdtype, row stride ldx elements, natural coordinates
+ *   y_dev  device, [batch][M] fp32, row stride ldy elements, natural coordinates
+ *   batch  1..64 (F16 plans use the matrix cores from batch 8 on)
+ */
+int  pivot_fc_run(const pivot_fc_plan_t* plan, const void* x_dev, int64_t ldx,
+                  void* y_dev, int64_t ldy, int batch,
+                  void* ws_dev, size_t ws_bytes, void* stream);
+
+/*
+ * Chains of layers (Section 4.2).  Between layer l and l+1 the producer's row
+ * scatter and the consumer's column gather are composed at plan time into one
+ * index array q_l[c] = invprow_l[pcol_{l+1}[c]] (Section 4.2.1); the device
+ * applies it on the producer's store, so intermediates live in the consumer's
+ * block order and no separate gather or scatter pass runs.  If
+ * pcol_{l+1} == prow_l the composed array is the identity and nothing
+ * irregular remains at that boundary (Section 4.2.3).  With
+ * PIVOT_MLP_KEEP_FINAL_BLOCK_ORDER the last layer's scatter is dropped and
+ * the host relabels outputs with prow of the last layer (Section 4.2.2):
+ * y_dev then holds M_pad_last values per batch row in block order.
+ * Intermediates have the plans' wdtype (F16 chains round once per boundary).
+ * All layers must share wdtype and device.  Layer plans are borrowed and must
+ * outlive the chain plan.
+ */
+#define PIVOT_MLP_KEEP_FINAL_BLOCK_ORDER 1
+
+typedef struct pivot_mlp_view {
+    int32_t L;
+    int32_t flags;
+    const int32_t* const* q;     /* [L-1] arrays, q[l] has K_{l+1} entries                    */
+    const int32_t* const* dst;   /* [L-1] arrays, dst[l] has M_pad_l entries:
+                                    dst[l][r] = invpcol_{l+1}[prow_l[r]], -1 in padding        */
+    const int32_t* identity;     /* [L-1] flags: 1 if q[l] is the identity                    */
+} pivot_mlp_view;
+
+int    pivot_mlp_plan(pivot_fc_plan_t* const* layers, int L, int flags, pivot_mlp_plan_t** out);
+int    pivot_mlp_plan_host_view(const pivot_mlp_plan_t* plan, pivot_mlp_view* view);
+void   pivot_mlp_plan_destroy(pivot_mlp_plan_t* plan);
+size_t pivot_mlp_workspace_bytes(const pivot_mlp_plan_t* plan, int batch);
+/* x_dev [batch][K_1] (stride ldx), y_dev [batch][M_L] fp32 (stride ldy), or
+ * [batch][M_pad_L] in block order with PIVOT_MLP_KEEP_FINAL_BLOCK_ORDER. */
+int    pivot_mlp_run(const pivot_mlp_plan_t* plan, const void* x_dev, int64_t ldx,
+                     void* y_dev, int64_t ldy, int batch,
+                     void* ws_dev, size_t ws_bytes, void* stream);
+
+/*
+ * Recurrent use: an LSTM whose gate matrix (4H x (H+I), gate order i,f,g,o,
+ * input [h_{t-1}; x_t]) is a pruned layer.  The recurrence is a PBP layer
+ * back-to-back with itself through a point-wise cell, so the boundary fusion
+ * of Section 4.2.1 applies: the cell reads the gates in block order through
+ * invprow and writes h_t straight into the block-order input of the next
+ * step through invpcol; all x_t are placed once up front.
+ *
+ *   xs_dev   device, [steps][batch][I] of wdtype
+ *   h_dev    device, [batch][H] fp32: h_0 on entry, h_steps on return
+ *   c_dev    device, [batch][H] fp32: c_0 on entry, c_steps on return
+ *   z_dbg    device, optional [batch][4H] fp32: gate pre-activations of the
+ *            last step in natural order (NULL to skip)
+ */
+size_t pivot_lstm_workspace_bytes(const pivot_fc_plan_t* plan, int H, int I, int steps, int batch);
+int    pivot_lstm_run(const pivot_fc_plan_t* plan, int H, int I, const void* xs_dev,
+                      float* h_dev, float* c_dev, float* z_dbg, int steps, int batch,
+                      void* ws_dev, size_t ws_bytes, void* stream);
+
+/*
+ * The dense comparator: y = act(W x + b) with the full M x K matrix streamed
+ * by this library's own dense kernel (the denominator of "speedup vs dense",
+ * Section 5.1).  W_dev [M][K] of wdtype row-major, x_dev [batch][K] of
+ * wdtype, bias_dev [M] fp32 or NULL, y_dev [batch][M] fp32.  batch 1..16.
+ */
+int  pivot_dense_run(const void* W_dev, int wdtype, int M, int K,
+                     const void* x_dev, int64_t ldx, const float* bias_dev,
+                     void* y_dev, int64_t ldy, int batch, int act, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PIVOT_FC_H */

@@ -1,0 +1,444 @@
+// C ABI of the library: argument checks, device upload, and the sequencing of
+// kernel launches for single layers, chains and the recurrent loop.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstring>
+#include <new>
+
+#include "pivot_internal.h"
+
+namespace pivot {
+const char* last_error();
+}
+
+using namespace pivot;
+
+#define API_HIP(expr, cleanup)                                                         \
+    do {                                                                               \
+        hipError_t e_ = (expr);                                                        \
+        if (e_ != hipSuccess) {                                                        \
+            set_error("%s failed: %s", #expr, hipGetErrorString(e_));                  \
+            cleanup;                                                                   \
+            return PIVOT_E_HIP;                                                        \
+        }                                                                              \
+    } while (0)
+
+namespace {
+
+struct DeviceGuard {
+    int prev = -1;
+    bool ok = true;
+    explicit DeviceGuard(int dev) {
+        if (hipGetDevice(&prev) != hipSuccess) { ok = false; return; }
+        if (prev != dev && hipSetDevice(dev) != hipSuccess) ok = false;
+    }
+    ~DeviceGuard() { if (prev >= 0) (void)hipSetDevice(prev); }
+};
+
+struct Piece { const void* src; size_t bytes; void** dst; };
+
+int upload(pivot_fc_plan_t* p) {
+    HostPlan& h = p->host;
+    DevPlan& d = p->dev;
+    Piece pieces[] = {
+        {h.vals.data(),      h.vals.size(),                 (void**)&d.vals},
+        {h.col_idx.data(),   h.col_idx.size() * 4,          (void**)&d.col_idx},
+        {h.chunks.data(),    h.chunks.size() * 4,           (void**)&d.chunks},
+        {h.part_base.data(), h.part_base.size() * 4,        (void**)&d.part_base},
+        {h.bias_p.data(),    h.bias_p.size() * 4,           (void**)&d.bias_p},
+        {h.prow_pad.data(),  h.prow_pad.size() * 4,         (void**)&d.prow_pad},
+        {h.pcol_pad.data(),  h.pcol_pad.size() * 4,         (void**)&d.pcol_pad},
+        {h.invprow.data(),   h.invprow.size() * 4,          (void**)&d.invprow},
+        {h.invpcol.data(),   h.invpcol.size() * 4,          (void**)&d.invpcol},
+    };
+    size_t total = 0;
+    for (auto& pc : pieces) total += align_up(pc.bytes + 16, 256);   // +16: vector loads of the last tile stay inside
+    DeviceGuard g(p->device);
+    if (!g.ok) { set_error("cannot select device %d", p->device); return PIVOT_E_HIP; }
+    void* base = nullptr;
+    hipError_t e = hipMalloc(&base, total);
+    if (e != hipSuccess) { set_error("hipMalloc(%zu) failed: %s", total, hipGetErrorString(e)); return PIVOT_E_ALLOC; }
+    d.base = (char*)base;
+    d.bytes = total;
+    size_t off = 0;
+    for (auto& pc : pieces) {
+        *pc.dst = d.base + off;
+        if (pc.bytes) {
+            e = hipMemcpy(d.base + off, pc.src, pc.bytes, hipMemcpyHostToDevice);
+            if (e != hipSuccess) {
+                set_error("hipMemcpy to device failed: %s", hipGetErrorString(e));
+                (void)hipFree(base);
+                d = DevPlan{};
+                return PIVOT_E_HIP;
+            }
+        }
+        off += align_up(pc.bytes + 16, 256);
+    }
+    return PIVOT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int pivot_version(void) { return PIVOT_VERSION; }
+
+const char* pivot_last_error(void) { return pivot::last_error(); }
+
+int pivot_fc_plan(const pivot_fc_desc* desc, const void* W, int w_space, const uint8_t* tile_mask,
+                  const int32_t* prow, const int32_t* pcol, const float* bias, pivot_fc_plan_t** out) {
+    if (out) *out = nullptr;
+    if (!desc || !out) { set_error("desc and out are required"); return PIVOT_E_NULL; }
+    if (desc->device >= 0) {
+        std::string why;
+        if (!device_supported(*desc, &why)) { set_error("%s", why.c_str()); return PIVOT_E_UNSUPPORTED; }
+    }
+    pivot_fc_plan_t* p = new (std::nothrow) pivot_fc_plan_t();
+    if (!p) { set_error("out of host memory"); return PIVOT_E_ALLOC; }
+    int rc = build_host_plan(*desc, W, w_space, tile_mask, prow, pcol, bias, p->host);
+    if (rc != PIVOT_OK) { delete p; return rc; }
+    p->device = desc->device;
+    if (p->device >= 0) {
+        rc = upload(p);
+        if (rc != PIVOT_OK) { delete p; return rc; }
+    }
+    *out = p;
+    return PIVOT_OK;
+}
+
+int pivot_fc_plan_host_view(const pivot_fc_plan_t* plan, pivot_plan_view* v) {
+    if (!plan || !v) { set_error("plan and view are required"); return PIVOT_E_NULL; }
+    const HostPlan& h = plan->host;
+    v->M = h.d.M; v->K = h.d.K; v->bh = h.d.bh; v->bw = h.d.bw; v->wdtype = h.d.wdtype;
+    v->layout = h.d.layout; v->act = h.d.act;
+    v->nbr = h.nbr; v->nbc = h.nbc; v->M_pad = h.M_pad; v->K_pad = h.K_pad; v->T = h.T;
+    v->chunk_tiles = h.chunk_tiles; v->nchunks = h.nchunks;
+    v->row_ptr = h.row_ptr.data(); v->col_idx = h.col_idx.data(); v->vals = h.vals.data();
+    v->bias_p = h.bias_p.data(); v->invprow = h.invprow.data(); v->invpcol = h.invpcol.data();
+    v->prow_pad = h.prow_pad.data(); v->pcol_pad = h.pcol_pad.data();
+    v->chunks = h.chunks.data(); v->part_base = h.part_base.data();
+    return PIVOT_OK;
+}
+
+int pivot_fc_plan_clone(const pivot_fc_plan_t* plan, pivot_fc_plan_t** out) {
+    if (out) *out = nullptr;
+    if (!plan || !out) { set_error("plan and out are required"); return PIVOT_E_NULL; }
+    pivot_fc_plan_t* p = new (std::nothrow) pivot_fc_plan_t();
+    if (!p) { set_error("out of host memory"); return PIVOT_E_ALLOC; }
+    try {
+        p->host = plan->host;
+    } catch (const std::bad_alloc&) {
+        delete p;
+        set_error("out of host memory");
+        return PIVOT_E_ALLOC;
+    }
+    p->device = plan->device;
+    if (p->device >= 0) {
+        int rc = upload(p);
+        if (rc != PIVOT_OK) { delete p; return rc; }
+    }
+    *out = p;
+    return PIVOT_OK;
+}
+
+void pivot_fc_plan_destroy(pivot_fc_plan_t* plan) {
+    if (!plan) return;
+    if (plan->dev.base) {
+        DeviceGuard g(plan->device);
+        (void)hipFree(plan->dev.base);
+    }
+    delete plan;
+}
+
+size_t pivot_fc_workspace_bytes(const pivot_fc_plan_t* plan, int batch) {
+    if (!plan || batch < 1) return 0;
+    return fc_workspace_bytes(plan->host, batch);
+}
+
+int pivot_workspace_init(void* ws_dev, size_t ws_bytes, void* stream) {
+    if (!ws_dev && ws_bytes) { set_error("workspace pointer is NULL"); return PIVOT_E_NULL; }
+    return launch_fill_zero(ws_dev, ws_bytes, stream);
+}
+
+}  // extern "C"
+
+namespace {
+
+// Fills the plan-dependent part of a launch and carves the workspace.
+int prepare(const pivot_fc_plan_t* plan, int batch, void* ws, size_t ws_bytes, FcLaunch& L) {
+    if (!plan) { set_error("plan is NULL"); return PIVOT_E_NULL; }
+    if (plan->device < 0) { set_error("host-only plan (device = -1) cannot run"); return PIVOT_E_NO_DEVICE; }
+    if (batch < 1 || batch > 64) { set_error("batch %d outside 1..64", batch); return PIVOT_E_SHAPE; }
+    const HostPlan& h = plan->host;
+    size_t need = fc_workspace_bytes(h, batch);
+    if (need > 0 && (!ws || ws_bytes < need)) { set_error("workspace too small: need %zu bytes, got %zu", need, ws ? ws_bytes : (size_t)0); return PIVOT_E_WORKSPACE; }
+    if (reinterpret_cast<uintptr_t>(ws) % 16 != 0) { set_error("workspace must be 16-byte aligned"); return PIVOT_E_WORKSPACE; }
+    const DevPlan& d = plan->dev;
+    L.vals = d.vals; L.col_idx = d.col_idx; L.chunks = d.chunks; L.part_base = d.part_base; L.bias_p = d.bias_p;
+    L.M_pad = h.M_pad; L.K_pad = h.K_pad; L.bh = h.d.bh; L.bw = h.d.bw; L.wdtype = h.d.wdtype; L.act = h.d.act;
+    L.nchunks = h.nchunks; L.nbr = h.nbr; L.chunk_tiles = h.chunk_tiles;
+    L.batch = batch;
+    int nbt = fc_batch_tile(h.d.wdtype, h.d.bh, h.d.bw, batch);
+    int ngy = (batch + nbt - 1) / nbt;
+    L.tickets = reinterpret_cast<uint32_t*>(ws);
+    L.partials = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + align_up((size_t)4 * h.nbr * ngy, 256));
+    return PIVOT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int pivot_fc_run(const pivot_fc_plan_t* plan, const void* x_dev, int64_t ldx, void* y_dev, int64_t ldy,
+                 int batch, void* ws_dev, size_t ws_bytes, void* stream) {
+    FcLaunch L{};
+    int rc = prepare(plan, batch, ws_dev, ws_bytes, L);
+    if (rc != PIVOT_OK) return rc;
+    if (!x_dev || !y_dev) { set_error("x_dev and y_dev are required"); return PIVOT_E_NULL; }
+    if (ldx < plan->host.d.K || ldy < plan->host.d.M) { set_error("ldx/ldy smaller than K/M"); return PIVOT_E_SHAPE; }
+    L.gather = plan->dev.pcol_pad;
+    L.scatter = plan->dev.prow_pad;
+    L.out_rows = plan->host.d.M;
+    L.x = x_dev; L.ldx = ldx; L.y = y_dev; L.ldy = ldy; L.out_f16 = 0; L.stream = stream;
+    return launch_fc(L);
+}
+
+// ------------------------------------------------------------------ chains
+
+int pivot_mlp_plan(pivot_fc_plan_t* const* layers, int Lcount, int flags, pivot_mlp_plan_t** out) {
+    if (out) *out = nullptr;
+    if (!layers || !out) { set_error("layers and out are required"); return PIVOT_E_NULL; }
+    if (Lcount < 1) { set_error("a chain needs at least one layer"); return PIVOT_E_SHAPE; }
+    if (flags & ~PIVOT_MLP_KEEP_FINAL_BLOCK_ORDER) { set_error("unknown flags"); return PIVOT_E_UNSUPPORTED; }
+    for (int l = 0; l < Lcount; ++l) {
+        if (!layers[l]) { set_error("layer %d is NULL", l); return PIVOT_E_NULL; }
+        if (layers[l]->host.d.wdtype != layers[0]->host.d.wdtype || layers[l]->device != layers[0]->device) {
+            set_error("all layers of a chain must share wdtype and device");
+            return PIVOT_E_UNSUPPORTED;
+        }
+        if (l > 0 && layers[l]->host.d.K != layers[l - 1]->host.d.M) {
+            set_error("layer %d takes %d inputs but layer %d produces %d", l, layers[l]->host.d.K, l - 1, layers[l - 1]->host.d.M);
+            return PIVOT_E_SHAPE;
+        }
+    }
+    pivot_mlp_plan_t* mp = new (std::nothrow) pivot_mlp_plan_t();
+    if (!mp) { set_error("out of host memory"); return PIVOT_E_ALLOC; }
+    try {
+        mp->layers.assign(layers, layers + Lcount);
+        mp->flags = flags;
+        mp->device = layers[0]->device;
+        for (int l = 0; l + 1 < Lcount; ++l) {
+            const HostPlan& a = layers[l]->host;
+            const HostPlan& b = layers[l + 1]->host;
+            std::vector<int32_t> q(b.d.K), dst(a.M_pad, -1);
+            bool ident = true;
+            for (int c = 0; c < b.d.K; ++c) {            // q[c] = invprow_l[pcol_{l+1}[c]]
+                q[c] = a.invprow[b.pcol_pad[c]];
+                ident = ident && (q[c] == c);
+            }
+            for (int r = 0; r < a.d.M; ++r) dst[r] = b.invpcol[a.prow_pad[r]];
+            mp->q.push_back(std::move(q));
+            mp->dst.push_back(std::move(dst));
+            mp->identity.push_back(ident ? 1 : 0);
+        }
+        for (auto& v : mp->q) mp->q_ptrs.push_back(v.data());
+        for (auto& v : mp->dst) mp->dst_ptrs.push_back(v.data());
+    } catch (const std::bad_alloc&) {
+        delete mp;
+        set_error("out of host memory");
+        return PIVOT_E_ALLOC;
+    }
+    if (mp->device >= 0 && Lcount > 1) {
+        size_t total = 0;
+        for (auto& v : mp->dst) total += align_up(v.size() * 4, 256);
+        DeviceGuard g(mp->device);
+        void* base = nullptr;
+        hipError_t e = hipMalloc(&base, total);
+        if (e != hipSuccess) { set_error("hipMalloc(%zu) failed: %s", total, hipGetErrorString(e)); delete mp; return PIVOT_E_ALLOC; }
+        mp->dev_base = (char*)base;
+        size_t off = 0;
+        for (auto& v : mp->dst) {
+            e = hipMemcpy(mp->dev_base + off, v.data(), v.size() * 4, hipMemcpyHostToDevice);
+            if (e != hipSuccess) { set_error("hipMemcpy failed: %s", hipGetErrorString(e)); (void)hipFree(base); delete mp; return PIVOT_E_HIP; }
+            mp->dst_dev.push_back(reinterpret_cast<int32_t*>(mp->dev_base + off));
+            off += align_up(v.size() * 4, 256);
+        }
+    }
+    *out = mp;
+    return PIVOT_OK;
+}
+
+int pivot_mlp_plan_host_view(const pivot_mlp_plan_t* plan, pivot_mlp_view* v) {
+    if (!plan || !v) { set_error("plan and view are required"); return PIVOT_E_NULL; }
+    v->L = (int32_t)plan->layers.size();
+    v->flags = plan->flags;
+    v->q = plan->q_ptrs.data();
+    v->dst = plan->dst_ptrs.data();
+    v->identity = plan->identity.data();
+    return PIVOT_OK;
+}
+
+void pivot_mlp_plan_destroy(pivot_mlp_plan_t* plan) {
+    if (!plan) return;
+    if (plan->dev_base) {
+        DeviceGuard g(plan->device);
+        (void)hipFree(plan->dev_base);
+    }
+    delete plan;
+}
+
+}  // extern "C"
+
+namespace {
+
+// Workspace of a chain: [layer scratch (largest)] [intermediate 0] [intermediate 1] ...
+// Intermediate l holds batch rows of K_pad_{l+1} elements of wdtype in the
+// consumer's block order; its padding columns stay zero from pivot_workspace_init.
+struct MlpLayout { size_t scratch, total; std::vector<size_t> inter_off; };
+
+MlpLayout mlp_layout(const pivot_mlp_plan_t* mp, int batch) {
+    MlpLayout m{0, 0, {}};
+    for (auto* l : mp->layers) m.scratch = std::max(m.scratch, fc_workspace_bytes(l->host, batch));
+    m.scratch = align_up(m.scratch, 256);
+    size_t off = m.scratch;
+    for (size_t l = 0; l + 1 < mp->layers.size(); ++l) {
+        m.inter_off.push_back(off);
+        off += align_up((size_t)batch * mp->layers[l + 1]->host.K_pad * elem_size(mp->layers[l + 1]->host.d.wdtype), 256);
+    }
+    m.total = off;
+    return m;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t pivot_mlp_workspace_bytes(const pivot_mlp_plan_t* plan, int batch) {
+    if (!plan || batch < 1) return 0;
+    return mlp_layout(plan, batch).total;
+}
+
+int pivot_mlp_run(const pivot_mlp_plan_t* plan, const void* x_dev, int64_t ldx, void* y_dev, int64_t ldy,
+                  int batch, void* ws_dev, size_t ws_bytes, void* stream) {
+    if (!plan) { set_error("plan is NULL"); return PIVOT_E_NULL; }
+    if (!x_dev || !y_dev) { set_error("x_dev and y_dev are required"); return PIVOT_E_NULL; }
+    if (plan->device < 0) { set_error("host-only chain cannot run"); return PIVOT_E_NO_DEVICE; }
+    if (batch < 1 || batch > 64) { set_error("batch %d outside 1..64", batch); return PIVOT_E_SHAPE; }
+    MlpLayout m = mlp_layout(plan, batch);
+    if (!ws_dev || ws_bytes < m.total) { set_error("workspace too small: need %zu bytes", m.total); return PIVOT_E_WORKSPACE; }
+    const int Lc = (int)plan->layers.size();
+    const bool keep = (plan->flags & PIVOT_MLP_KEEP_FINAL_BLOCK_ORDER) != 0;
+    const pivot_fc_plan_t* last = plan->layers[Lc - 1];
+    if (ldx < plan->layers[0]->host.d.K || ldy < (keep ? last->host.M_pad : last->host.d.M)) { set_error("ldx/ldy too small"); return PIVOT_E_SHAPE; }
+    char* ws = reinterpret_cast<char*>(ws_dev);
+    for (int l = 0; l < Lc; ++l) {
+        const pivot_fc_plan_t* p = plan->layers[l];
+        FcLaunch L{};
+        int rc = prepare(p, batch, ws, m.scratch, L);
+        if (rc != PIVOT_OK) return rc;
+        L.stream = stream;
+        if (l == 0) { L.gather = p->dev.pcol_pad; L.x = x_dev; L.ldx = ldx; }
+        else        { L.gather = nullptr; L.x = ws + m.inter_off[l - 1]; L.ldx = p->host.K_pad; }
+        if (l + 1 < Lc) {
+            // producer-side store through the composed boundary array; identity boundaries store contiguously
+            L.scatter = plan->identity[l] ? nullptr : plan->dst_dev[l];
+            L.out_rows = p->host.d.M;
+            L.y = ws + m.inter_off[l];
+            L.ldy = plan->layers[l + 1]->host.K_pad;
+            L.out_f16 = (p->host.d.wdtype == PIVOT_F16);
+        } else {
+            L.scatter = keep ? nullptr : p->dev.prow_pad;
+            L.out_rows = keep ? p->host.M_pad : p->host.d.M;
+            L.y = y_dev; L.ldy = ldy; L.out_f16 = 0;
+        }
+        rc = launch_fc(L);
+        if (rc != PIVOT_OK) return rc;
+    }
+    return PIVOT_OK;
+}
+
+// --------------------------------------------------------------- recurrence
+
+}  // extern "C"
+
+namespace {
+
+struct LstmLayout { size_t scratch, z_off, xg_off, xg_step, total; };
+
+LstmLayout lstm_layout(const pivot_fc_plan_t* p, int steps, int batch) {
+    LstmLayout m{};
+    m.scratch = align_up(fc_workspace_bytes(p->host, batch), 256);
+    m.z_off = m.scratch;
+    m.xg_off = m.z_off + align_up((size_t)batch * p->host.M_pad * 4, 256);
+    m.xg_step = align_up((size_t)batch * p->host.K_pad * elem_size(p->host.d.wdtype), 256);
+    m.total = m.xg_off + m.xg_step * (size_t)(steps > 0 ? steps : 1);
+    return m;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t pivot_lstm_workspace_bytes(const pivot_fc_plan_t* plan, int H, int I, int steps, int batch) {
+    if (!plan || batch < 1 || steps < 0) return 0;
+    (void)H; (void)I;
+    return lstm_layout(plan, steps, batch).total;
+}
+
+int pivot_lstm_run(const pivot_fc_plan_t* plan, int H, int I, const void* xs_dev, float* h_dev, float* c_dev,
+                   float* z_dbg, int steps, int batch, void* ws_dev, size_t ws_bytes, void* stream) {
+    if (!plan) { set_error("plan is NULL"); return PIVOT_E_NULL; }
+    if (!xs_dev || !h_dev || !c_dev) { set_error("xs_dev, h_dev and c_dev are required"); return PIVOT_E_NULL; }
+    if (plan->device < 0) { set_error("host-only plan cannot run"); return PIVOT_E_NO_DEVICE; }
+    const HostPlan& h = plan->host;
+    if (H < 1 || I < 0 || h.d.M != 4 * H || h.d.K != H + I) { set_error("plan is %dx%d, expected 4H x (H+I) with H=%d I=%d", h.d.M, h.d.K, H, I); return PIVOT_E_SHAPE; }
+    if (steps < 0 || batch < 1 || batch > 64) { set_error("bad steps/batch"); return PIVOT_E_SHAPE; }
+    if (steps == 0) return PIVOT_OK;
+    LstmLayout m = lstm_layout(plan, steps, batch);
+    if (!ws_dev || ws_bytes < m.total) { set_error("workspace too small: need %zu bytes", m.total); return PIVOT_E_WORKSPACE; }
+    char* ws = reinterpret_cast<char*>(ws_dev);
+    float* z = reinterpret_cast<float*>(ws + m.z_off);
+    char* xg = ws + m.xg_off;
+    int rc;
+    // block-order inputs of all steps: padding zero, x_t placed once, h_0 placed into step 0
+    if ((rc = launch_fill_zero(xg, m.xg_step * (size_t)steps, stream)) != PIVOT_OK) return rc;
+    if (m.xg_step != (size_t)batch * h.K_pad * elem_size(h.d.wdtype)) {
+        // steps are padded apart: place step by step
+        for (int t = 0; t < steps; ++t) {
+            const char* xs_t = reinterpret_cast<const char*>(xs_dev) + (size_t)t * batch * I * elem_size(h.d.wdtype);
+            if ((rc = launch_lstm_place_inputs(xs_t, xg + m.xg_step * (size_t)t, plan->dev.invpcol, H, I, h.K_pad, 1, batch, h.d.wdtype, stream)) != PIVOT_OK) return rc;
+        }
+    } else {
+        if ((rc = launch_lstm_place_inputs(xs_dev, xg, plan->dev.invpcol, H, I, h.K_pad, steps, batch, h.d.wdtype, stream)) != PIVOT_OK) return rc;
+    }
+    if ((rc = launch_lstm_place_state(h_dev, xg, plan->dev.invpcol, H, h.K_pad, batch, h.d.wdtype, stream)) != PIVOT_OK) return rc;
+    for (int t = 0; t < steps; ++t) {
+        FcLaunch L{};
+        rc = prepare(plan, batch, ws, m.scratch, L);
+        if (rc != PIVOT_OK) return rc;
+        L.gather = nullptr;
+        L.x = xg + m.xg_step * (size_t)t; L.ldx = h.K_pad;
+        L.scatter = nullptr; L.out_rows = h.M_pad;
+        L.y = z; L.ldy = h.M_pad; L.out_f16 = 0; L.stream = stream;
+        if ((rc = launch_fc(L)) != PIVOT_OK) return rc;
+        LstmCellLaunch C{};
+        C.z = z; C.invprow = plan->dev.invprow; C.invpcol = plan->dev.invpcol;
+        C.h = h_dev; C.c = c_dev;
+        C.xg_next = (t + 1 < steps) ? (void*)(xg + m.xg_step * (size_t)(t + 1)) : nullptr;
+        C.z_dbg = (t + 1 == steps) ? z_dbg : nullptr;
+        C.H = H; C.M_pad = h.M_pad; C.K_pad = h.K_pad; C.batch = batch; C.wdtype = h.d.wdtype; C.stream = stream;
+        if ((rc = launch_lstm_cell(C)) != PIVOT_OK) return rc;
+    }
+    return PIVOT_OK;
+}
+
+int pivot_dense_run(const void* W_dev, int wdtype, int M, int K, const void* x_dev, int64_t ldx,
+                    const float* bias_dev, void* y_dev, int64_t ldy, int batch, int act, void* stream) {
+    if (!W_dev || !x_dev || !y_dev) { set_error("W_dev, x_dev and y_dev are required"); return PIVOT_E_NULL; }
+    if (M < 1 || K < 1 || ldx < K || ldy < M) { set_error("bad shape"); return PIVOT_E_SHAPE; }
+    if (wdtype != PIVOT_F32 && wdtype != PIVOT_F16) { set_error("unknown wdtype"); return PIVOT_E_UNSUPPORTED; }
+    return launch_dense(W_dev, wdtype, M, K, x_dev, ldx, bias_dev, y_dev, ldy, batch, act, stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,126 @@
+// Internal declarations shared by the host plan builder, the C ABI glue and
+// the kernel launchers.  Not part of the public interface.
+#pragma once
+
+#include <cstddef>
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "pivot_fc.h"
+
+namespace pivot {
+
+void set_error(const char* fmt, ...);
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline int    elem_size(int wdtype) { return wdtype == PIVOT_F32 ? 4 : 2; }
+
+// Host-side canonical arrays of one layer (what pivot_plan_view exposes).
+struct HostPlan {
+    pivot_fc_desc d{};
+    int nbr = 0, nbc = 0, M_pad = 0, K_pad = 0, T = 0, chunk_tiles = 0, nchunks = 0;
+    int max_parts = 1;                 // largest number of pieces of one block row
+    std::vector<int32_t> row_ptr, col_idx, invprow, invpcol, prow_pad, pcol_pad;
+    std::vector<int32_t> chunks;       // nchunks x 4
+    std::vector<int32_t> part_base;    // nbr + 1
+    std::vector<float>   bias_p;
+    std::vector<uint8_t> vals;         // T*bh*bw elements of wdtype
+};
+
+// Device copies (one allocation, sub-arrays 256-byte aligned).
+struct DevPlan {
+    char*   base = nullptr;
+    size_t  bytes = 0;
+    void*    vals = nullptr;
+    int32_t* col_idx = nullptr;
+    int32_t* chunks = nullptr;
+    int32_t* part_base = nullptr;
+    float*   bias_p = nullptr;
+    int32_t* prow_pad = nullptr;
+    int32_t* pcol_pad = nullptr;
+    int32_t* invprow = nullptr;
+    int32_t* invpcol = nullptr;
+};
+
+// Builds every host array.  Returns PIVOT_OK or an error code (error text set).
+int build_host_plan(const pivot_fc_desc& d, const void* W, int w_space, const uint8_t* tile_mask,
+                    const int32_t* prow, const int32_t* pcol, const float* bias, HostPlan& hp);
+
+// Cuts the schedule for a given chunk size (also used when the library picks it).
+void build_schedule(HostPlan& hp, int chunk_tiles);
+
+// True if the device kernels can run this plan.
+bool device_supported(const pivot_fc_desc& d, std::string* why);
+// Largest chunk (in tiles) whose staged input fits in LDS at the largest batch tile.
+int  max_chunk_tiles(const pivot_fc_desc& d);
+// The library's own choice of chunk size.
+int  choose_chunk_tiles(const HostPlan& hp);
+
+// ---- what a kernel launch sees -------------------------------------------
+struct FcLaunch {
+    // plan
+    const void*    vals;
+    const int32_t* col_idx;
+    const int32_t* chunks;      // int4 per chunk
+    const int32_t* part_base;
+    const float*   bias_p;
+    const int32_t* gather;      // block-space column -> index into x (-1 = padding); NULL = x already in block order
+    const int32_t* scatter;     // block-space row -> index into y (-1 = skip); NULL = store in block order (rows < out_rows)
+    int M_pad, K_pad, bh, bw, wdtype, act, nchunks, nbr, chunk_tiles;
+    int out_rows;               // rows stored when scatter == NULL
+    // data
+    const void* x; int64_t ldx;
+    void*       y; int64_t ldy;
+    int out_f16;                // 1: y is fp16 (chain intermediates of F16 plans), 0: fp32
+    int batch;
+    float*    partials;
+    uint32_t* tickets;
+    void*     stream;
+};
+
+// Batch rows one launch of the layer kernel covers (grid.y repeats it).
+int    fc_batch_tile(int wdtype, int bh, int bw, int batch);
+size_t fc_workspace_bytes(const HostPlan& hp, int batch);
+int    launch_fc(const FcLaunch& L);
+int    launch_fill_zero(void* dev, size_t bytes, void* stream);
+int    launch_dense(const void* W, int wdtype, int M, int K, const void* x, int64_t ldx,
+                    const float* bias, void* y, int64_t ldy, int batch, int act, void* stream);
+
+struct LstmCellLaunch {
+    const float* z;             // [batch][M_pad] gate pre-activations in block order (bias included)
+    const int32_t* invprow;     // natural gate row -> block-space row
+    const int32_t* invpcol;     // natural input column -> block-space column
+    float* h; float* c;         // [batch][H]
+    void* xg_next;              // [batch][K_pad] of wdtype: next step's block-order input, or NULL
+    float* z_dbg;               // optional [batch][4H] natural order
+    int H, M_pad, K_pad, batch, wdtype;
+    void* stream;
+};
+int launch_lstm_cell(const LstmCellLaunch& L);
+// Places x_t (natural columns H..H+I-1) of every step into its block-order input buffer.
+int launch_lstm_place_inputs(const void* xs, void* xg_all, const int32_t* invpcol, int H, int I,
+                             int K_pad, int steps, int batch, int wdtype, void* stream);
+// Places h (fp32, natural) into one block-order input buffer.
+int launch_lstm_place_state(const float* h, void* xg, const int32_t* invpcol, int H, int K_pad,
+                            int batch, int wdtype, void* stream);
+
+}  // namespace pivot
+
+struct pivot_fc_plan {
+    pivot::HostPlan host;
+    pivot::DevPlan  dev;
+    int device = -1;
+};
+
+struct pivot_mlp_plan {
+    std::vector<pivot_fc_plan_t*> layers;
+    int flags = 0;
+    std::vector<std::vector<int32_t>> q, dst;
+    std::vector<const int32_t*> q_ptrs, dst_ptrs;
+    std::vector<int32_t> identity;
+    // device: dst arrays (one allocation)
+    char* dev_base = nullptr;
+    std::vector<int32_t*> dst_dev;
+    int device = -1;
+};

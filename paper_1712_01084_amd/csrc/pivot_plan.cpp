@@ -1,0 +1,189 @@
+// Host-side plan builder: the static "compile" step of the PBP form (paper
+// Eq. 1 and Section 4.2.1).  Pure CPU code, integer work and bit copies only.
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <numeric>
+
+#include "pivot_internal.h"
+
+namespace pivot {
+
+static thread_local char g_error[512] = "";
+
+void set_error(const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_error, sizeof(g_error), fmt, ap);
+    va_end(ap);
+}
+
+const char* last_error() { return g_error; }
+
+static bool is_pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
+
+bool device_supported(const pivot_fc_desc& d, std::string* why) {
+    auto fail = [&](const char* m) { if (why) *why = m; return false; };
+    if (d.layout != PIVOT_BRC) return fail("the device kernels read the BRC layout only");
+    if (!is_pow2(d.bh) || !is_pow2(d.bw)) return fail("tile sides must be powers of two on the device path");
+    if (d.bh < 8 || d.bh > 64 || d.bw < 8 || d.bw > 64) return fail("tile sides must lie in 8..64 on the device path");
+    return true;
+}
+
+// Batch rows the widest kernel of this plan stages per launch.
+static int widest_batch_tile(const pivot_fc_desc& d) {
+    if (d.wdtype == PIVOT_F32) return 4;
+    if (d.bw % 32 == 0 && d.bh % 16 == 0) return 16;
+    if (d.bh % 32 == 0 && d.bw % 16 == 0) return 32;
+    return 4;
+}
+
+int max_chunk_tiles(const pivot_fc_desc& d) {
+    const int lds_budget = 32 * 1024;
+    int per_tile = d.bw * widest_batch_tile(d) * elem_size(d.wdtype);
+    return std::max(1, lds_budget / std::max(1, per_tile));
+}
+
+int choose_chunk_tiles(const HostPlan& hp) {
+    // About three work items per compute unit, but none smaller than 4 KB of
+    // tile values, and never more than LDS can stage.
+    const int target_items = 256 * 3;
+    int tile_bytes = hp.d.bh * hp.d.bw * elem_size(hp.d.wdtype);
+    int ct = (hp.T + target_items - 1) / target_items;
+    ct = std::max(ct, (4096 + tile_bytes - 1) / tile_bytes);
+    ct = std::max(ct, 1);
+    return std::min(ct, max_chunk_tiles(hp.d));
+}
+
+void build_schedule(HostPlan& hp, int chunk_tiles) {
+    hp.chunk_tiles = chunk_tiles;
+    struct C { int32_t br, b, e, slot; };
+    std::vector<C> cs;
+    hp.part_base.assign(hp.nbr + 1, 0);
+    hp.max_parts = 1;
+    for (int i = 0; i < hp.nbr; ++i) {
+        int b = hp.row_ptr[i], e = hp.row_ptr[i + 1];
+        int first = (int)cs.size();
+        if (b == e) cs.push_back({i, b, e, (int32_t)cs.size()});
+        for (int s = b; s < e; s += chunk_tiles) {
+            int n = std::min(chunk_tiles, e - s);
+            cs.push_back({i, s, s + n, (int32_t)cs.size()});
+        }
+        hp.part_base[i + 1] = (int32_t)cs.size();
+        hp.max_parts = std::max(hp.max_parts, (int)cs.size() - first);
+    }
+    std::stable_sort(cs.begin(), cs.end(), [](const C& a, const C& b) { return (a.e - a.b) > (b.e - b.b); });
+    hp.nchunks = (int)cs.size();
+    hp.chunks.resize((size_t)hp.nchunks * 4);
+    for (int j = 0; j < hp.nchunks; ++j) {
+        hp.chunks[4 * j + 0] = cs[j].br;
+        hp.chunks[4 * j + 1] = cs[j].b;
+        hp.chunks[4 * j + 2] = cs[j].e;
+        hp.chunks[4 * j + 3] = cs[j].slot;
+    }
+}
+
+static int check_permutation(const int32_t* p, int n, const char* name, std::vector<int32_t>& inv) {
+    inv.assign(n, -1);
+    for (int i = 0; i < n; ++i) {
+        int32_t v = p[i];
+        if (v < 0 || v >= n) {
+            set_error("%s[%d] = %d is outside 0..%d", name, i, v, n - 1);
+            return PIVOT_E_NOT_PERMUTATION;
+        }
+        if (inv[v] != -1) {
+            set_error("%s is not a bijection: value %d appears at %d and %d", name, v, inv[v], i);
+            return PIVOT_E_NOT_PERMUTATION;
+        }
+        inv[v] = i;
+    }
+    return PIVOT_OK;
+}
+
+template <typename E>
+static void pack_tiles(const HostPlan& hp, const E* W, int w_space, const int32_t* prow, const int32_t* pcol, E* out) {
+    const int M = hp.d.M, K = hp.d.K, bh = hp.d.bh, bw = hp.d.bw, layout = hp.d.layout;
+    const size_t T = (size_t)hp.T;
+    for (int i = 0; i < hp.nbr; ++i) {
+        for (int t = hp.row_ptr[i]; t < hp.row_ptr[i + 1]; ++t) {
+            const int j = hp.col_idx[t];
+            for (int r = 0; r < bh; ++r) {
+                const int R = i * bh + r;
+                const E* src_row = nullptr;
+                if (R < M) src_row = W + (size_t)(w_space == PIVOT_W_PIVOTED ? R : prow[R]) * K;
+                for (int c = 0; c < bw; ++c) {
+                    const int C = j * bw + c;
+                    E v = E(0);
+                    if (src_row && C < K) v = src_row[w_space == PIVOT_W_PIVOTED ? C : pcol[C]];
+                    size_t off;
+                    if (layout == PIVOT_BRC)      off = ((size_t)t * bh + r) * bw + c;
+                    else if (layout == PIVOT_BCR) off = ((size_t)t * bw + c) * bh + r;
+                    else                          off = ((size_t)c * T + t) * bh + r;
+                    out[off] = v;
+                }
+            }
+        }
+    }
+}
+
+int build_host_plan(const pivot_fc_desc& d, const void* W, int w_space, const uint8_t* tile_mask,
+                    const int32_t* prow, const int32_t* pcol, const float* bias, HostPlan& hp) {
+    if (!W || !tile_mask || !prow || !pcol) { set_error("W, tile_mask, prow and pcol are required"); return PIVOT_E_NULL; }
+    if (d.M <= 0 || d.K <= 0 || d.bh <= 0 || d.bw <= 0) { set_error("M, K, bh, bw must be positive"); return PIVOT_E_SHAPE; }
+    if ((int64_t)d.M * d.K > (int64_t)1 << 40) { set_error("matrix too large"); return PIVOT_E_SHAPE; }
+    if (d.wdtype != PIVOT_F32 && d.wdtype != PIVOT_F16) { set_error("unknown wdtype %d", d.wdtype); return PIVOT_E_UNSUPPORTED; }
+    if (d.layout != PIVOT_BRC && d.layout != PIVOT_BCR && d.layout != PIVOT_CBR) { set_error("unknown layout %d", d.layout); return PIVOT_E_UNSUPPORTED; }
+    if (d.act != PIVOT_ACT_NONE && d.act != PIVOT_ACT_RELU) { set_error("unknown activation %d", d.act); return PIVOT_E_UNSUPPORTED; }
+    if (w_space != PIVOT_W_NATURAL && w_space != PIVOT_W_PIVOTED) { set_error("unknown weight space %d", w_space); return PIVOT_E_UNSUPPORTED; }
+    if (d.chunk_tiles < 0) { set_error("chunk_tiles must be >= 0"); return PIVOT_E_SHAPE; }
+    if (d.flags != 0) { set_error("flags must be 0"); return PIVOT_E_UNSUPPORTED; }
+
+    hp.d = d;
+    hp.nbr = (d.M + d.bh - 1) / d.bh;
+    hp.nbc = (d.K + d.bw - 1) / d.bw;
+    hp.M_pad = hp.nbr * d.bh;
+    hp.K_pad = hp.nbc * d.bw;
+
+    int rc = check_permutation(prow, d.M, "prow", hp.invprow);
+    if (rc) return rc;
+    rc = check_permutation(pcol, d.K, "pcol", hp.invpcol);
+    if (rc) return rc;
+
+    try {
+        hp.row_ptr.assign(hp.nbr + 1, 0);
+        hp.col_idx.clear();
+        for (int i = 0; i < hp.nbr; ++i) {
+            for (int j = 0; j < hp.nbc; ++j)
+                if (tile_mask[(size_t)i * hp.nbc + j]) hp.col_idx.push_back(j);
+            if (hp.col_idx.size() > (size_t)INT32_MAX) { set_error("too many tiles"); return PIVOT_E_SHAPE; }
+            hp.row_ptr[i + 1] = (int32_t)hp.col_idx.size();
+        }
+        hp.T = (int)hp.col_idx.size();
+        size_t nvals = (size_t)hp.T * d.bh * d.bw;
+        if (nvals * elem_size(d.wdtype) > ((size_t)1 << 36)) { set_error("kept tiles exceed 64 GiB"); return PIVOT_E_SHAPE; }
+        hp.vals.assign(nvals * elem_size(d.wdtype), 0);
+        if (d.wdtype == PIVOT_F32)
+            pack_tiles<uint32_t>(hp, (const uint32_t*)W, w_space, prow, pcol, (uint32_t*)hp.vals.data());
+        else
+            pack_tiles<uint16_t>(hp, (const uint16_t*)W, w_space, prow, pcol, (uint16_t*)hp.vals.data());
+
+        hp.bias_p.assign(hp.M_pad, 0.0f);
+        if (bias) for (int r = 0; r < d.M; ++r) hp.bias_p[r] = bias[prow[r]];
+        hp.prow_pad.assign(hp.M_pad, -1);
+        std::copy(prow, prow + d.M, hp.prow_pad.begin());
+        hp.pcol_pad.assign(hp.K_pad, -1);
+        std::copy(pcol, pcol + d.K, hp.pcol_pad.begin());
+
+        int ct = d.chunk_tiles;
+        if (ct == 0) ct = choose_chunk_tiles(hp);
+        if (d.device >= 0) ct = std::min(ct, max_chunk_tiles(d));
+        build_schedule(hp, ct);
+    } catch (const std::bad_alloc&) {
+        set_error("out of host memory while building the plan");
+        return PIVOT_E_ALLOC;
+    }
+    return PIVOT_OK;
+}
+
+}  // namespace pivot
