@@ -82,6 +82,7 @@ typedef struct pivot_fc_desc {
     int32_t act;          /* PIVOT_ACT_*                                                 */
     int32_t chunk_tiles;  /* max tiles per work item; 0 = the library chooses            */
     int32_t device;       /* HIP device ordinal, or -1 for a host-only plan (no GPU use) */
+    int32_t wg_waves;     /* wavefronts per work item: 4, 8 or 16; 0 = the library chooses */
     int32_t flags;        /* reserved, must be 0                                         */
 } pivot_fc_desc;
 
@@ -103,6 +104,7 @@ typedef struct pivot_plan_view {
     int32_t nbr, nbc, M_pad, K_pad;
     int32_t T;                 /* kept tiles */
     int32_t chunk_tiles;       /* resolved value */
+    int32_t wg_waves;          /* resolved value */
     int32_t nchunks;
     const int32_t* row_ptr;    /* [nbr+1] */
     const int32_t* col_idx;    /* [T]     */
@@ -114,6 +116,8 @@ typedef struct pivot_plan_view {
     const int32_t* pcol_pad;   /* [K_pad]  pcol, -1 in padding */
     const int32_t* chunks;     /* [nchunks][4] */
     const int32_t* part_base;  /* [nbr+1] */
+    const int32_t* xidx;       /* [T*bw]   xidx[t*bw+c] = pcol_pad[col_idx[t]*bw+c]: the column gather
+                                  composed with the tile list, what the device reads */
 } pivot_plan_view;
 
 int         pivot_version(void);
@@ -230,6 +234,11 @@ int    pivot_lstm_run(const pivot_fc_plan_t* plan, int H, int I, const void* xs_
 int  pivot_dense_run(const void* W_dev, int wdtype, int M, int K,
                      const void* x_dev, int64_t ldx, const float* bias_dev,
                      void* y_dev, int64_t ldy, int batch, int act, void* stream);
+
+/* Measurement aid: enqueues one empty kernel (a single wavefront that does
+ * nothing), so that a harness can report the launch floor of the device next
+ * to the layer times (the paper averages whole calls, Section 5.1). */
+int  pivot_null_run(void* stream);
 
 #ifdef __cplusplus
 }

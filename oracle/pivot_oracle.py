@@ -186,17 +186,23 @@ def oracle_mlp(layers, x, boundary_dtype=None, return_all=False):
     is given the activation handed to the next layer is rounded to it once
     (the point where the HIP path stores a half-precision intermediate)."""
     h = np.asarray(x)
-    outs, scales = [], []
+    outs, scales, chain = [], [], []
+    S = None
     for li, L in enumerate(layers):
         Wd = dense_masked_natural(L["Wp"], L["tile_mask"], L["prow"], L["pcol"], L["bh"], L["bw"])
         y = fc_dense(Wd, h, L["bias"], L["act"])
+        D = error_scale(Wd, h, L["bias"])
+        # first-order bound on how an error of relative size eps in every layer
+        # reaches this layer's output: eps * S with S_1 = D_1, S_l = |W_l| S_{l-1} + D_l
+        S = D if S is None else S @ np.abs(Wd).T + D
         outs.append(y)
-        scales.append(error_scale(Wd, h, L["bias"]))
+        scales.append(D)
+        chain.append(S)
         h = y
         if boundary_dtype is not None and li + 1 < len(layers):
             h = y.astype(boundary_dtype)
     if return_all:
-        return outs, scales
+        return outs, scales, chain
     return outs[-1]
 
 
@@ -336,8 +342,10 @@ def oracle_plan(W, w_space_pivoted, tile_mask, prow, pcol, bias, M, K, bh, bw,
     prow_pad[:M] = prow
     pcol_pad = np.full(Kp, -1, dtype=np.int32)
     pcol_pad[:K] = pcol
+    # the column gather composed with the tile list: index into x of column c of tile t
+    xidx = pcol_pad.reshape(nbc, bw)[col_idx].reshape(-1) if T else np.zeros(0, dtype=np.int32)
     chunks, part_base = build_schedule(row_ptr, chunk_tiles)
-    return dict(row_ptr=row_ptr, col_idx=col_idx, vals=vals, bias_p=bias_p,
+    return dict(xidx=np.ascontiguousarray(xidx, dtype=np.int32), row_ptr=row_ptr, col_idx=col_idx, vals=vals, bias_p=bias_p,
                 invprow=invert_permutation(prow), invpcol=invert_permutation(pcol),
                 prow_pad=prow_pad, pcol_pad=pcol_pad, chunks=chunks,
                 part_base=part_base, T=T, M_pad=Mp, K_pad=Kp)

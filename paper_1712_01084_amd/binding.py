@@ -29,7 +29,7 @@ EXPORTS = [
     "pivot_mlp_plan", "pivot_mlp_plan_host_view", "pivot_mlp_plan_destroy",
     "pivot_mlp_workspace_bytes", "pivot_mlp_run",
     "pivot_lstm_workspace_bytes", "pivot_lstm_run",
-    "pivot_dense_run",
+    "pivot_dense_run", "pivot_null_run",
 ]
 
 
@@ -41,18 +41,19 @@ class PivotError(RuntimeError):
 
 class pivot_fc_desc(C.Structure):
     _fields_ = [(n, C.c_int32) for n in
-                ("M", "K", "bh", "bw", "wdtype", "layout", "act", "chunk_tiles", "device", "flags")]
+                ("M", "K", "bh", "bw", "wdtype", "layout", "act", "chunk_tiles", "device", "wg_waves", "flags")]
 
 
 class pivot_plan_view(C.Structure):
     _fields_ = ([(n, C.c_int32) for n in
                  ("M", "K", "bh", "bw", "wdtype", "layout", "act", "nbr", "nbc", "M_pad", "K_pad",
-                  "T", "chunk_tiles", "nchunks")]
+                  "T", "chunk_tiles", "wg_waves", "nchunks")]
                 + [("row_ptr", C.POINTER(C.c_int32)), ("col_idx", C.POINTER(C.c_int32)),
                    ("vals", C.c_void_p), ("bias_p", C.POINTER(C.c_float)),
                    ("invprow", C.POINTER(C.c_int32)), ("invpcol", C.POINTER(C.c_int32)),
                    ("prow_pad", C.POINTER(C.c_int32)), ("pcol_pad", C.POINTER(C.c_int32)),
-                   ("chunks", C.POINTER(C.c_int32)), ("part_base", C.POINTER(C.c_int32))])
+                   ("chunks", C.POINTER(C.c_int32)), ("part_base", C.POINTER(C.c_int32)),
+                   ("xidx", C.POINTER(C.c_int32))])
 
 
 class pivot_mlp_view(C.Structure):
@@ -100,6 +101,7 @@ def lib():
     L.pivot_lstm_workspace_bytes.restype = sz
     L.pivot_lstm_run.argtypes = [vp, i32, i32, vp, vp, vp, vp, i32, i32, vp, sz, vp]
     L.pivot_dense_run.argtypes = [vp, i32, i32, i32, vp, i64, vp, vp, i64, i32, i32, vp]
+    L.pivot_null_run.argtypes = [vp]
     _lib = L
     return L
 
@@ -122,9 +124,9 @@ def pivot_last_error():
 
 
 def pivot_fc_plan(M, K, bh, bw, wdtype, W, w_space, tile_mask, prow, pcol, bias, *, layout=PIVOT_BRC,
-                  act=PIVOT_ACT_NONE, chunk_tiles=0, device=-1, flags=0):
+                  act=PIVOT_ACT_NONE, chunk_tiles=0, device=-1, wg_waves=0, flags=0):
     """Host numpy arrays in, opaque plan handle out."""
-    d = pivot_fc_desc(M, K, bh, bw, wdtype, layout, act, chunk_tiles, device, flags)
+    d = pivot_fc_desc(M, K, bh, bw, wdtype, layout, act, chunk_tiles, device, wg_waves, flags)
     W = None if W is None else np.ascontiguousarray(W, dtype=np.float32 if wdtype == PIVOT_F32 else np.float16)
     tile_mask = None if tile_mask is None else np.ascontiguousarray(tile_mask, dtype=np.uint8)
     prow = None if prow is None else np.ascontiguousarray(prow, dtype=np.int32)
@@ -148,7 +150,7 @@ def pivot_fc_plan_host_view(plan):
 
     wd = np.float32 if v.wdtype == PIVOT_F32 else np.float16
     out = {k: getattr(v, k) for k in ("M", "K", "bh", "bw", "wdtype", "layout", "act", "nbr", "nbc", "M_pad",
-                                      "K_pad", "T", "chunk_tiles", "nchunks")}
+                                      "K_pad", "T", "chunk_tiles", "wg_waves", "nchunks")}
     out["row_ptr"] = arr(v.row_ptr, v.nbr + 1, np.int32)
     out["col_idx"] = arr(v.col_idx, v.T, np.int32)
     out["vals"] = arr(v.vals, v.T * v.bh * v.bw, wd)
@@ -159,6 +161,7 @@ def pivot_fc_plan_host_view(plan):
     out["pcol_pad"] = arr(v.pcol_pad, v.K_pad, np.int32)
     out["chunks"] = arr(v.chunks, v.nchunks * 4, np.int32).reshape(-1, 4)
     out["part_base"] = arr(v.part_base, v.nbr + 1, np.int32)
+    out["xidx"] = arr(v.xidx, v.T * v.bw, np.int32)
     return out
 
 
@@ -228,3 +231,7 @@ def pivot_lstm_run(plan, H, I, xs_ptr, h_ptr, c_ptr, z_dbg_ptr, steps, batch, ws
 
 def pivot_dense_run(W_ptr, wdtype, M, K, x_ptr, ldx, bias_ptr, y_ptr, ldy, batch, act, stream=None):
     _check(lib().pivot_dense_run(W_ptr, wdtype, M, K, x_ptr, ldx, bias_ptr, y_ptr, ldy, batch, act, stream))
+
+
+def pivot_null_run(stream=None):
+    _check(lib().pivot_null_run(stream))

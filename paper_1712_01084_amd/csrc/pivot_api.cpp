@@ -41,6 +41,12 @@ struct Piece { const void* src; size_t bytes; void** dst; };
 int upload(pivot_fc_plan_t* p) {
     HostPlan& h = p->host;
     DevPlan& d = p->dev;
+    std::vector<int32_t> xblk;
+    try {
+        xblk.resize(h.xidx.size());
+    } catch (const std::bad_alloc&) { set_error("out of host memory"); return PIVOT_E_ALLOC; }
+    for (int t = 0; t < h.T; ++t)
+        for (int c = 0; c < h.d.bw; ++c) xblk[(size_t)t * h.d.bw + c] = h.col_idx[t] * h.d.bw + c;
     Piece pieces[] = {
         {h.vals.data(),      h.vals.size(),                 (void**)&d.vals},
         {h.col_idx.data(),   h.col_idx.size() * 4,          (void**)&d.col_idx},
@@ -51,6 +57,8 @@ int upload(pivot_fc_plan_t* p) {
         {h.pcol_pad.data(),  h.pcol_pad.size() * 4,         (void**)&d.pcol_pad},
         {h.invprow.data(),   h.invprow.size() * 4,          (void**)&d.invprow},
         {h.invpcol.data(),   h.invpcol.size() * 4,          (void**)&d.invpcol},
+        {h.xidx.data(),      h.xidx.size() * 4,             (void**)&d.xidx},
+        {xblk.data(),        xblk.size() * 4,               (void**)&d.xidx_blk},
     };
     size_t total = 0;
     for (auto& pc : pieces) total += align_up(pc.bytes + 16, 256);   // +16: vector loads of the last tile stay inside
@@ -113,11 +121,11 @@ int pivot_fc_plan_host_view(const pivot_fc_plan_t* plan, pivot_plan_view* v) {
     v->M = h.d.M; v->K = h.d.K; v->bh = h.d.bh; v->bw = h.d.bw; v->wdtype = h.d.wdtype;
     v->layout = h.d.layout; v->act = h.d.act;
     v->nbr = h.nbr; v->nbc = h.nbc; v->M_pad = h.M_pad; v->K_pad = h.K_pad; v->T = h.T;
-    v->chunk_tiles = h.chunk_tiles; v->nchunks = h.nchunks;
+    v->chunk_tiles = h.chunk_tiles; v->wg_waves = h.wg_waves; v->nchunks = h.nchunks;
     v->row_ptr = h.row_ptr.data(); v->col_idx = h.col_idx.data(); v->vals = h.vals.data();
     v->bias_p = h.bias_p.data(); v->invprow = h.invprow.data(); v->invpcol = h.invpcol.data();
     v->prow_pad = h.prow_pad.data(); v->pcol_pad = h.pcol_pad.data();
-    v->chunks = h.chunks.data(); v->part_base = h.part_base.data();
+    v->chunks = h.chunks.data(); v->part_base = h.part_base.data(); v->xidx = h.xidx.data();
     return PIVOT_OK;
 }
 
@@ -177,7 +185,7 @@ int prepare(const pivot_fc_plan_t* plan, int batch, void* ws, size_t ws_bytes, F
     const DevPlan& d = plan->dev;
     L.vals = d.vals; L.col_idx = d.col_idx; L.chunks = d.chunks; L.part_base = d.part_base; L.bias_p = d.bias_p;
     L.M_pad = h.M_pad; L.K_pad = h.K_pad; L.bh = h.d.bh; L.bw = h.d.bw; L.wdtype = h.d.wdtype; L.act = h.d.act;
-    L.nchunks = h.nchunks; L.nbr = h.nbr; L.chunk_tiles = h.chunk_tiles;
+    L.nchunks = h.nchunks; L.nbr = h.nbr; L.chunk_tiles = h.chunk_tiles; L.wg_waves = h.wg_waves;
     L.batch = batch;
     int nbt = fc_batch_tile(h.d.wdtype, h.d.bh, h.d.bw, batch);
     int ngy = (batch + nbt - 1) / nbt;
@@ -197,7 +205,7 @@ int pivot_fc_run(const pivot_fc_plan_t* plan, const void* x_dev, int64_t ldx, vo
     if (rc != PIVOT_OK) return rc;
     if (!x_dev || !y_dev) { set_error("x_dev and y_dev are required"); return PIVOT_E_NULL; }
     if (ldx < plan->host.d.K || ldy < plan->host.d.M) { set_error("ldx/ldy smaller than K/M"); return PIVOT_E_SHAPE; }
-    L.gather = plan->dev.pcol_pad;
+    L.xidx = plan->dev.xidx;
     L.scatter = plan->dev.prow_pad;
     L.out_rows = plan->host.d.M;
     L.x = x_dev; L.ldx = ldx; L.y = y_dev; L.ldy = ldy; L.out_f16 = 0; L.stream = stream;
@@ -338,8 +346,8 @@ int pivot_mlp_run(const pivot_mlp_plan_t* plan, const void* x_dev, int64_t ldx, 
         int rc = prepare(p, batch, ws, m.scratch, L);
         if (rc != PIVOT_OK) return rc;
         L.stream = stream;
-        if (l == 0) { L.gather = p->dev.pcol_pad; L.x = x_dev; L.ldx = ldx; }
-        else        { L.gather = nullptr; L.x = ws + m.inter_off[l - 1]; L.ldx = p->host.K_pad; }
+        if (l == 0) { L.xidx = p->dev.xidx; L.x = x_dev; L.ldx = ldx; }
+        else        { L.xidx = p->dev.xidx_blk; L.x = ws + m.inter_off[l - 1]; L.ldx = p->host.K_pad; }
         if (l + 1 < Lc) {
             // producer-side store through the composed boundary array; identity boundaries store contiguously
             L.scatter = plan->identity[l] ? nullptr : plan->dst_dev[l];
@@ -417,7 +425,7 @@ int pivot_lstm_run(const pivot_fc_plan_t* plan, int H, int I, const void* xs_dev
         FcLaunch L{};
         rc = prepare(plan, batch, ws, m.scratch, L);
         if (rc != PIVOT_OK) return rc;
-        L.gather = nullptr;
+        L.xidx = plan->dev.xidx_blk;
         L.x = xg + m.xg_step * (size_t)t; L.ldx = h.K_pad;
         L.scatter = nullptr; L.out_rows = h.M_pad;
         L.y = z; L.ldy = h.M_pad; L.out_f16 = 0; L.stream = stream;
@@ -432,6 +440,8 @@ int pivot_lstm_run(const pivot_fc_plan_t* plan, int H, int I, const void* xs_dev
     }
     return PIVOT_OK;
 }
+
+int pivot_null_run(void* stream) { return launch_null(stream); }
 
 int pivot_dense_run(const void* W_dev, int wdtype, int M, int K, const void* x_dev, int64_t ldx,
                     const float* bias_dev, void* y_dev, int64_t ldy, int batch, int act, void* stream) {

@@ -19,9 +19,10 @@ inline int    elem_size(int wdtype) { return wdtype == PIVOT_F32 ? 4 : 2; }
 // Host-side canonical arrays of one layer (what pivot_plan_view exposes).
 struct HostPlan {
     pivot_fc_desc d{};
-    int nbr = 0, nbc = 0, M_pad = 0, K_pad = 0, T = 0, chunk_tiles = 0, nchunks = 0;
+    int nbr = 0, nbc = 0, M_pad = 0, K_pad = 0, T = 0, chunk_tiles = 0, nchunks = 0, wg_waves = 4;
     int max_parts = 1;                 // largest number of pieces of one block row
     std::vector<int32_t> row_ptr, col_idx, invprow, invpcol, prow_pad, pcol_pad;
+    std::vector<int32_t> xidx;         // T*bw: xidx[t*bw+c] = pcol_pad[col_idx[t]*bw+c]
     std::vector<int32_t> chunks;       // nchunks x 4
     std::vector<int32_t> part_base;    // nbr + 1
     std::vector<float>   bias_p;
@@ -41,6 +42,8 @@ struct DevPlan {
     int32_t* pcol_pad = nullptr;
     int32_t* invprow = nullptr;
     int32_t* invpcol = nullptr;
+    int32_t* xidx = nullptr;      // gather index for natural-order x
+    int32_t* xidx_blk = nullptr;  // same for x already in block order: col_idx[t]*bw+c
 };
 
 // Builds every host array.  Returns PIVOT_OK or an error code (error text set).
@@ -56,6 +59,8 @@ bool device_supported(const pivot_fc_desc& d, std::string* why);
 int  max_chunk_tiles(const pivot_fc_desc& d);
 // The library's own choice of chunk size.
 int  choose_chunk_tiles(const HostPlan& hp);
+// The library's own choice of wavefronts per work item (after the schedule is cut).
+int  choose_wg_waves(const HostPlan& hp);
 
 // ---- what a kernel launch sees -------------------------------------------
 struct FcLaunch {
@@ -65,9 +70,10 @@ struct FcLaunch {
     const int32_t* chunks;      // int4 per chunk
     const int32_t* part_base;
     const float*   bias_p;
-    const int32_t* gather;      // block-space column -> index into x (-1 = padding); NULL = x already in block order
+    const int32_t* xidx;        // [T*bw]: index into x of column c of tile t (-1 = padding): through pcol for
+                                // natural-order x, the block-space column itself for x already in block order
     const int32_t* scatter;     // block-space row -> index into y (-1 = skip); NULL = store in block order (rows < out_rows)
-    int M_pad, K_pad, bh, bw, wdtype, act, nchunks, nbr, chunk_tiles;
+    int M_pad, K_pad, bh, bw, wdtype, act, nchunks, nbr, chunk_tiles, wg_waves;
     int out_rows;               // rows stored when scatter == NULL
     // data
     const void* x; int64_t ldx;
@@ -84,6 +90,7 @@ int    fc_batch_tile(int wdtype, int bh, int bw, int batch);
 size_t fc_workspace_bytes(const HostPlan& hp, int batch);
 int    launch_fc(const FcLaunch& L);
 int    launch_fill_zero(void* dev, size_t bytes, void* stream);
+int    launch_null(void* stream);
 int    launch_dense(const void* W, int wdtype, int M, int K, const void* x, int64_t ldx,
                     const float* bias, void* y, int64_t ldy, int batch, int act, void* stream);
 

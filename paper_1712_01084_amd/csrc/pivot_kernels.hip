@@ -36,7 +36,7 @@ struct FcArgs {
     const int4*    chunks;
     const int32_t* part_base;
     const float*   bias_p;
-    const int32_t* gather;
+    const int32_t* xidx;        // [T*bw] index into x of every kept tile's columns (-1 = padding)
     const int32_t* scatter;
     const void*    x;
     void*          y;
@@ -71,74 +71,123 @@ __device__ __forceinline__ void store_out(void* y, long long idx, float v, int o
     else         reinterpret_cast<float*>(y)[idx] = v;
 }
 
-// Stage the chunk's x-segments in LDS: xs[b][t*BW + c] = x[b][gather[col_idx[t]*BW + c]].
-// Padding columns (gather index -1) and batch rows past `batch` read as zero.
-template <typename WT, int BW, int NBT>
-__device__ __forceinline__ void stage_x(const FcArgs& a, WT* xs, int tile_begin, int ntiles,
-                                        int b0, int tid, int nthreads) {
-    const int ne = ntiles * BW;
-    const WT* x = reinterpret_cast<const WT*>(a.x);
-    // NBT consecutive threads share one column (one index load) and take one batch row each
-    const int b = tid % NBT;
-    const bool row_ok = (b0 + b) < a.batch;
-    const WT* xrow = x + (long long)(row_ok ? b0 + b : 0) * a.ldx;
-    for (int e = tid / NBT; e < ne; e += nthreads / NBT) {
-        const int t = e / BW;
-        const int c = e - t * BW;
-        const int kb = a.col_idx[tile_begin + t] * BW + c;
-        const int src = a.gather ? a.gather[kb] : kb;
-        WT v = WT(0);
-        if (src >= 0 && row_ok) v = xrow[src];
-        xs[b * a.xs_stride + e] = v;
+// Per-thread values that depend only on the block row, loaded at kernel start
+// so that their latency overlaps the weight stream instead of following it:
+// the bias and the destination index of every output this thread will finish
+// (outputs idx = tid + k*NT, idx = j*BH + r).
+template <int BH, int N, int NT>
+struct RowPre {
+    static constexpr int CNT = (N + NT - 1) / NT;
+    float bias[CNT];
+    int   dst[CNT];
+    __device__ __forceinline__ void load(const FcArgs& a, int br, int tid) {
+        #pragma unroll
+        for (int k = 0; k < CNT; ++k) {
+            const int idx = tid + k * NT;
+            bias[k] = 0.f;
+            dst[k] = -1;
+            if (idx < N) {
+                const int row = br * BH + idx % BH;
+                bias[k] = a.bias_p[row];
+                dst[k] = a.scatter ? a.scatter[row] : ((row < a.out_rows) ? row : -1);
+            }
+        }
     }
-}
+};
 
-// Everything after the per-workgroup sums are in LDS `red[idx]`, idx = j*BH + r
+// Staging of the chunk's x-segments in LDS (Listing 1: the group fetch through
+// P_col): xs[b][t*BW + c] = x[b][xidx[(tile_begin + t)*BW + c]].  xidx is the
+// column index array already composed with the tile list, so one index load
+// feeds the gather.  Index -1 (padding column) and batch rows past `batch`
+// read as zero.  NBT consecutive threads share one column and take one batch
+// row each.  The first XP indices per thread are fetched before the weight
+// stream is issued (loads return in order: an index fetched after the weights
+// would only arrive after them).
+template <typename WT, int BW, int NBT, int NT>
+struct XStage {
+    static constexpr int XP = 2;
+    static constexpr int STEP = NT / NBT;
+    int src[XP];
+    __device__ __forceinline__ void load_idx(const FcArgs& a, int tile_begin, int ne, int tid) {
+        const int32_t* xi = a.xidx + (size_t)tile_begin * BW;
+        #pragma unroll
+        for (int k = 0; k < XP; ++k) {
+            const int e = tid / NBT + k * STEP;
+            src[k] = (e < ne) ? xi[e] : -1;
+        }
+    }
+    __device__ __forceinline__ void gather(const FcArgs& a, WT* xs, int tile_begin, int ne, int b0, int tid) {
+        const int b = tid % NBT;
+        const bool row_ok = (b0 + b) < a.batch;
+        const WT* xrow = reinterpret_cast<const WT*>(a.x) + (long long)(row_ok ? b0 + b : 0) * a.ldx;
+        #pragma unroll
+        for (int k = 0; k < XP; ++k) {
+            const int e = tid / NBT + k * STEP;
+            if (e < ne) {
+                WT v = WT(0);
+                if (src[k] >= 0 && row_ok) v = xrow[src[k]];
+                xs[b * a.xs_stride + e] = v;
+            }
+        }
+        const int32_t* xi = a.xidx + (size_t)tile_begin * BW;
+        for (int e = tid / NBT + XP * STEP; e < ne; e += STEP) {
+            const int sidx = xi[e];
+            WT v = WT(0);
+            if (sidx >= 0 && row_ok) v = xrow[sidx];
+            xs[b * a.xs_stride + e] = v;
+        }
+    }
+};
+
+// Everything after the per-wave sums are in LDS `red[w*N + idx]`, idx = j*BH + r
 // (j = batch column of this launch tile, r = row inside the block row):
-// hand-over between the chunks of a split block row, bias, activation, store.
-template <int BH, int NBT>
-__device__ __forceinline__ void finish_rows(const FcArgs& a, const float* red, int nred, int br, int slot,
-                                            int b0, int gy, int tid, int nthreads, int* s_flag) {
-    const int first = a.part_base[br];
-    const int nparts = a.part_base[br + 1] - first;
+// hand-over between the chunks of a split block row (Section 4.1.5: tiles that
+// share rows need one more reduction), bias, activation, store through P_row.
+template <int BH, int NBT, int NT>
+__device__ __forceinline__ void finish_rows(const FcArgs& a, const float* red, int nred, int slot, int first,
+                                            int nparts, const RowPre<BH, BH * NBT, NT>& rp,
+                                            int b0, int gy, int tid, int* s_flag) {
     constexpr int N = BH * NBT;
     if (nparts > 1) {
         float* mine = a.partials + ((size_t)gy * a.nchunks + slot) * N;
-        for (int idx = tid; idx < N; idx += nthreads) {
+        for (int idx = tid; idx < N; idx += NT) {
             float s = 0.f;
             for (int w = 0; w < nred; ++w) s += red[w * N + idx];
             agent_store(mine + idx, s);
         }
-        __threadfence();
+        // Hand-over without a device-wide fence.  The partials are written with
+        // device-coherent (write-through) stores and read back with device-coherent
+        // loads, so no cache write-back or invalidate is needed; all that has to
+        // hold is that every store of this workgroup has completed before its
+        // arrival is counted.  A release fence at device scope would write back the
+        // whole L2 of the XCD for every workgroup and serialise the launch.
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         if (tid == 0) {
-            uint32_t* tk = a.tickets + (size_t)gy * a.nbr + br;
-            uint32_t prev = __hip_atomic_fetch_add(tk, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+            uint32_t* tk = a.tickets + (size_t)gy * a.nbr + a.chunks[blockIdx.x].x;
+            uint32_t prev = __hip_atomic_fetch_add(tk, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             int last = (prev == (uint32_t)(nparts - 1));
             if (last) __hip_atomic_store(tk, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             *s_flag = last;
         }
         __syncthreads();
         if (!*s_flag) return;
-        __threadfence();
     }
-    for (int idx = tid; idx < N; idx += nthreads) {
+    #pragma unroll
+    for (int k = 0; k < RowPre<BH, N, NT>::CNT; ++k) {
+        const int idx = tid + k * NT;
+        if (idx >= N) break;
         const int j = idx / BH;
-        const int r = idx - j * BH;
         if (b0 + j >= a.batch) continue;
         float s = 0.f;
         if (nparts > 1) {
             const float* p = a.partials + ((size_t)gy * a.nchunks + first) * N + idx;
-            for (int k = 0; k < nparts; ++k) s += agent_load(p + (size_t)k * N);
+            for (int q = 0; q < nparts; ++q) s += agent_load(p + (size_t)q * N);
         } else {
             for (int w = 0; w < nred; ++w) s += red[w * N + idx];
         }
-        const int row = br * BH + r;
-        float v = apply_act(s + a.bias_p[row], a.act);
-        int dst;
-        if (a.scatter) dst = a.scatter[row];
-        else           dst = (row < a.out_rows) ? row : -1;
-        if (dst >= 0) store_out(a.y, (long long)(b0 + j) * a.ldy + dst, v, a.out_f16);
+        const float v = apply_act(s + rp.bias[k], a.act);
+        if (rp.dst[k] >= 0) store_out(a.y, (long long)(b0 + j) * a.ldy + rp.dst[k], v, a.out_f16);
     }
 }
 
@@ -151,12 +200,14 @@ template <typename WT, int BH, int BW, int NB, int NW>
 __global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(FcArgs a) {
     using V = typename Elem<WT>::vec;
     constexpr int VEC = Elem<WT>::VEC;
+    constexpr int NT  = NW * 64;
     constexpr int LPR = BW / VEC;                       // lanes per tile row
     constexpr int RPW = 64 / LPR;                       // tile rows per wave-load
     constexpr int NL  = (BH >= RPW) ? BH / RPW : 1;     // wave-loads per tile
     constexpr int TPL = (BH >= RPW) ? 1 : RPW / BH;     // tiles per wave-load
     constexpr int U   = (NL >= 8) ? 1 : 8 / NL;         // groups in flight per wave
     constexpr int GROUP = TPL * BH * BW;                // elements per group of TPL tiles
+    constexpr int N   = BH * NB;
     static_assert(BW >= VEC && LPR <= 64, "tile width not supported");
 
     extern __shared__ __align__(16) char smem[];
@@ -169,6 +220,14 @@ __global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(FcArgs a) {
     const int4 cd = a.chunks[blockIdx.x];
     const int br = cd.x, tile_begin = cd.y, ntiles = cd.z - cd.y, slot = cd.w;
     const int ngroups = (ntiles + TPL - 1) / TPL;
+    const int first = a.part_base[br];
+    const int nparts = a.part_base[br + 1] - first;
+
+    // order of issue = order of arrival: gather indices, epilogue operands, then the weights
+    XStage<WT, BW, NB, NT> xst;
+    xst.load_idx(a, tile_begin, ntiles * BW, tid);
+    RowPre<BH, N, NT> rp;
+    rp.load(a, br, tid);
 
     const int s  = lane / LPR;                          // row within the wave-load
     const int cg = lane % LPR;                          // column group
@@ -189,8 +248,8 @@ __global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(FcArgs a) {
         }
     };
 
-    issue(wave);                                        // weights first: they do not depend on x
-    stage_x<WT, BW, NB>(a, xs, tile_begin, ntiles, b0, tid, NW * 64);
+    issue(wave);
+    xst.gather(a, xs, tile_begin, ntiles * BW, b0, tid);
     lds_barrier();
 
     float acc[NL][NB];
@@ -227,7 +286,6 @@ __global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(FcArgs a) {
         }
 
     __syncthreads();                                    // xs no longer needed; red aliases it
-    constexpr int N = BH * NB;
     if (cg == 0 && (TPL == 1 || s < BH)) {
         #pragma unroll
         for (int j = 0; j < NL; ++j) {
@@ -237,7 +295,7 @@ __global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(FcArgs a) {
         }
     }
     __syncthreads();
-    finish_rows<BH, NB>(a, red, NW, br, slot, b0, gy, tid, NW * 64, &s_flag);
+    finish_rows<BH, NB, NT>(a, red, NW, slot, first, nparts, rp, b0, gy, tid, &s_flag);
 }
 
 // ---------------------------------------------------------------------------
@@ -272,10 +330,12 @@ __global__ void __launch_bounds__(NW * 64) fc_mfma_kernel(FcArgs a) {
     using MF = Mfma<KIND>;
     using acc_t = typename MF::acc_t;
     constexpr int MR = MF::MR, MK = MF::MK, NBT = MF::NBT, CV = MF::CV;
+    constexpr int NT = NW * 64;
     constexpr int RB = BH / MR;                         // row blocks per tile
     constexpr int KS = BW / MK;                         // k steps per tile
     constexpr int LT = RB * KS;                         // 16-byte loads per lane per tile
     constexpr int U  = (LT >= 8) ? 1 : 8 / LT;          // tiles in flight per wave
+    constexpr int N  = BH * NBT;
     static_assert(BH % MR == 0 && BW % MK == 0, "tile shape does not fit this MFMA");
 
     extern __shared__ __align__(16) char smem[];
@@ -287,6 +347,13 @@ __global__ void __launch_bounds__(NW * 64) fc_mfma_kernel(FcArgs a) {
     const int gy = blockIdx.y, b0 = gy * NBT;
     const int4 cd = a.chunks[blockIdx.x];
     const int br = cd.x, tile_begin = cd.y, ntiles = cd.z - cd.y, slot = cd.w;
+    const int first = a.part_base[br];
+    const int nparts = a.part_base[br + 1] - first;
+
+    XStage<_Float16, BW, NBT, NT> xst;
+    xst.load_idx(a, tile_begin, ntiles * BW, tid);
+    RowPre<BH, N, NT> rp;
+    rp.load(a, br, tid);
 
     const int li = lane % MR;                           // A row / B column of this lane
     const int lg = lane / MR;                           // k group of 8
@@ -309,7 +376,7 @@ __global__ void __launch_bounds__(NW * 64) fc_mfma_kernel(FcArgs a) {
     };
 
     issue(wave);
-    stage_x<_Float16, BW, NBT>(a, xs, tile_begin, ntiles, b0, tid, NW * 64);
+    xst.gather(a, xs, tile_begin, ntiles * BW, b0, tid);
     lds_barrier();
 
     acc_t acc[RB];
@@ -333,14 +400,13 @@ __global__ void __launch_bounds__(NW * 64) fc_mfma_kernel(FcArgs a) {
     }
 
     __syncthreads();                                    // xs no longer needed; red aliases it
-    constexpr int N = BH * NBT;
     #pragma unroll
     for (int rb = 0; rb < RB; ++rb)
         #pragma unroll
         for (int v = 0; v < CV; ++v)
             red[wave * N + li * BH + rb * MR + MF::row_of(lane, v)] = acc[rb][v];
     __syncthreads();
-    finish_rows<BH, NBT>(a, red, NW, br, slot, b0, gy, tid, NW * 64, &s_flag);
+    finish_rows<BH, NBT, NT>(a, red, NW, slot, first, nparts, rp, b0, gy, tid, &s_flag);
 }
 
 // ---------------------------------------------------------------------------
@@ -374,18 +440,20 @@ size_t fc_workspace_bytes(const HostPlan& hp, int batch) {
 }
 
 template <typename WT, int BH, int BW, int NB>
-static int launch_gemv_t(const FcArgs& a, dim3 grid, size_t smem, hipStream_t st) {
-    hipLaunchKernelGGL((fc_gemv_kernel<WT, BH, BW, NB, kWaves>), grid, dim3(kWaves * 64), smem, st, a);
+static int launch_gemv_t(const FcArgs& a, int nw, dim3 grid, size_t smem, hipStream_t st) {
+    if (nw == 16)     hipLaunchKernelGGL((fc_gemv_kernel<WT, BH, BW, NB, 16>), grid, dim3(16 * 64), smem, st, a);
+    else if (nw == 8) hipLaunchKernelGGL((fc_gemv_kernel<WT, BH, BW, NB, 8>), grid, dim3(8 * 64), smem, st, a);
+    else              hipLaunchKernelGGL((fc_gemv_kernel<WT, BH, BW, NB, 4>), grid, dim3(4 * 64), smem, st, a);
     HIP_TRY(hipGetLastError());
     return PIVOT_OK;
 }
 
 template <typename WT, int BH, int BW>
-static int launch_gemv_nb(const FcArgs& a, int nb, dim3 grid, size_t smem, hipStream_t st) {
+static int launch_gemv_nb(const FcArgs& a, int nb, int nw, dim3 grid, size_t smem, hipStream_t st) {
     switch (nb) {
-        case 1: return launch_gemv_t<WT, BH, BW, 1>(a, grid, smem, st);
-        case 2: return launch_gemv_t<WT, BH, BW, 2>(a, grid, smem, st);
-        default: return launch_gemv_t<WT, BH, BW, 4>(a, grid, smem, st);
+        case 1: return launch_gemv_t<WT, BH, BW, 1>(a, nw, grid, smem, st);
+        case 2: return launch_gemv_t<WT, BH, BW, 2>(a, nw, grid, smem, st);
+        default: return launch_gemv_t<WT, BH, BW, 4>(a, nw, grid, smem, st);
     }
 }
 
@@ -407,7 +475,7 @@ int launch_fc(const FcLaunch& L) {
     const int ngy = (L.batch + nbt - 1) / nbt;
     FcArgs a;
     a.vals = L.vals; a.col_idx = L.col_idx; a.chunks = reinterpret_cast<const int4*>(L.chunks);
-    a.part_base = L.part_base; a.bias_p = L.bias_p; a.gather = L.gather; a.scatter = L.scatter;
+    a.part_base = L.part_base; a.bias_p = L.bias_p; a.xidx = L.xidx; a.scatter = L.scatter;
     a.x = L.x; a.y = L.y; a.partials = L.partials; a.tickets = L.tickets;
     a.ldx = L.ldx; a.ldy = L.ldy; a.batch = L.batch; a.act = L.act; a.out_f16 = L.out_f16;
     a.out_rows = L.out_rows; a.nchunks = L.nchunks; a.nbr = L.nbr;
@@ -415,7 +483,8 @@ int launch_fc(const FcLaunch& L) {
     // staged x: nbt rows of chunk_tiles*bw elements (+16 bytes to skew LDS banks)
     a.xs_stride = L.chunk_tiles * L.bw + 16 / es;
     size_t xs_bytes = (size_t)nbt * a.xs_stride * es;
-    size_t red_bytes = (size_t)kWaves * L.bh * nbt * 4;
+    const int nw = (nbt >= 16) ? kWaves : ((L.wg_waves == 16 || L.wg_waves == 8) ? L.wg_waves : 4);
+    size_t red_bytes = (size_t)nw * L.bh * nbt * 4;
     size_t smem = align_up(xs_bytes > red_bytes ? xs_bytes : red_bytes, 16);
     if (smem > 64 * 1024) { set_error("chunk does not fit in LDS (%zu bytes)", smem); return PIVOT_E_UNSUPPORTED; }
     dim3 grid(L.nchunks, ngy);
@@ -434,11 +503,11 @@ int launch_fc(const FcLaunch& L) {
         return PIVOT_E_UNSUPPORTED;
     }
     if (L.wdtype == PIVOT_F32) {
-#define X(BH_, BW_) if (L.bh == BH_ && L.bw == BW_) return launch_gemv_nb<float, BH_, BW_>(a, nbt, grid, smem, st);
+#define X(BH_, BW_) if (L.bh == BH_ && L.bw == BW_) return launch_gemv_nb<float, BH_, BW_>(a, nbt, nw, grid, smem, st);
         PIVOT_SHAPES(X)
 #undef X
     } else {
-#define X(BH_, BW_) if (L.bh == BH_ && L.bw == BW_) return launch_gemv_nb<_Float16, BH_, BW_>(a, nbt, grid, smem, st);
+#define X(BH_, BW_) if (L.bh == BH_ && L.bw == BW_) return launch_gemv_nb<_Float16, BH_, BW_>(a, nbt, nw, grid, smem, st);
         PIVOT_SHAPES(X)
 #undef X
     }
@@ -453,6 +522,14 @@ __global__ void fill_zero_kernel(uint32_t* p, size_t nwords) {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     for (; i < nwords; i += stride) p[i] = 0u;
+}
+
+__global__ void null_kernel() {}
+
+int launch_null(void* stream) {
+    hipLaunchKernelGGL(null_kernel, dim3(1), dim3(64), 0, reinterpret_cast<hipStream_t>(stream));
+    HIP_TRY(hipGetLastError());
+    return PIVOT_OK;
 }
 
 int launch_fill_zero(void* dev, size_t bytes, void* stream) {

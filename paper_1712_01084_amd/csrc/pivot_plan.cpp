@@ -56,6 +56,18 @@ int choose_chunk_tiles(const HostPlan& hp) {
     return std::min(ct, max_chunk_tiles(hp.d));
 }
 
+int choose_wg_waves(const HostPlan& hp) {
+    // One wavefront keeps about 8 KB of tile values in flight; give the
+    // largest work item enough wavefronts to have all of it in flight at once.
+    size_t tile_bytes = (size_t)hp.d.bh * hp.d.bw * elem_size(hp.d.wdtype);
+    size_t big = 0;
+    for (int j = 0; j < hp.nchunks; ++j)
+        big = std::max(big, (size_t)(hp.chunks[4 * j + 2] - hp.chunks[4 * j + 1]) * tile_bytes);
+    if (big <= 4 * 8192) return 4;
+    if (big <= 8 * 8192) return 8;
+    return 16;
+}
+
 void build_schedule(HostPlan& hp, int chunk_tiles) {
     hp.chunk_tiles = chunk_tiles;
     struct C { int32_t br, b, e, slot; };
@@ -138,6 +150,7 @@ int build_host_plan(const pivot_fc_desc& d, const void* W, int w_space, const ui
     if (w_space != PIVOT_W_NATURAL && w_space != PIVOT_W_PIVOTED) { set_error("unknown weight space %d", w_space); return PIVOT_E_UNSUPPORTED; }
     if (d.chunk_tiles < 0) { set_error("chunk_tiles must be >= 0"); return PIVOT_E_SHAPE; }
     if (d.flags != 0) { set_error("flags must be 0"); return PIVOT_E_UNSUPPORTED; }
+    if (d.wg_waves != 0 && d.wg_waves != 4 && d.wg_waves != 8 && d.wg_waves != 16) { set_error("wg_waves must be 0, 4, 8 or 16"); return PIVOT_E_UNSUPPORTED; }
 
     hp.d = d;
     hp.nbr = (d.M + d.bh - 1) / d.bh;
@@ -175,10 +188,15 @@ int build_host_plan(const pivot_fc_desc& d, const void* W, int w_space, const ui
         hp.pcol_pad.assign(hp.K_pad, -1);
         std::copy(pcol, pcol + d.K, hp.pcol_pad.begin());
 
+        hp.xidx.resize((size_t)hp.T * d.bw);
+        for (int t = 0; t < hp.T; ++t)
+            for (int c = 0; c < d.bw; ++c) hp.xidx[(size_t)t * d.bw + c] = hp.pcol_pad[(size_t)hp.col_idx[t] * d.bw + c];
+
         int ct = d.chunk_tiles;
         if (ct == 0) ct = choose_chunk_tiles(hp);
         if (d.device >= 0) ct = std::min(ct, max_chunk_tiles(d));
         build_schedule(hp, ct);
+        hp.wg_waves = d.wg_waves ? d.wg_waves : choose_wg_waves(hp);
     } catch (const std::bad_alloc&) {
         set_error("out of host memory while building the plan");
         return PIVOT_E_ALLOC;

@@ -1,0 +1,145 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle for single
+layers.  Needs a GPU."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import pivot_oracle as O
+from paper_1712_01084_amd import binding as B
+from paper_1712_01084_amd import workloads as WL
+
+import gpu_util as G
+
+pytestmark = pytest.mark.gpu
+
+SHAPES = [(bh, bw) for bh in (8, 16, 32, 64) for bw in (8, 16, 32, 64)]
+
+
+@pytest.mark.parametrize("wdtype", [WL.F32, WL.F16])
+@pytest.mark.parametrize("bh,bw", SHAPES)
+def test_every_tile_shape_ragged_small(bh, bw, wdtype):
+    # several tiles per block row, ragged last block row and block column, an
+    # empty block row, rows split over several work items
+    M, K = 5 * bh - 3, 9 * bw - 5
+    for batch, ct in ((1, 2), (3, 4)):
+        p = WL.gen_fc(M, K, bh, bw, 0.6, seed=100 + bh + bw, wdtype=wdtype, batch=batch, act=WL.ACT_RELU)
+        p.tile_mask[2, :] = 0
+        G.check_fc(p, chunk_tiles=ct)
+
+
+@pytest.mark.parametrize("batch", [1, 2, 3, 4, 5, 8])
+def test_batches_fp32(batch):
+    p = WL.gen_fc(200, 328, 16, 16, 0.5, seed=7, batch=batch, act=WL.ACT_NONE)
+    G.check_fc(p, chunk_tiles=3)
+
+
+@pytest.mark.parametrize("batch", [1, 2, 4, 7, 8, 16, 33, 64])
+@pytest.mark.parametrize("bh,bw", [(64, 16), (16, 32), (32, 32), (16, 16)])
+def test_batches_fp16_including_matrix_core_path(bh, bw, batch):
+    p = WL.gen_fc(5 * bh - 1, 11 * bw - 2, bh, bw, 0.5, seed=8, wdtype=WL.F16, batch=batch, act=WL.ACT_RELU)
+    p.tile_mask[1, :] = 0
+    G.check_fc(p, chunk_tiles=3)
+
+
+def test_degenerate_masks_and_natural_weights():
+    p = WL.gen_fc(64, 96, 16, 16, 0.5, seed=9, act=WL.ACT_RELU)
+    p.tile_mask[:] = 0                                   # no tile kept: y = relu(b)
+    G.check_fc(p)
+    p = WL.gen_fc(64, 96, 16, 16, 1.0, seed=10, mask="full")
+    G.check_fc(p, chunk_tiles=1)                         # every tile its own work item
+    G.check_fc(p, chunk_tiles=6)                         # whole block rows
+    p = WL.gen_fc(70, 100, 16, 32, 0.4, seed=11, wdtype=WL.F16, batch=2)
+    G.check_fc(p, natural=True)
+
+
+def test_identity_perms_full_mask_matches_dense_kernel():
+    for wdtype in (WL.F32, WL.F16):
+        p = WL.gen_fc(256, 512, 32, 32, 1.0, seed=12, mask="full", perms="identity", wdtype=wdtype, batch=4)
+        G.check_fc(p)
+        st = torch.cuda.current_stream().cuda_stream
+        Wd = torch.from_numpy(p.Wp).cuda()
+        xd = torch.from_numpy(p.x).cuda()
+        bd = torch.from_numpy(p.bias).cuda()
+        for batch in (1, 4):
+            yd = torch.full((batch, p.M), float("nan"), dtype=torch.float32, device="cuda")
+            B.pivot_dense_run(Wd.data_ptr(), G.wd(p), p.M, p.K, xd.data_ptr(), p.K, bd.data_ptr(), yd.data_ptr(),
+                              p.M, batch, p.act, st)
+            torch.cuda.synchronize()
+            y_ref, D = G.oracle_of(p, x=p.x[:batch])
+            assert O.max_scaled_error(yd.cpu().numpy(), y_ref, D) <= G.TOL[wdtype]
+
+
+def test_fp16_subnormal_weights_are_kept():
+    p = WL.gen_fc(128, 128, 64, 16, 0.5, seed=13, wdtype=WL.F16, batch=16)
+    tiny = (np.random.default_rng(1).integers(1, 1024, size=p.Wp.shape).astype(np.uint16)).view(np.float16)
+    p.Wp = tiny                                           # every weight a positive fp16 subnormal
+    p.bias[:] = 0
+    for batch in (1, 16):
+        x = np.abs(p.x[:batch])
+        y_ref, D = G.oracle_of(p, x=x)
+        assert y_ref.max() > 0
+        G.check_fc(p, chunk_tiles=2, x=x)
+
+
+def test_strided_x_and_y():
+    p = WL.gen_fc(96, 160, 32, 32, 0.5, seed=14, batch=3, act=WL.ACT_RELU)
+    plan = G.dev_plan(p, chunk_tiles=2)
+    try:
+        ldx, ldy = p.K + 24, p.M + 8
+        xd = torch.zeros((3, ldx), dtype=torch.float32, device="cuda")
+        xd[:, :p.K] = torch.from_numpy(p.x).cuda()
+        yd = torch.full((3, ldy), -7.0, dtype=torch.float32, device="cuda")
+        ws = G.workspace(B.pivot_fc_workspace_bytes(plan, 3))
+        B.pivot_fc_run(plan, xd.data_ptr(), ldx, yd.data_ptr(), ldy, 3, ws.data_ptr(), ws.numel(),
+                       torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        y = yd.cpu().numpy()
+        y_ref, D = G.oracle_of(p)
+        assert O.max_scaled_error(y[:, :p.M], y_ref, D) <= 1e-5
+        assert np.all(y[:, p.M:] == -7.0)                 # nothing written past M
+    finally:
+        B.pivot_fc_plan_destroy(plan)
+
+
+def test_run_error_paths_on_device_plans():
+    p = WL.gen_fc(64, 64, 16, 16, 0.5, seed=15)
+    plan = G.dev_plan(p, chunk_tiles=1)
+    try:
+        xd = torch.zeros((1, 64), device="cuda")
+        yd = torch.zeros((1, 64), device="cuda")
+        for kw, code in ((dict(ws=0, nb=0), B.PIVOT_E_WORKSPACE), (dict(batch=0), B.PIVOT_E_SHAPE),
+                         (dict(batch=65), B.PIVOT_E_SHAPE), (dict(ldx=8), B.PIVOT_E_SHAPE), (dict(x=0), B.PIVOT_E_NULL)):
+            ws = G.workspace(B.pivot_fc_workspace_bytes(plan, 1))
+            a = dict(x=xd.data_ptr(), ldx=64, y=yd.data_ptr(), ldy=64, batch=1, ws=ws.data_ptr(), nb=ws.numel())
+            a.update(kw)
+            with pytest.raises(B.PivotError) as e:
+                B.pivot_fc_run(plan, a["x"], a["ldx"], a["y"], a["ldy"], a["batch"], a["ws"], a["nb"], None)
+            assert e.value.code == code
+    finally:
+        B.pivot_fc_plan_destroy(plan)
+
+
+# ------------------------------------------------------------- full-size configurations
+
+@pytest.mark.parametrize("seed", [0, 1])
+def test_config1_full(seed):
+    G.check_fc(WL.config1(seed=seed))
+
+
+def test_config2_full():
+    p = WL.config2(seed=0)
+    err = G.check_fc(p)
+    print("config2 scaled error %.3g" % err)
+
+
+@pytest.mark.parametrize("frac", WL.CONFIG3_FRACS)
+def test_config3_full(frac):
+    for batch in (1, 4, 16):
+        G.check_fc(WL.config3(seed=0, batch=batch, frac=frac))
+
+
+def test_config5_gate_matrix_full_batch8():
+    lp = WL.config5(seed=0, steps=1)
+    p = lp.fc
+    p.x = np.random.default_rng(3).standard_normal((8, p.K)).astype(np.float16)
+    G.check_fc(p)

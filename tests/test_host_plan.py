@@ -14,7 +14,7 @@ from paper_1712_01084_amd import workloads as WL
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 PLAN_ARRAYS = ("row_ptr", "col_idx", "vals", "bias_p", "invprow", "invpcol", "prow_pad", "pcol_pad",
-               "chunks", "part_base")
+               "chunks", "part_base", "xidx")
 
 
 def _wd(p):

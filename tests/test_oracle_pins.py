@@ -278,7 +278,8 @@ def test_fused_chain_equals_natural_coordinate_chain(eliminated):
 def test_mlp_boundary_rounding_happens_once_between_layers():
     probs = WL.config4(seed=2, dims=(64, 32, 32), wdtype=WL.F16)
     layers = _as_layers(probs)
-    outs, _ = O.oracle_mlp(layers, probs[0].x, boundary_dtype=np.float16, return_all=True)
+    outs, scales, chain = O.oracle_mlp(layers, probs[0].x, boundary_dtype=np.float16, return_all=True)
+    assert np.array_equal(chain[0], scales[0]) and np.all(chain[1] >= scales[1])
     h1 = outs[0].astype(np.float16)
     want = O.oracle_fc(probs[1].Wp, probs[1].tile_mask, probs[1].prow, probs[1].pcol, probs[1].bias,
                        h1, 32, 32, probs[1].act)
