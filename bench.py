@@ -1,0 +1,209 @@
+#!/usr/bin/env python3
+"""Benchmark of the pruned fully-connected hot path on one MI355X.
+
+One "step" is one application of the layer through pivot_fc_run (gather
+through P_col into LDS, tile stream, reduction, bias, activation, scatter
+through P_row) on one batch of synthetic input that is already resident in
+HBM.  The workload is the AlexNet-fc6-shaped layer of the workload list
+(4096 x 9216, fp32, batch 1, 32x32 tiles, 10 % kept, balanced rows).
+
+The headline value is the cache-cold time per layer: consecutive steps rotate
+through enough separate device copies of the plan and of x that no byte a step
+reads is still in the L2 or the 256 MB Infinity Cache.  The warm time (same
+copy back to back) is reported beside it.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0            # MI355X published HBM3E peak
+COLD_FOOTPRINT = 2 * (256 + 32) * (1 << 20)   # rotate through >= 2 x (Infinity Cache + all L2)
+
+
+def parse_traffic():
+    """HBM bytes per launch measured with rocprofv3 --pmc (profiles/*.txt), or None."""
+    path = os.path.join(ROOT, "profiles", "fc_gemv_cfg2_hbm_traffic.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_launch"):
+                    return float(line.split("=")[1].split()[0])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2500)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (the layer is a single-device kernel); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_1712_01084_amd import binding as B
+    from paper_1712_01084_amd import workloads as WL
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    B.lib()                                      # fails loudly if the HIP library is not built
+    torch.cuda.set_device(0)
+    st = torch.cuda.current_stream().cuda_stream
+    K, Wm = args.steps, args.warmup
+
+    p = WL.config2(seed=args.seed)
+    wd = B.PIVOT_F32
+    plan0 = B.pivot_fc_plan(p.M, p.K, p.bh, p.bw, wd, p.Wp, B.PIVOT_W_PIVOTED, p.tile_mask, p.prow, p.pcol,
+                            p.bias, act=p.act, device=0)
+    view = B.pivot_fc_plan_host_view(plan0)
+    alg_bytes = p.algorithmic_bytes(1)
+    ncopies = max(2, -(-COLD_FOOTPRINT // alg_bytes))
+    plans = [plan0] + [B.pivot_fc_plan_clone(plan0) for _ in range(ncopies - 1)]
+    xs = [torch.from_numpy(p.x.copy()).cuda() for _ in range(ncopies)]
+    ys = [torch.empty((1, p.M), dtype=torch.float32, device="cuda") for _ in range(ncopies)]
+    ws_bytes = max(256, B.pivot_fc_workspace_bytes(plan0, 1))
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    B.pivot_workspace_init(ws.data_ptr(), ws_bytes, st)
+
+    def run_steps(n, rotate):
+        for i in range(n):
+            j = i % ncopies if rotate else 0
+            B.pivot_fc_run(plans[j], xs[j].data_ptr(), p.K, ys[j].data_ptr(), p.M, 1, ws.data_ptr(), ws_bytes, st)
+
+    def timed(n, rotate, warm):
+        run_steps(warm, rotate)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        run_steps(n, rotate)
+        e1.record()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        return e0.elapsed_time(e1) / n, wall / n * 1e3      # ms per step (device events), ms per step (host clock)
+
+    cold_ms, cold_wall_ms = timed(K, True, Wm)
+    warm_ms, _ = timed(K, False, Wm)
+
+    # launch floor: an empty kernel back to back on the same stream
+    for _ in range(100):
+        B.pivot_null_run(st)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(2000):
+        B.pivot_null_run(st)
+    e1.record()
+    torch.cuda.synchronize()
+    null_us = e0.elapsed_time(e1) / 2000 * 1e3
+
+    # the same layer dense on the GPU: this library's streaming kernel, cold, and torch.mv as a guard
+    dense_bytes = p.dense_bytes(1)
+    nd = max(2, -(-COLD_FOOTPRINT // dense_bytes))
+    Wnat = np.empty_like(p.Wp)
+    Wnat[np.ix_(p.prow, p.pcol)] = p.Wp          # un-pivot: the dense comparator works in natural coordinates
+    Wds = [torch.from_numpy(Wnat).cuda() for _ in range(nd)]
+    bd = torch.from_numpy(p.bias).cuda()
+    yd = torch.empty((1, p.M), dtype=torch.float32, device="cuda")
+
+    def dense_steps(n):
+        for i in range(n):
+            j = i % nd
+            B.pivot_dense_run(Wds[j].data_ptr(), wd, p.M, p.K, xs[j].data_ptr(), p.K, bd.data_ptr(), yd.data_ptr(),
+                              p.M, 1, p.act, st)
+
+    dense_steps(2 * nd)
+    torch.cuda.synchronize()
+    nde = 200
+    e0.record(); dense_steps(nde); e1.record(); torch.cuda.synchronize()
+    dense_us = e0.elapsed_time(e1) / nde * 1e3
+    xv = xs[0][0]
+    for j in range(2 * nd):
+        torch.mv(Wds[j % nd], xv)
+    torch.cuda.synchronize()
+    e0.record()
+    for j in range(nde):
+        torch.mv(Wds[j % nd], xv)
+    e1.record(); torch.cuda.synchronize()
+    torch_mv_us = e0.elapsed_time(e1) / nde * 1e3
+    dense_best_us = min(dense_us, torch_mv_us)
+
+    cold_us, warm_us = cold_ms * 1e3, warm_ms * 1e3
+    kept = p.T / float(p.nbr * p.nbc)
+    achieved = alg_bytes / (cold_us * 1e-6) / 1e9
+    out = {
+        "metric": "us per pruned FC layer @batch 1 (cache-cold) and % HBM roofline; speedup vs dense GEMV",
+        "value": round(cold_us, 3),
+        "unit": "us/layer",
+        "n_gpus": 1, "steps": K, "warmup": Wm,
+        "ms_per_step": cold_ms,
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "configs[1]: FC 4096x9216 (AlexNet fc6 shape) fp32 batch 1, 32x32 tiles, "
+                               "29 of 288 tiles kept per block row (balanced), uniform random P_r/P_c, ReLU",
+                   "seed": args.seed, "kept_fraction": round(kept, 5), "tiles": p.T,
+                   "chunk_tiles": view["chunk_tiles"], "work_items": view["nchunks"], "wg_waves": view["wg_waves"],
+                   "cold_copies": ncopies},
+        "warm_us": round(warm_us, 3),
+        "cold_host_clock_us": round(cold_wall_ms * 1e3, 3),
+        "null_kernel_us": round(null_us, 3),
+        "dense_gpu_us": {"own_kernel_cold": round(dense_us, 3), "torch_mv_cold": round(torch_mv_us, 3)},
+        "speedup_vs_dense": round(dense_best_us / cold_us, 3),
+        "linear_speedup": round(1.0 / kept, 3),
+        "algorithmic_bytes": alg_bytes,
+        "roofline": {"bound": "hbm", "kernel": "fc_gemv_kernel<float,32,32,1,*>", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": parse_traffic(),
+                     "warm_effective": round(alg_bytes / (warm_us * 1e-6) / 1e9, 1)},
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import pivot_oracle as O
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
+        except Exception:
+            cores = len(os.sched_getaffinity(0))
+        Wd = O.dense_masked_natural(p.Wp, p.tile_mask, p.prow, p.pcol, p.bh, p.bw)
+        y_ref = O.fc_dense(Wd, p.x, p.bias, p.act)       # warm-up + parity of the timed configuration
+        D = O.error_scale(Wd, p.x, p.bias)
+        err = O.max_scaled_error(ys[0].cpu().numpy(), y_ref, D)
+        t0 = time.perf_counter()
+        n = 0
+        while time.perf_counter() - t0 < 10.0:
+            O.fc_dense(Wd, p.x, p.bias, p.act)
+            n += 1
+        cpu_us = (time.perf_counter() - t0) / n * 1e6
+        out["cpu_baseline"] = {"value": round(cpu_us, 1), "unit": "us/layer", "cores": int(cores), "kind": "oracle",
+                               "sample": "%d applications of the same layer (float64 dense masked matvec, matrix "
+                                         "prebuilt), about 10 s" % n}
+        out["parity_max_scaled_error"] = err
+        if not (err <= 1e-5):
+            print("bench.py: parity check failed (%.3g)" % err, file=sys.stderr)
+            sys.exit(1)
+
+    for h in plans:
+        B.pivot_fc_plan_destroy(h)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

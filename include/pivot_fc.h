@@ -83,6 +83,7 @@ typedef struct pivot_fc_desc {
     int32_t chunk_tiles;  /* max tiles per work item; 0 = the library chooses            */
     int32_t device;       /* HIP device ordinal, or -1 for a host-only plan (no GPU use) */
     int32_t wg_waves;     /* wavefronts per work item: 4, 8 or 16; 0 = the library chooses */
+    int32_t row_slices;   /* independent work items per tile height: 1, 2, 4 or 8; 0 = the library chooses */
     int32_t flags;        /* reserved, must be 0                                         */
 } pivot_fc_desc;
 
@@ -105,6 +106,7 @@ typedef struct pivot_plan_view {
     int32_t T;                 /* kept tiles */
     int32_t chunk_tiles;       /* resolved value */
     int32_t wg_waves;          /* resolved value */
+    int32_t row_slices;        /* resolved value */
     int32_t nchunks;
     const int32_t* row_ptr;    /* [nbr+1] */
     const int32_t* col_idx;    /* [T]     */
@@ -164,7 +166,9 @@ int    pivot_workspace_init(void* ws_dev, size_t ws_bytes, void* stream);
  *
  *   x_dev  device, [batch][K] of wdtype, row stride ldx elements, natural coordinates
  *   y_dev  device, [batch][M] fp32, row stride ldy elements, natural coordinates
- *   batch  1..64 (F16 plans use the matrix cores from batch 8 on)
+ *   batch  1..64.  F16 plans whose tiles fit an MFMA shape use the matrix
+ *          cores from batch 8 on; that path first copies x into block order
+ *          (one small extra kernel) and reads it from there.
  */
 int  pivot_fc_run(const pivot_fc_plan_t* plan, const void* x_dev, int64_t ldx,
                   void* y_dev, int64_t ldy, int batch,
@@ -180,7 +184,8 @@ int  pivot_fc_run(const pivot_fc_plan_t* plan, const void* x_dev, int64_t ldx,
  * irregular remains at that boundary (Section 4.2.3).  With
  * PIVOT_MLP_KEEP_FINAL_BLOCK_ORDER the last layer's scatter is dropped and
  * the host relabels outputs with prow of the last layer (Section 4.2.2):
- * y_dev then holds M_pad_last values per batch row in block order.
+ * y_dev then holds M_pad_last values per batch row in block order (padding
+ * entries are not written).
  * Intermediates have the plans' wdtype (F16 chains round once per boundary).
  * All layers must share wdtype and device.  Layer plans are borrowed and must
  * outlive the chain plan.

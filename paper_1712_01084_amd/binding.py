@@ -41,13 +41,13 @@ class PivotError(RuntimeError):
 
 class pivot_fc_desc(C.Structure):
     _fields_ = [(n, C.c_int32) for n in
-                ("M", "K", "bh", "bw", "wdtype", "layout", "act", "chunk_tiles", "device", "wg_waves", "flags")]
+                ("M", "K", "bh", "bw", "wdtype", "layout", "act", "chunk_tiles", "device", "wg_waves", "row_slices", "flags")]
 
 
 class pivot_plan_view(C.Structure):
     _fields_ = ([(n, C.c_int32) for n in
                  ("M", "K", "bh", "bw", "wdtype", "layout", "act", "nbr", "nbc", "M_pad", "K_pad",
-                  "T", "chunk_tiles", "wg_waves", "nchunks")]
+                  "T", "chunk_tiles", "wg_waves", "row_slices", "nchunks")]
                 + [("row_ptr", C.POINTER(C.c_int32)), ("col_idx", C.POINTER(C.c_int32)),
                    ("vals", C.c_void_p), ("bias_p", C.POINTER(C.c_float)),
                    ("invprow", C.POINTER(C.c_int32)), ("invpcol", C.POINTER(C.c_int32)),
@@ -124,9 +124,9 @@ def pivot_last_error():
 
 
 def pivot_fc_plan(M, K, bh, bw, wdtype, W, w_space, tile_mask, prow, pcol, bias, *, layout=PIVOT_BRC,
-                  act=PIVOT_ACT_NONE, chunk_tiles=0, device=-1, wg_waves=0, flags=0):
+                  act=PIVOT_ACT_NONE, chunk_tiles=0, device=-1, wg_waves=0, row_slices=0, flags=0):
     """Host numpy arrays in, opaque plan handle out."""
-    d = pivot_fc_desc(M, K, bh, bw, wdtype, layout, act, chunk_tiles, device, wg_waves, flags)
+    d = pivot_fc_desc(M, K, bh, bw, wdtype, layout, act, chunk_tiles, device, wg_waves, row_slices, flags)
     W = None if W is None else np.ascontiguousarray(W, dtype=np.float32 if wdtype == PIVOT_F32 else np.float16)
     tile_mask = None if tile_mask is None else np.ascontiguousarray(tile_mask, dtype=np.uint8)
     prow = None if prow is None else np.ascontiguousarray(prow, dtype=np.int32)
@@ -150,7 +150,7 @@ def pivot_fc_plan_host_view(plan):
 
     wd = np.float32 if v.wdtype == PIVOT_F32 else np.float16
     out = {k: getattr(v, k) for k in ("M", "K", "bh", "bw", "wdtype", "layout", "act", "nbr", "nbc", "M_pad",
-                                      "K_pad", "T", "chunk_tiles", "wg_waves", "nchunks")}
+                                      "K_pad", "T", "chunk_tiles", "wg_waves", "row_slices", "nchunks")}
     out["row_ptr"] = arr(v.row_ptr, v.nbr + 1, np.int32)
     out["col_idx"] = arr(v.col_idx, v.T, np.int32)
     out["vals"] = arr(v.vals, v.T * v.bh * v.bw, wd)

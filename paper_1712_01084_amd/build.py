@@ -16,7 +16,8 @@ CSRC = os.path.join(HERE, "csrc")
 OBJDIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libpivotfc.so")
 
-SOURCES = ["pivot_plan.cpp", "pivot_api.cpp", "pivot_kernels.hip"]
+SOURCES = ["pivot_gemv_f32.hip", "pivot_gemv_f16.hip", "pivot_mfma_f16.hip", "pivot_misc.hip", "pivot_launch.hip",
+           "pivot_plan.cpp", "pivot_api.cpp"]
 
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"), "-I", CSRC,
           "-Wall", "-Wno-unused-function"]
@@ -43,7 +44,7 @@ def _compile(src):
 
 def build(verbose=False):
     os.makedirs(OBJDIR, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=4) as ex:
+    with ThreadPoolExecutor(max_workers=7) as ex:
         results = list(ex.map(_compile, SOURCES))
     if verbose:
         for _, out in results:

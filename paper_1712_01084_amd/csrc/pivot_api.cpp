@@ -47,6 +47,8 @@ int upload(pivot_fc_plan_t* p) {
     } catch (const std::bad_alloc&) { set_error("out of host memory"); return PIVOT_E_ALLOC; }
     for (int t = 0; t < h.T; ++t)
         for (int c = 0; c < h.d.bw; ++c) xblk[(size_t)t * h.d.bw + c] = h.col_idx[t] * h.d.bw + c;
+    std::vector<int32_t> rowid(h.M_pad, -1);
+    for (int r = 0; r < h.d.M; ++r) rowid[r] = r;
     Piece pieces[] = {
         {h.vals.data(),      h.vals.size(),                 (void**)&d.vals},
         {h.col_idx.data(),   h.col_idx.size() * 4,          (void**)&d.col_idx},
@@ -59,9 +61,13 @@ int upload(pivot_fc_plan_t* p) {
         {h.invpcol.data(),   h.invpcol.size() * 4,          (void**)&d.invpcol},
         {h.xidx.data(),      h.xidx.size() * 4,             (void**)&d.xidx},
         {xblk.data(),        xblk.size() * 4,               (void**)&d.xidx_blk},
+        {rowid.data(),       rowid.size() * 4,              (void**)&d.rowid_pad},
     };
     size_t total = 0;
-    for (auto& pc : pieces) total += align_up(pc.bytes + 16, 256);   // +16: vector loads of the last tile stay inside
+    // every array is followed by zeroed padding: 16 KB after the tile values (clamped
+    // vector loads of an empty or last work item stay inside), 16 bytes after the others
+    auto padded = [&](const Piece& pc) { return align_up(pc.bytes + (pc.src == (const void*)h.vals.data() ? kValsPadBytes : 16), 256); };
+    for (auto& pc : pieces) total += padded(pc);
     DeviceGuard g(p->device);
     if (!g.ok) { set_error("cannot select device %d", p->device); return PIVOT_E_HIP; }
     void* base = nullptr;
@@ -69,6 +75,8 @@ int upload(pivot_fc_plan_t* p) {
     if (e != hipSuccess) { set_error("hipMalloc(%zu) failed: %s", total, hipGetErrorString(e)); return PIVOT_E_ALLOC; }
     d.base = (char*)base;
     d.bytes = total;
+    e = hipMemset(base, 0, total);
+    if (e != hipSuccess) { set_error("hipMemset failed: %s", hipGetErrorString(e)); (void)hipFree(base); d = DevPlan{}; return PIVOT_E_HIP; }
     size_t off = 0;
     for (auto& pc : pieces) {
         *pc.dst = d.base + off;
@@ -81,7 +89,7 @@ int upload(pivot_fc_plan_t* p) {
                 return PIVOT_E_HIP;
             }
         }
-        off += align_up(pc.bytes + 16, 256);
+        off += padded(pc);
     }
     return PIVOT_OK;
 }
@@ -121,7 +129,7 @@ int pivot_fc_plan_host_view(const pivot_fc_plan_t* plan, pivot_plan_view* v) {
     v->M = h.d.M; v->K = h.d.K; v->bh = h.d.bh; v->bw = h.d.bw; v->wdtype = h.d.wdtype;
     v->layout = h.d.layout; v->act = h.d.act;
     v->nbr = h.nbr; v->nbc = h.nbc; v->M_pad = h.M_pad; v->K_pad = h.K_pad; v->T = h.T;
-    v->chunk_tiles = h.chunk_tiles; v->wg_waves = h.wg_waves; v->nchunks = h.nchunks;
+    v->chunk_tiles = h.chunk_tiles; v->wg_waves = h.wg_waves; v->row_slices = h.row_slices; v->nchunks = h.nchunks;
     v->row_ptr = h.row_ptr.data(); v->col_idx = h.col_idx.data(); v->vals = h.vals.data();
     v->bias_p = h.bias_p.data(); v->invprow = h.invprow.data(); v->invpcol = h.invpcol.data();
     v->prow_pad = h.prow_pad.data(); v->pcol_pad = h.pcol_pad.data();
@@ -161,7 +169,7 @@ void pivot_fc_plan_destroy(pivot_fc_plan_t* plan) {
 
 size_t pivot_fc_workspace_bytes(const pivot_fc_plan_t* plan, int batch) {
     if (!plan || batch < 1) return 0;
-    return fc_workspace_bytes(plan->host, batch);
+    return fc_workspace_bytes(plan->host, batch) + fc_gather_bytes(plan->host, batch);
 }
 
 int pivot_workspace_init(void* ws_dev, size_t ws_bytes, void* stream) {
@@ -173,7 +181,8 @@ int pivot_workspace_init(void* ws_dev, size_t ws_bytes, void* stream) {
 
 namespace {
 
-// Fills the plan-dependent part of a launch and carves the workspace.
+// Fills the plan-dependent part of a launch and carves the workspace
+// ([arrival counters][partials]; `ws_bytes` must cover fc_workspace_bytes).
 int prepare(const pivot_fc_plan_t* plan, int batch, void* ws, size_t ws_bytes, FcLaunch& L) {
     if (!plan) { set_error("plan is NULL"); return PIVOT_E_NULL; }
     if (plan->device < 0) { set_error("host-only plan (device = -1) cannot run"); return PIVOT_E_NO_DEVICE; }
@@ -186,11 +195,28 @@ int prepare(const pivot_fc_plan_t* plan, int batch, void* ws, size_t ws_bytes, F
     L.vals = d.vals; L.col_idx = d.col_idx; L.chunks = d.chunks; L.part_base = d.part_base; L.bias_p = d.bias_p;
     L.M_pad = h.M_pad; L.K_pad = h.K_pad; L.bh = h.d.bh; L.bw = h.d.bw; L.wdtype = h.d.wdtype; L.act = h.d.act;
     L.nchunks = h.nchunks; L.nbr = h.nbr; L.chunk_tiles = h.chunk_tiles; L.wg_waves = h.wg_waves;
+    L.row_slices = h.row_slices;
     L.batch = batch;
     int nbt = fc_batch_tile(h.d.wdtype, h.d.bh, h.d.bw, batch);
     int ngy = (batch + nbt - 1) / nbt;
     L.tickets = reinterpret_cast<uint32_t*>(ws);
-    L.partials = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + align_up((size_t)4 * h.nbr * ngy, 256));
+    L.partials = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + fc_ticket_bytes(h.nbr, ngy, h.row_slices));
+    return PIVOT_OK;
+}
+
+// Input side of a launch whose x is in natural order: the vector kernel
+// gathers through the composed index array; the matrix-core kernel wants block
+// order, so x is copied there first (`xg`: fc_gather_bytes of scratch).
+int natural_input(const pivot_fc_plan_t* plan, const void* x_dev, int64_t ldx, int batch, void* xg, void* stream,
+                  FcLaunch& L) {
+    const HostPlan& h = plan->host;
+    if (fc_uses_matrix_cores(h.d.wdtype, h.d.bh, h.d.bw, batch)) {
+        int rc = launch_gather_x(x_dev, ldx, plan->dev.pcol_pad, xg, h.K_pad, batch, h.d.wdtype, stream);
+        if (rc != PIVOT_OK) return rc;
+        L.x = xg; L.ldx = h.K_pad; L.xidx = plan->dev.xidx_blk; L.x_block_order = 1;
+    } else {
+        L.x = x_dev; L.ldx = ldx; L.xidx = plan->dev.xidx; L.x_block_order = 0;
+    }
     return PIVOT_OK;
 }
 
@@ -205,10 +231,12 @@ int pivot_fc_run(const pivot_fc_plan_t* plan, const void* x_dev, int64_t ldx, vo
     if (rc != PIVOT_OK) return rc;
     if (!x_dev || !y_dev) { set_error("x_dev and y_dev are required"); return PIVOT_E_NULL; }
     if (ldx < plan->host.d.K || ldy < plan->host.d.M) { set_error("ldx/ldy smaller than K/M"); return PIVOT_E_SHAPE; }
-    L.xidx = plan->dev.xidx;
+    const size_t base = fc_workspace_bytes(plan->host, batch);
+    if (ws_bytes < base + fc_gather_bytes(plan->host, batch)) { set_error("workspace too small: need %zu bytes", base + fc_gather_bytes(plan->host, batch)); return PIVOT_E_WORKSPACE; }
+    rc = natural_input(plan, x_dev, ldx, batch, reinterpret_cast<char*>(ws_dev) + base, stream, L);
+    if (rc != PIVOT_OK) return rc;
     L.scatter = plan->dev.prow_pad;
-    L.out_rows = plan->host.d.M;
-    L.x = x_dev; L.ldx = ldx; L.y = y_dev; L.ldy = ldy; L.out_f16 = 0; L.stream = stream;
+    L.y = y_dev; L.ldy = ldy; L.out_f16 = 0; L.stream = stream;
     return launch_fc(L);
 }
 
@@ -300,15 +328,17 @@ void pivot_mlp_plan_destroy(pivot_mlp_plan_t* plan) {
 
 namespace {
 
-// Workspace of a chain: [layer scratch (largest)] [intermediate 0] [intermediate 1] ...
+// Workspace of a chain: [layer scratch (largest)] [block-order copy of x (matrix path)] [intermediate 0] ...
 // Intermediate l holds batch rows of K_pad_{l+1} elements of wdtype in the
 // consumer's block order; its padding columns stay zero from pivot_workspace_init.
-struct MlpLayout { size_t scratch, total; std::vector<size_t> inter_off; };
+struct MlpLayout { size_t scratch, gather_off, total; std::vector<size_t> inter_off; };
 
 MlpLayout mlp_layout(const pivot_mlp_plan_t* mp, int batch) {
-    MlpLayout m{0, 0, {}};
+    MlpLayout m{0, 0, 0, {}};
     for (auto* l : mp->layers) m.scratch = std::max(m.scratch, fc_workspace_bytes(l->host, batch));
     m.scratch = align_up(m.scratch, 256);
+    m.gather_off = m.scratch;
+    m.scratch += fc_gather_bytes(mp->layers[0]->host, batch);
     size_t off = m.scratch;
     for (size_t l = 0; l + 1 < mp->layers.size(); ++l) {
         m.inter_off.push_back(off);
@@ -343,21 +373,23 @@ int pivot_mlp_run(const pivot_mlp_plan_t* plan, const void* x_dev, int64_t ldx, 
     for (int l = 0; l < Lc; ++l) {
         const pivot_fc_plan_t* p = plan->layers[l];
         FcLaunch L{};
-        int rc = prepare(p, batch, ws, m.scratch, L);
+        int rc = prepare(p, batch, ws, m.gather_off, L);
         if (rc != PIVOT_OK) return rc;
         L.stream = stream;
-        if (l == 0) { L.xidx = p->dev.xidx; L.x = x_dev; L.ldx = ldx; }
-        else        { L.xidx = p->dev.xidx_blk; L.x = ws + m.inter_off[l - 1]; L.ldx = p->host.K_pad; }
+        if (l == 0) {
+            rc = natural_input(p, x_dev, ldx, batch, ws + m.gather_off, stream, L);
+            if (rc != PIVOT_OK) return rc;
+        } else {
+            L.xidx = p->dev.xidx_blk; L.x = ws + m.inter_off[l - 1]; L.ldx = p->host.K_pad; L.x_block_order = 1;
+        }
         if (l + 1 < Lc) {
             // producer-side store through the composed boundary array; identity boundaries store contiguously
-            L.scatter = plan->identity[l] ? nullptr : plan->dst_dev[l];
-            L.out_rows = p->host.d.M;
+            L.scatter = plan->identity[l] ? p->dev.rowid_pad : plan->dst_dev[l];
             L.y = ws + m.inter_off[l];
             L.ldy = plan->layers[l + 1]->host.K_pad;
             L.out_f16 = (p->host.d.wdtype == PIVOT_F16);
         } else {
-            L.scatter = keep ? nullptr : p->dev.prow_pad;
-            L.out_rows = keep ? p->host.M_pad : p->host.d.M;
+            L.scatter = keep ? p->dev.rowid_pad : p->dev.prow_pad;
             L.y = y_dev; L.ldy = ldy; L.out_f16 = 0;
         }
         rc = launch_fc(L);
@@ -425,9 +457,9 @@ int pivot_lstm_run(const pivot_fc_plan_t* plan, int H, int I, const void* xs_dev
         FcLaunch L{};
         rc = prepare(plan, batch, ws, m.scratch, L);
         if (rc != PIVOT_OK) return rc;
-        L.xidx = plan->dev.xidx_blk;
+        L.xidx = plan->dev.xidx_blk; L.x_block_order = 1;
         L.x = xg + m.xg_step * (size_t)t; L.ldx = h.K_pad;
-        L.scatter = nullptr; L.out_rows = h.M_pad;
+        L.scatter = plan->dev.rowid_pad;
         L.y = z; L.ldy = h.M_pad; L.out_f16 = 0; L.stream = stream;
         if ((rc = launch_fc(L)) != PIVOT_OK) return rc;
         LstmCellLaunch C{};

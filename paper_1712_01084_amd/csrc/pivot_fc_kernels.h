@@ -1,0 +1,465 @@
+// Device templates of the pruned-layer kernels for gfx950 (paper Eq. 2 and
+// Listing 1, generalised per Section 4.1.5 to tiles that share block rows).
+//
+// One workgroup ("work item") handles one chunk of the schedule: up to
+// chunk_tiles consecutive kept tiles of one block row, and within them one row
+// slice (blockIdx.z) of every tile.  The steps of Listing 1 map as follows:
+//   group fetch through P_col  -> the chunk's x-segments are gathered into LDS
+//                                 (vector kernel) or read as MFMA B fragments
+//                                 from an x already in block order (matrix kernel)
+//   block row dot products     -> 16-byte-per-lane coalesced stream of the BRC
+//                                 tile values, FMA / dot2 (batch <= 4) or MFMA
+//   (Section 4.1.5) reduction  -> lanes (DPP), waves (LDS), chunks of a split
+//                                 block row (fixed-order sum by the last
+//                                 workgroup to arrive)
+//   group store through P_row  -> bias, activation, scatter
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "pivot_device.h"
+#include "pivot_internal.h"
+
+namespace pivot {
+
+#define HIP_TRY(expr)                                                                  \
+    do {                                                                               \
+        hipError_t e_ = (expr);                                                        \
+        if (e_ != hipSuccess) {                                                        \
+            set_error("%s failed: %s", #expr, hipGetErrorString(e_));                  \
+            return PIVOT_E_HIP;                                                        \
+        }                                                                              \
+    } while (0)
+
+static constexpr int kTicketStride = 64;   // uint32 words between arrival counters (one per 256-byte line)
+
+// Arguments of the layer kernels (passed by value).
+struct FcArgs {
+    const void*    vals;
+    const int32_t* col_idx;     // [T] block column of every kept tile (matrix kernel)
+    const int32_t* xidx;        // [T*bw] index into x of every kept tile's columns, -1 = padding (vector kernel)
+    const int4*    chunks;
+    const int32_t* part_base;
+    const float*   bias_p;
+    const int32_t* scatter;     // [M_pad] destination of every block-space row, -1 = not stored
+    const void*    x;
+    void*          y;
+    float*         partials;
+    uint32_t*      tickets;
+    long long ldx, ldy;
+    int batch, act, out_f16, nchunks, nbr, xs_stride;
+    int bh_full;                // rows of a whole tile (the kernels' BH is the height of one row slice)
+    int tile_elems;             // bh_full * bw
+};
+
+// Per-dtype / per-path launchers, each in its own translation unit.
+int launch_gemv_f32(const FcArgs& a, int bhs, int bw, int nb, int nw, dim3 grid, size_t smem, hipStream_t st);
+int launch_gemv_f16(const FcArgs& a, int bhs, int bw, int nb, int nw, dim3 grid, size_t smem, hipStream_t st);
+int launch_mfma_f16(const FcArgs& a, int kind, int bhs, int bw, int nw, dim3 grid, size_t smem, hipStream_t st);
+
+#define PIVOT_SHAPES(X) \
+    X(8, 8) X(8, 16) X(8, 32) X(8, 64) \
+    X(16, 8) X(16, 16) X(16, 32) X(16, 64) \
+    X(32, 8) X(32, 16) X(32, 32) X(32, 64) \
+    X(64, 8) X(64, 16) X(64, 32) X(64, 64)
+
+template <typename WT> struct Elem;
+template <> struct Elem<float>    { using vec = f32x4; static constexpr int VEC = 4; };
+template <> struct Elem<_Float16> { using vec = f16x8; static constexpr int VEC = 8; };
+
+__device__ __forceinline__ float dot_vec(const f32x4& w, const f32x4& x, float acc) {
+    acc = fmaf(w.x, x.x, acc);
+    acc = fmaf(w.y, x.y, acc);
+    acc = fmaf(w.z, x.z, acc);
+    acc = fmaf(w.w, x.w, acc);
+    return acc;
+}
+__device__ __forceinline__ float dot_vec(const f16x8& w, const f16x8& x, float acc) {
+    // fp16 products are exact in fp32; v_dot2_f32_f16 accumulates in fp32.
+    acc = __builtin_amdgcn_fdot2(f16x2{w[0], w[1]}, f16x2{x[0], x[1]}, acc, false);
+    acc = __builtin_amdgcn_fdot2(f16x2{w[2], w[3]}, f16x2{x[2], x[3]}, acc, false);
+    acc = __builtin_amdgcn_fdot2(f16x2{w[4], w[5]}, f16x2{x[4], x[5]}, acc, false);
+    acc = __builtin_amdgcn_fdot2(f16x2{w[6], w[7]}, f16x2{x[6], x[7]}, acc, false);
+    return acc;
+}
+
+__device__ __forceinline__ void store_out(void* y, long long idx, float v, int out_f16) {
+    if (out_f16) reinterpret_cast<_Float16*>(y)[idx] = (_Float16)v;
+    else         reinterpret_cast<float*>(y)[idx] = v;
+}
+
+// Per-thread values that depend only on the block row, loaded at kernel start
+// so that their latency overlaps the weight stream instead of following it:
+// the bias and the destination index of every output this thread will finish
+// (outputs idx = tid + k*NT, idx = j*BH + r).  The loads are unconditional (the
+// row is always inside the padded block row), so no branch hides them from the
+// compiler's count of outstanding loads.
+template <int BH, int N, int NT>
+struct RowPre {
+    static constexpr int CNT = (N + NT - 1) / NT;
+    float bias[CNT];
+    int   dst[CNT];
+    __device__ __forceinline__ void load(const FcArgs& a, int row0, int tid) {
+        #pragma unroll
+        for (int k = 0; k < CNT; ++k) {
+            const int row = row0 + (tid + k * NT) % BH;
+            bias[k] = a.bias_p[row];
+            dst[k] = a.scatter[row];
+        }
+    }
+};
+
+// Staging of the chunk's x-segments in LDS (Listing 1: the group fetch through
+// P_col): xs[b][t*BW + c] = x[b][xidx[(tile_begin + t)*BW + c]].  xidx is the
+// column index array already composed with the tile list, so one index load
+// feeds the gather.  Index -1 (padding column) and batch rows past `batch`
+// read as zero.  NB consecutive threads share one column and take one batch
+// row each.  The first XP indices per thread are fetched before the weight
+// stream is issued (loads return in order: an index fetched after the weights
+// would only arrive after them).  All of these loads and LDS writes are
+// unconditional: out-of-range elements use a clamped index and land in a dump
+// slot at the end of the LDS row.
+template <typename WT, int BW, int NB, int NT>
+struct XStage {
+    static constexpr int XP = 4;
+    static constexpr int STEP = NT / NB;
+    int src[XP];
+    __device__ __forceinline__ void load_idx(const FcArgs& a, int tile_begin, int ne, int tid) {
+        const int32_t* xi = a.xidx + (size_t)tile_begin * BW;
+        const int emax = ne > 0 ? ne - 1 : 0;       // index arrays carry 16 bytes of padding: xi[0] is readable
+        #pragma unroll
+        for (int k = 0; k < XP; ++k) {
+            const int e = tid / NB + k * STEP;
+            src[k] = xi[e < emax ? e : emax];
+        }
+    }
+    __device__ __forceinline__ void gather(const FcArgs& a, WT* xs, int tile_begin, int ne, int b0, int tid) {
+        const int b = tid % NB;
+        const bool row_ok = (b0 + b) < a.batch;
+        const WT* xrow = reinterpret_cast<const WT*>(a.x) + (long long)(row_ok ? b0 + b : 0) * a.ldx;
+        WT* xsrow = xs + b * a.xs_stride;
+        const int dump = a.xs_stride - 1;
+        WT v[XP];
+        #pragma unroll
+        for (int k = 0; k < XP; ++k) v[k] = xrow[src[k] > 0 ? src[k] : 0];
+        #pragma unroll
+        for (int k = 0; k < XP; ++k) {
+            const int e = tid / NB + k * STEP;
+            xsrow[e < ne ? e : dump] = (src[k] >= 0 && row_ok) ? v[k] : WT(0);
+        }
+        const int32_t* xi = a.xidx + (size_t)tile_begin * BW;
+        for (int e = tid / NB + XP * STEP; e < ne; e += STEP) {
+            const int sidx = xi[e];
+            WT vv = WT(0);
+            if (sidx >= 0 && row_ok) vv = xrow[sidx];
+            xsrow[e] = vv;
+        }
+    }
+};
+
+// Everything after the per-wave sums are in LDS `red[w*N + idx]`, idx = j*BH + r
+// (j = batch column of this launch tile, r = row inside the row slice):
+// hand-over between the chunks of a split block row (Section 4.1.5: tiles that
+// share rows need one more reduction), bias, activation, store through P_row.
+template <int BH, int NBT, int NT>
+__device__ __forceinline__ void finish_rows(const FcArgs& a, const float* red, int nred, int br, int slot,
+                                            int first, int nparts, const RowPre<BH, BH * NBT, NT>& rp,
+                                            int b0, int tid, int* s_flag) {
+    constexpr int N = BH * NBT;
+    const int gy = blockIdx.y, slice = blockIdx.z, SL = gridDim.z;
+    if (nparts > 1) {
+        float* mine = a.partials + (((size_t)gy * a.nchunks + slot) * SL + slice) * N;
+        for (int idx = tid; idx < N; idx += NT) {
+            float s = 0.f;
+            for (int w = 0; w < nred; ++w) s += red[w * N + idx];
+            agent_store(mine + idx, s);
+        }
+        // Hand-over without a device-wide fence.  The partials are written with
+        // device-coherent (write-through) stores and read back with device-coherent
+        // loads, so no cache write-back or invalidate is needed; all that has to
+        // hold is that every store of this workgroup has completed before its
+        // arrival is counted.  A release fence at device scope would write back the
+        // whole L2 of the XCD for every workgroup and serialise the launch.
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (tid == 0) {
+            // one counter per 256-byte line: counters of different rows never share a line
+            uint32_t* tk = a.tickets + (((size_t)gy * a.nbr + br) * SL + slice) * kTicketStride;
+            uint32_t prev = __hip_atomic_fetch_add(tk, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            int last = (prev == (uint32_t)(nparts - 1));
+            if (last) __hip_atomic_store(tk, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            *s_flag = last;
+        }
+        __syncthreads();
+        if (!*s_flag) return;
+    }
+    #pragma unroll
+    for (int k = 0; k < RowPre<BH, N, NT>::CNT; ++k) {
+        const int idx = tid + k * NT;
+        if (idx >= N) break;
+        const int j = idx / BH;
+        if (b0 + j >= a.batch) continue;
+        float s = 0.f;
+        if (nparts > 1) {
+            const float* p = a.partials + (((size_t)gy * a.nchunks + first) * SL + slice) * N + idx;
+            for (int q = 0; q < nparts; ++q) s += agent_load(p + (size_t)q * SL * N);
+        } else {
+            for (int w = 0; w < nred; ++w) s += red[w * N + idx];
+        }
+        const float v = apply_act(s + rp.bias[k], a.act);
+        if (rp.dst[k] >= 0) store_out(a.y, (long long)(b0 + j) * a.ldy + rp.dst[k], v, a.out_f16);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// batch 1..4: vector-ALU kernel.  BH is the height of the row slice.  Lane l
+// of a wave reads bytes [16 l, 16 l+16) of each 1 KB piece of the slice's tile
+// stream, i.e. VEC columns of one tile row; LPR lanes cover a row, a wave
+// covers RPW rows per load.
+// ---------------------------------------------------------------------------
+template <typename WT, int BH, int BW, int NB, int NW>
+__global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(FcArgs a) {
+    using V = typename Elem<WT>::vec;
+    constexpr int VEC = Elem<WT>::VEC;
+    constexpr int NT  = NW * 64;
+    constexpr int LPR = BW / VEC;                       // lanes per tile row
+    constexpr int RPW = 64 / LPR;                       // tile rows per wave-load
+    constexpr int NL  = (BH >= RPW) ? BH / RPW : 1;     // wave-loads per tile
+    constexpr int TPL = (BH >= RPW) ? 1 : RPW / BH;     // tiles per wave-load (only with a single slice)
+    constexpr int U   = (NL >= 8) ? 1 : 8 / NL;         // groups in flight per wave
+    constexpr int N   = BH * NB;
+    static_assert(BW >= VEC && LPR <= 64, "tile width not supported");
+
+    extern __shared__ __align__(16) char smem[];
+    __shared__ int s_flag;
+    WT* xs = reinterpret_cast<WT*>(smem);
+    float* red = reinterpret_cast<float*>(smem);        // reused after the stream phase
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int b0 = blockIdx.y * NB, slice = blockIdx.z;
+    const int4 cd = a.chunks[blockIdx.x];
+    const int br = cd.x, tile_begin = cd.y, ntiles = cd.z - cd.y, slot = cd.w;
+    const int ngroups = (ntiles + TPL - 1) / TPL;
+    const int first = a.part_base[br];
+    const int nparts = a.part_base[br + 1] - first;
+    const int row0 = br * a.bh_full + slice * BH;
+
+    // order of issue = order of arrival: gather indices, epilogue operands, then the weights
+    XStage<WT, BW, NB, NT> xst;
+    xst.load_idx(a, tile_begin, ntiles * BW, tid);
+    RowPre<BH, N, NT> rp;
+    rp.load(a, row0, tid);
+
+    const int s  = lane / LPR;                          // row within the wave-load
+    const int cg = lane % LPR;                          // column group
+    const int ts = (TPL > 1) ? s / BH : 0;              // tile within the group
+    const size_t gstride = (size_t)TPL * a.tile_elems;  // elements between groups of tiles
+    const WT* vbase = reinterpret_cast<const WT*>(a.vals) + (size_t)tile_begin * a.tile_elems
+                      + (size_t)slice * BH * BW + lane * VEC;
+
+    // Loads are unconditional (group index clamped; the value array is padded by
+    // one group of zeros, so even an empty chunk reads valid memory): no branch
+    // sits between the loads and the compiler can wait for exactly the ones it needs.
+    const int gmax = ngroups > 0 ? ngroups - 1 : 0;
+    V w[U][NL];
+    auto issue = [&](int g0) {
+        #pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int g = g0 + u * NW;
+            const int gc = g < gmax ? g : gmax;
+            #pragma unroll
+            for (int j = 0; j < NL; ++j) w[u][j] = load16<V>(vbase + gc * gstride + j * 64 * VEC);
+        }
+    };
+
+    issue(wave);
+    xst.gather(a, xs, tile_begin, ntiles * BW, b0, tid);
+    lds_barrier();
+
+    float acc[NL][NB];
+    #pragma unroll
+    for (int j = 0; j < NL; ++j)
+        #pragma unroll
+        for (int b = 0; b < NB; ++b) acc[j][b] = 0.f;
+
+    for (int g0 = wave; g0 < ngroups; g0 += NW * U) {
+        #pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int g = g0 + u * NW;
+            const int tl = g * TPL + ts;
+            if (g < ngroups && tl < ntiles) {
+                #pragma unroll
+                for (int b = 0; b < NB; ++b) {
+                    const V xv = *reinterpret_cast<const V*>(xs + b * a.xs_stride + tl * BW + cg * VEC);
+                    #pragma unroll
+                    for (int j = 0; j < NL; ++j) acc[j][b] = dot_vec(w[u][j], xv, acc[j][b]);
+                }
+            }
+        }
+        if (g0 + NW * U < ngroups) issue(g0 + NW * U);
+    }
+
+    // lanes -> rows
+    #pragma unroll
+    for (int j = 0; j < NL; ++j)
+        #pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            float v = group_sum<LPR>(acc[j][b]);
+            if constexpr (TPL > 1) v = stride_sum<BH * LPR>(v);
+            acc[j][b] = v;
+        }
+
+    __syncthreads();                                    // xs no longer needed; red aliases it
+    if (cg == 0 && (TPL == 1 || s < BH)) {
+        #pragma unroll
+        for (int j = 0; j < NL; ++j) {
+            const int r = (TPL > 1) ? s : j * RPW + s;
+            #pragma unroll
+            for (int b = 0; b < NB; ++b) red[wave * N + b * BH + r] = acc[j][b];
+        }
+    }
+    __syncthreads();
+    finish_rows<BH, NB, NT>(a, red, NW, br, slot, first, nparts, rp, b0, tid, &s_flag);
+}
+
+// ---------------------------------------------------------------------------
+// batch >= 8, fp16 weights: matrix-core kernels.  The tile is the A operand,
+// the x-segment (k x batch) the B operand, accumulation in fp32.  x must be in
+// block order already ([batch][K_pad], produced by the previous layer's store,
+// by the recurrent cell, or by gather_x_kernel): lane l reads its B fragment,
+// 8 consecutive k of one batch row, with one 16-byte load, no LDS staging.
+// KIND 0: v_mfma_f32_16x16x32_f16, slices with BH % 16 == 0, BW % 32 == 0, 16 batch columns.
+//         lane l supplies A[row l%16][k 8(l/16)..+7] = 16 contiguous bytes of a BRC tile row.
+// KIND 1: v_mfma_f32_32x32x16_f16, slices with BH % 32 == 0, BW % 16 == 0, 32 batch columns.
+//         lane l supplies A[row l%32][k 8(l/32)..+7].
+// Batch columns past `batch` read row batch-1 again; their results are never stored.
+// ---------------------------------------------------------------------------
+template <int KIND> struct Mfma;
+template <> struct Mfma<0> {
+    static constexpr int MR = 16, MK = 32, NBT = 16, CV = 4;
+    using acc_t = f32x4;
+    __device__ static __forceinline__ acc_t run(f16x8 a, f16x8 b, acc_t c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+    }
+    // accumulator element v of lane l is C[row][col = l % 16]
+    __device__ static __forceinline__ int row_of(int lane, int v) { return 4 * (lane / 16) + v; }
+};
+template <> struct Mfma<1> {
+    static constexpr int MR = 32, MK = 16, NBT = 32, CV = 16;
+    using acc_t = f32x16;
+    __device__ static __forceinline__ acc_t run(f16x8 a, f16x8 b, acc_t c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+    }
+    __device__ static __forceinline__ int row_of(int lane, int v) { return 8 * (v / 4) + 4 * (lane / 32) + (v % 4); }
+};
+
+template <int KIND, int BH, int BW, int NW>
+__global__ void __launch_bounds__(NW * 64) fc_mfma_kernel(FcArgs a) {
+    using MF = Mfma<KIND>;
+    using acc_t = typename MF::acc_t;
+    constexpr int MR = MF::MR, MK = MF::MK, NBT = MF::NBT, CV = MF::CV;
+    constexpr int NT = NW * 64;
+    constexpr int RB = BH / MR;                         // row blocks per tile slice
+    constexpr int KS = BW / MK;                         // k steps per tile
+    constexpr int LT = RB * KS;                         // 16-byte weight loads per lane per tile
+    constexpr int U  = (LT >= 8) ? 1 : 8 / LT;          // tiles in flight per wave
+    constexpr int N  = BH * NBT;
+    constexpr int RW = NW < 4 ? NW : 4;                 // waves that hold the sums at the end
+    static_assert(BH % MR == 0 && BW % MK == 0, "tile shape does not fit this MFMA");
+
+    extern __shared__ __align__(16) char smem[];
+    __shared__ int s_flag;
+    float* red = reinterpret_cast<float*>(smem);        // RW * N floats
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int b0 = blockIdx.y * NBT, slice = blockIdx.z;
+    const int4 cd = a.chunks[blockIdx.x];
+    const int br = cd.x, tile_begin = cd.y, ntiles = cd.z - cd.y, slot = cd.w;
+    const int first = a.part_base[br];
+    const int nparts = a.part_base[br + 1] - first;
+    const int row0 = br * a.bh_full + slice * BH;
+
+    RowPre<BH, N, NT> rp;
+    rp.load(a, row0, tid);
+
+    const int li = lane % MR;                           // A row / B column of this lane
+    const int lg = lane / MR;                           // k group of 8
+    const _Float16* vbase = reinterpret_cast<const _Float16*>(a.vals) + (size_t)tile_begin * a.tile_elems
+                            + (size_t)slice * BH * BW + li * BW + lg * 8;
+    const int brow = (b0 + li < a.batch) ? b0 + li : a.batch - 1;
+    const _Float16* xb = reinterpret_cast<const _Float16*>(a.x) + (long long)brow * a.ldx + lg * 8;
+    const int32_t* ci_base = a.col_idx + tile_begin;    // wave-uniform: scalar loads, their own counter
+
+    const int tmax = ntiles > 0 ? ntiles - 1 : 0;       // clamped, unconditional loads (see fc_gemv_kernel)
+    f16x8 w[U][LT];
+    f16x8 xv[U][KS];
+    auto issue = [&](int t0) {
+        int ci[U];
+        #pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int t = t0 + u * NW;
+            ci[u] = ci_base[t < tmax ? t : tmax];
+        }
+        #pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int t = t0 + u * NW;
+            const int tc = t < tmax ? t : tmax;
+            #pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+                #pragma unroll
+                for (int ks = 0; ks < KS; ++ks)
+                    w[u][rb * KS + ks] = load16<f16x8>(vbase + (size_t)tc * a.tile_elems + rb * MR * BW + ks * MK);
+        }
+        #pragma unroll
+        for (int u = 0; u < U; ++u)
+            #pragma unroll
+            for (int ks = 0; ks < KS; ++ks) xv[u][ks] = load16<f16x8>(xb + (size_t)ci[u] * BW + ks * MK);
+    };
+
+    acc_t acc[RB];
+    #pragma unroll
+    for (int rb = 0; rb < RB; ++rb) acc[rb] = acc_t(0);
+
+    if (wave < ntiles) issue(wave);
+    for (int t0 = wave; t0 < ntiles; t0 += NW * U) {
+        #pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (t0 + u * NW < ntiles) {
+                #pragma unroll
+                for (int ks = 0; ks < KS; ++ks)
+                    #pragma unroll
+                    for (int rb = 0; rb < RB; ++rb) acc[rb] = MF::run(w[u][rb * KS + ks], xv[u][ks], acc[rb]);
+            }
+        }
+        if (t0 + NW * U < ntiles) issue(t0 + NW * U);
+    }
+
+    // waves -> one sum: rounds of (up to) 4 writers into a 4-slot LDS buffer
+    auto put = [&](int w_slot) {
+        #pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+            #pragma unroll
+            for (int v = 0; v < CV; ++v)
+                red[w_slot * N + li * BH + rb * MR + MF::row_of(lane, v)] = acc[rb][v];
+    };
+    #pragma unroll
+    for (int base = RW; base < NW; base += RW) {
+        if (wave >= base && wave < base + RW) put(wave - base);
+        __syncthreads();
+        if (wave < RW) {
+            #pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+                #pragma unroll
+                for (int v = 0; v < CV; ++v)
+                    acc[rb][v] += red[wave * N + li * BH + rb * MR + MF::row_of(lane, v)];
+        }
+        __syncthreads();
+    }
+    if (wave < RW) put(wave);
+    __syncthreads();
+    finish_rows<BH, NBT, NT>(a, red, RW, br, slot, first, nparts, rp, b0, tid, &s_flag);
+}
+
+}  // namespace pivot

@@ -15,11 +15,14 @@ void set_error(const char* fmt, ...);
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline int    elem_size(int wdtype) { return wdtype == PIVOT_F32 ? 4 : 2; }
+// Zero bytes kept after the tile values on the device: kernels issue clamped,
+// unconditional loads of up to one group of tiles (at most 64x64 fp32).
+constexpr size_t kValsPadBytes = 16 * 1024;
 
 // Host-side canonical arrays of one layer (what pivot_plan_view exposes).
 struct HostPlan {
     pivot_fc_desc d{};
-    int nbr = 0, nbc = 0, M_pad = 0, K_pad = 0, T = 0, chunk_tiles = 0, nchunks = 0, wg_waves = 4;
+    int nbr = 0, nbc = 0, M_pad = 0, K_pad = 0, T = 0, chunk_tiles = 0, nchunks = 0, wg_waves = 4, row_slices = 1;
     int max_parts = 1;                 // largest number of pieces of one block row
     std::vector<int32_t> row_ptr, col_idx, invprow, invpcol, prow_pad, pcol_pad;
     std::vector<int32_t> xidx;         // T*bw: xidx[t*bw+c] = pcol_pad[col_idx[t]*bw+c]
@@ -44,6 +47,7 @@ struct DevPlan {
     int32_t* invpcol = nullptr;
     int32_t* xidx = nullptr;      // gather index for natural-order x
     int32_t* xidx_blk = nullptr;  // same for x already in block order: col_idx[t]*bw+c
+    int32_t* rowid_pad = nullptr; // [M_pad] r for r < M, -1 in padding: stores that stay in block order
 };
 
 // Builds every host array.  Returns PIVOT_OK or an error code (error text set).
@@ -55,12 +59,11 @@ void build_schedule(HostPlan& hp, int chunk_tiles);
 
 // True if the device kernels can run this plan.
 bool device_supported(const pivot_fc_desc& d, std::string* why);
-// Largest chunk (in tiles) whose staged input fits in LDS at the largest batch tile.
+// Largest chunk (in tiles) whose staged input fits in LDS at the largest batch tile of the vector kernel.
 int  max_chunk_tiles(const pivot_fc_desc& d);
-// The library's own choice of chunk size.
-int  choose_chunk_tiles(const HostPlan& hp);
-// The library's own choice of wavefronts per work item (after the schedule is cut).
-int  choose_wg_waves(const HostPlan& hp);
+// The library's own choice of row slices, chunk size and wavefronts per work
+// item; values given in the descriptor (non-zero) are kept.
+void choose_schedule(HostPlan& hp);
 
 // ---- what a kernel launch sees -------------------------------------------
 struct FcLaunch {
@@ -72,9 +75,9 @@ struct FcLaunch {
     const float*   bias_p;
     const int32_t* xidx;        // [T*bw]: index into x of column c of tile t (-1 = padding): through pcol for
                                 // natural-order x, the block-space column itself for x already in block order
-    const int32_t* scatter;     // block-space row -> index into y (-1 = skip); NULL = store in block order (rows < out_rows)
-    int M_pad, K_pad, bh, bw, wdtype, act, nchunks, nbr, chunk_tiles, wg_waves;
-    int out_rows;               // rows stored when scatter == NULL
+    const int32_t* scatter;     // [M_pad] block-space row -> index into y (-1 = padding row, not stored)
+    int M_pad, K_pad, bh, bw, wdtype, act, nchunks, nbr, chunk_tiles, wg_waves, row_slices;
+    int x_block_order;          // 1: x is [batch][K_pad] in block order (what the matrix-core kernel needs)
     // data
     const void* x; int64_t ldx;
     void*       y; int64_t ldy;
@@ -87,8 +90,16 @@ struct FcLaunch {
 
 // Batch rows one launch of the layer kernel covers (grid.y repeats it).
 int    fc_batch_tile(int wdtype, int bh, int bw, int batch);
-size_t fc_workspace_bytes(const HostPlan& hp, int batch);
+bool   fc_uses_matrix_cores(int wdtype, int bh, int bw, int batch);
+int    fc_row_slices(int wdtype, int bh, int bw, int batch, int want);
+// Workspace of one layer application: [arrival counters][partials of split rows][x in block order (matrix path)]
+size_t fc_ticket_bytes(int nbr, int ngy, int slices);
+size_t fc_partial_bytes(const HostPlan& hp, int batch);
+size_t fc_workspace_bytes(const HostPlan& hp, int batch);     // counters + partials
+size_t fc_gather_bytes(const HostPlan& hp, int batch);        // block-order copy of a natural-order x
 int    launch_fc(const FcLaunch& L);
+int    launch_gather_x(const void* x, int64_t ldx, const int32_t* pcol_pad, void* xg, int K_pad, int batch,
+                       int wdtype, void* stream);
 int    launch_fill_zero(void* dev, size_t bytes, void* stream);
 int    launch_null(void* stream);
 int    launch_dense(const void* W, int wdtype, int M, int K, const void* x, int64_t ldx,

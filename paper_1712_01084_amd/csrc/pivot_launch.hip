@@ -1,0 +1,105 @@
+// Chooses the kernel, the row slicing and the launch shape for one layer
+// application and sizes its workspace.
+#include "pivot_fc_kernels.h"
+
+namespace pivot {
+
+static int mfma_kind(int wdtype, int bh, int bw) {
+    if (wdtype != PIVOT_F16) return -1;
+    if (bw % 32 == 0 && bh % 16 == 0) return 0;
+    if (bh % 32 == 0 && bw % 16 == 0) return 1;
+    return -1;
+}
+
+bool fc_uses_matrix_cores(int wdtype, int bh, int bw, int batch) {
+    return batch >= 8 && mfma_kind(wdtype, bh, bw) >= 0;
+}
+
+int fc_batch_tile(int wdtype, int bh, int bw, int batch) {
+    if (fc_uses_matrix_cores(wdtype, bh, bw, batch)) return mfma_kind(wdtype, bh, bw) == 0 ? 16 : 32;
+    return batch >= 3 ? 4 : batch;
+}
+
+// Largest number of row slices <= want that the chosen kernel supports: a
+// slice of the vector kernel must hold at least one 1 KB wave-load and 8 rows,
+// a slice of the matrix kernel whole MFMA row blocks.
+int fc_row_slices(int wdtype, int bh, int bw, int batch, int want) {
+    int sl = want < 1 ? 1 : want;
+    while (sl > 1) {
+        bool ok = (bh % sl == 0);
+        const int bhs = bh / sl;
+        if (ok) {
+            if (fc_uses_matrix_cores(wdtype, bh, bw, batch)) {
+                const int mr = mfma_kind(wdtype, bh, bw) == 0 ? 16 : 32;
+                ok = (bhs % mr == 0);
+            } else {
+                const int vec = 16 / elem_size(wdtype);
+                const int rpw = 64 / (bw / vec > 0 ? bw / vec : 1);
+                ok = bhs >= 8 && bhs >= rpw;
+            }
+        }
+        if (ok) break;
+        sl /= 2;
+    }
+    return sl;
+}
+
+size_t fc_ticket_bytes(int nbr, int ngy, int slices) { return (size_t)4 * kTicketStride * nbr * ngy * slices; }
+
+size_t fc_partial_bytes(const HostPlan& hp, int batch) {
+    if (hp.max_parts <= 1) return 0;
+    const int nbt = fc_batch_tile(hp.d.wdtype, hp.d.bh, hp.d.bw, batch);
+    const int ngy = (batch + nbt - 1) / nbt;
+    return align_up((size_t)4 * hp.nchunks * hp.d.bh * nbt * ngy, 256);
+}
+
+size_t fc_workspace_bytes(const HostPlan& hp, int batch) {
+    if (batch < 1) return 0;
+    const int nbt = fc_batch_tile(hp.d.wdtype, hp.d.bh, hp.d.bw, batch);
+    const int ngy = (batch + nbt - 1) / nbt;
+    // counters are sized for the plan's slice count (a launch may use fewer)
+    return fc_ticket_bytes(hp.nbr, ngy, hp.row_slices) + fc_partial_bytes(hp, batch);
+}
+
+size_t fc_gather_bytes(const HostPlan& hp, int batch) {
+    if (!fc_uses_matrix_cores(hp.d.wdtype, hp.d.bh, hp.d.bw, batch)) return 0;
+    return align_up((size_t)batch * hp.K_pad * elem_size(hp.d.wdtype), 256);
+}
+
+int launch_fc(const FcLaunch& L) {
+    const bool mc = fc_uses_matrix_cores(L.wdtype, L.bh, L.bw, L.batch);
+    const int nbt = fc_batch_tile(L.wdtype, L.bh, L.bw, L.batch);
+    const int ngy = (L.batch + nbt - 1) / nbt;
+    const int sl = fc_row_slices(L.wdtype, L.bh, L.bw, L.batch, L.row_slices);
+    const int bhs = L.bh / sl;
+    const int nw = (L.wg_waves == 16 || L.wg_waves == 8) ? L.wg_waves : 4;
+    const int es = elem_size(L.wdtype);
+
+    FcArgs a;
+    a.vals = L.vals; a.col_idx = L.col_idx; a.xidx = L.xidx; a.chunks = reinterpret_cast<const int4*>(L.chunks);
+    a.part_base = L.part_base; a.bias_p = L.bias_p; a.scatter = L.scatter;
+    a.x = L.x; a.y = L.y; a.partials = L.partials; a.tickets = L.tickets;
+    a.ldx = L.ldx; a.ldy = L.ldy; a.batch = L.batch; a.act = L.act; a.out_f16 = L.out_f16;
+    a.nchunks = L.nchunks; a.nbr = L.nbr;
+    a.bh_full = L.bh; a.tile_elems = L.bh * L.bw;
+    dim3 grid(L.nchunks, ngy, sl);
+    hipStream_t st = reinterpret_cast<hipStream_t>(L.stream);
+
+    if (mc) {
+        if (!L.x_block_order) { set_error("internal: the matrix-core kernel needs x in block order"); return PIVOT_E_UNSUPPORTED; }
+        a.xs_stride = 0;
+        const int rw = nw < 4 ? nw : 4;
+        size_t smem = (size_t)rw * bhs * nbt * 4;
+        return launch_mfma_f16(a, mfma_kind(L.wdtype, L.bh, L.bw), bhs, L.bw, nw, grid, smem, st);
+    }
+    // staged x: nbt rows of chunk_tiles*bw elements, plus 16 bytes whose last element is the dump slot
+    a.xs_stride = L.chunk_tiles * L.bw + 16 / es;
+    size_t xs_bytes = (size_t)nbt * a.xs_stride * es;
+    size_t red_bytes = (size_t)nw * bhs * nbt * 4;
+    size_t smem = align_up(xs_bytes > red_bytes ? xs_bytes : red_bytes, 16);
+    if (smem > 64 * 1024) { set_error("chunk does not fit in LDS (%zu bytes)", smem); return PIVOT_E_UNSUPPORTED; }
+    if (L.wdtype == PIVOT_F32) return launch_gemv_f32(a, bhs, L.bw, nbt, nw, grid, smem, st);
+    return launch_gemv_f16(a, bhs, L.bw, nbt, nw, grid, smem, st);
+}
+
+}  // namespace pivot

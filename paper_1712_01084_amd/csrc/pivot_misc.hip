@@ -1,0 +1,214 @@
+// Utility kernels around the layer kernels: workspace clearing, the empty
+// kernel used to measure the launch floor, the pre-gather of x for the
+// matrix-core path, the dense comparator and the LSTM cell.
+#include "pivot_fc_kernels.h"
+
+namespace pivot {
+
+// ---------------------------------------------------------------------------
+// x in natural order -> block order: xg[b][c] = x[b][pcol_pad[c]] (0 in padding
+// columns).  The matrix-core kernel reads its B fragments from xg; gathering
+// once per launch costs K*batch loads instead of (kept tiles)*bw*batch.
+// ---------------------------------------------------------------------------
+template <typename WT>
+__global__ void gather_x_kernel(const WT* x, long long ldx, const int32_t* pcol_pad, WT* xg, int K_pad, int batch) {
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= K_pad) return;
+    const int src = pcol_pad[c];
+    for (int b = 0; b < batch; ++b)
+        xg[(size_t)b * K_pad + c] = (src >= 0) ? x[(size_t)b * ldx + src] : WT(0);
+}
+
+int launch_gather_x(const void* x, int64_t ldx, const int32_t* pcol_pad, void* xg, int K_pad, int batch,
+                    int wdtype, void* stream) {
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    dim3 grid((K_pad + 255) / 256);
+    if (wdtype == PIVOT_F16)
+        hipLaunchKernelGGL(gather_x_kernel<_Float16>, grid, dim3(256), 0, st, (const _Float16*)x, (long long)ldx, pcol_pad, (_Float16*)xg, K_pad, batch);
+    else
+        hipLaunchKernelGGL(gather_x_kernel<float>, grid, dim3(256), 0, st, (const float*)x, (long long)ldx, pcol_pad, (float*)xg, K_pad, batch);
+    HIP_TRY(hipGetLastError());
+    return PIVOT_OK;
+}
+
+// ---------------------------------------------------------------------------
+// small utility kernels
+// ---------------------------------------------------------------------------
+__global__ void fill_zero_kernel(uint32_t* p, size_t nwords) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < nwords; i += stride) p[i] = 0u;
+}
+
+__global__ void null_kernel() {}
+
+int launch_null(void* stream) {
+    hipLaunchKernelGGL(null_kernel, dim3(1), dim3(64), 0, reinterpret_cast<hipStream_t>(stream));
+    HIP_TRY(hipGetLastError());
+    return PIVOT_OK;
+}
+
+int launch_fill_zero(void* dev, size_t bytes, void* stream) {
+    if (bytes == 0) return PIVOT_OK;
+    if (bytes % 4 != 0 || (reinterpret_cast<uintptr_t>(dev) % 4) != 0) { set_error("fill needs 4-byte alignment"); return PIVOT_E_SHAPE; }
+    size_t nwords = bytes / 4;
+    int blocks = (int)((nwords + 255) / 256 > 2048 ? 2048 : (nwords + 255) / 256);
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, reinterpret_cast<hipStream_t>(stream),
+                       reinterpret_cast<uint32_t*>(dev), nwords);
+    HIP_TRY(hipGetLastError());
+    return PIVOT_OK;
+}
+
+// ---------------------------------------------------------------------------
+// dense comparator: y = act(W x + b), W streamed once, one wave per R rows.
+// ---------------------------------------------------------------------------
+template <typename WT, int NB, int R>
+__global__ void __launch_bounds__(256) dense_kernel(const WT* W, int M, int K, const WT* x, long long ldx,
+                                                    const float* bias, float* y, long long ldy, int batch, int act) {
+    using V = typename Elem<WT>::vec;
+    constexpr int VEC = Elem<WT>::VEC;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int row0 = (blockIdx.x * 4 + wave) * R;
+    if (row0 >= M) return;
+    float acc[R][NB];
+    #pragma unroll
+    for (int r = 0; r < R; ++r)
+        #pragma unroll
+        for (int b = 0; b < NB; ++b) acc[r][b] = 0.f;
+    const WT* wrow[R];
+    #pragma unroll
+    for (int r = 0; r < R; ++r) wrow[r] = W + (size_t)((row0 + r < M) ? row0 + r : M - 1) * K;
+    #pragma unroll 2
+    for (int k = lane * VEC; k < K; k += 64 * VEC) {
+        V wv[R];
+        #pragma unroll
+        for (int r = 0; r < R; ++r) wv[r] = load16<V>(wrow[r] + k);
+        #pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const V xv = (b < batch) ? load16<V>(x + (size_t)b * ldx + k) : V(0);
+            #pragma unroll
+            for (int r = 0; r < R; ++r) acc[r][b] = dot_vec(wv[r], xv, acc[r][b]);
+        }
+    }
+    #pragma unroll
+    for (int r = 0; r < R; ++r)
+        #pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            float v = group_sum<64>(acc[r][b]);
+            if (lane == 0 && row0 + r < M && b < batch)
+                y[(size_t)b * ldy + row0 + r] = apply_act(v + (bias ? bias[row0 + r] : 0.f), act);
+        }
+}
+
+template <typename WT, int NB, int R>
+static int launch_dense_t(const void* W, int M, int K, const void* x, int64_t ldx, const float* bias,
+                          void* y, int64_t ldy, int batch, int act, hipStream_t st) {
+    int rows_per_block = 4 * R;
+    dim3 grid((M + rows_per_block - 1) / rows_per_block);
+    hipLaunchKernelGGL((dense_kernel<WT, NB, R>), grid, dim3(256), 0, st, (const WT*)W, M, K, (const WT*)x,
+                       (long long)ldx, bias, (float*)y, (long long)ldy, batch, act);
+    HIP_TRY(hipGetLastError());
+    return PIVOT_OK;
+}
+
+int launch_dense(const void* W, int wdtype, int M, int K, const void* x, int64_t ldx, const float* bias,
+                 void* y, int64_t ldy, int batch, int act, void* stream) {
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    const int vec = (wdtype == PIVOT_F32) ? 4 : 8;
+    if (K % vec != 0 || ldx % vec != 0) { set_error("dense comparator needs K and ldx to be multiples of %d", vec); return PIVOT_E_UNSUPPORTED; }
+    if (batch < 1 || batch > 16) { set_error("dense comparator supports batch 1..16"); return PIVOT_E_UNSUPPORTED; }
+    if (wdtype == PIVOT_F32) {
+        if (batch == 1) return launch_dense_t<float, 1, 4>(W, M, K, x, ldx, bias, y, ldy, batch, act, st);
+        if (batch <= 4) return launch_dense_t<float, 4, 2>(W, M, K, x, ldx, bias, y, ldy, batch, act, st);
+        return launch_dense_t<float, 16, 1>(W, M, K, x, ldx, bias, y, ldy, batch, act, st);
+    }
+    if (batch == 1) return launch_dense_t<_Float16, 1, 4>(W, M, K, x, ldx, bias, y, ldy, batch, act, st);
+    if (batch <= 4) return launch_dense_t<_Float16, 4, 2>(W, M, K, x, ldx, bias, y, ldy, batch, act, st);
+    return launch_dense_t<_Float16, 16, 1>(W, M, K, x, ldx, bias, y, ldy, batch, act, st);
+}
+
+// ---------------------------------------------------------------------------
+// LSTM cell around the pruned gate matrix (gate order i,f,g,o).
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ float sigmoidf_(float v) { return 1.0f / (1.0f + __expf(-v)); }
+
+__global__ void lstm_cell_kernel(LstmCellLaunch L) {
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= L.batch * L.H) return;
+    const int b = idx / L.H, j = idx - b * L.H;
+    const float* z = L.z + (size_t)b * L.M_pad;
+    const float zi = z[L.invprow[j]];
+    const float zf = z[L.invprow[L.H + j]];
+    const float zg = z[L.invprow[2 * L.H + j]];
+    const float zo = z[L.invprow[3 * L.H + j]];
+    const float c = sigmoidf_(zf) * L.c[idx] + sigmoidf_(zi) * tanhf(zg);
+    const float h = sigmoidf_(zo) * tanhf(c);
+    L.c[idx] = c;
+    L.h[idx] = h;
+    if (L.xg_next) {
+        const size_t o = (size_t)b * L.K_pad + L.invpcol[j];
+        if (L.wdtype == PIVOT_F16) reinterpret_cast<_Float16*>(L.xg_next)[o] = (_Float16)h;
+        else                       reinterpret_cast<float*>(L.xg_next)[o] = h;
+    }
+    if (L.z_dbg) {
+        float* zd = L.z_dbg + (size_t)b * 4 * L.H;
+        zd[j] = zi; zd[L.H + j] = zf; zd[2 * L.H + j] = zg; zd[3 * L.H + j] = zo;
+    }
+}
+
+int launch_lstm_cell(const LstmCellLaunch& L) {
+    int n = L.batch * L.H;
+    hipLaunchKernelGGL(lstm_cell_kernel, dim3((n + 255) / 256), dim3(256), 0, reinterpret_cast<hipStream_t>(L.stream), L);
+    HIP_TRY(hipGetLastError());
+    return PIVOT_OK;
+}
+
+template <typename WT>
+__global__ void lstm_place_inputs_kernel(const WT* xs, WT* xg_all, const int32_t* invpcol, int H, int I,
+                                         int K_pad, size_t total) {
+    size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; idx < total; idx += stride) {
+        const size_t tb = idx / I;               // step*batch + b
+        const int i = (int)(idx - tb * I);
+        xg_all[tb * K_pad + invpcol[H + i]] = xs[idx];
+    }
+}
+
+int launch_lstm_place_inputs(const void* xs, void* xg_all, const int32_t* invpcol, int H, int I, int K_pad,
+                             int steps, int batch, int wdtype, void* stream) {
+    size_t total = (size_t)steps * batch * I;
+    if (total == 0) return PIVOT_OK;
+    int blocks = (int)((total + 255) / 256 > 4096 ? 4096 : (total + 255) / 256);
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (wdtype == PIVOT_F16)
+        hipLaunchKernelGGL(lstm_place_inputs_kernel<_Float16>, dim3(blocks), dim3(256), 0, st,
+                           (const _Float16*)xs, (_Float16*)xg_all, invpcol, H, I, K_pad, total);
+    else
+        hipLaunchKernelGGL(lstm_place_inputs_kernel<float>, dim3(blocks), dim3(256), 0, st,
+                           (const float*)xs, (float*)xg_all, invpcol, H, I, K_pad, total);
+    HIP_TRY(hipGetLastError());
+    return PIVOT_OK;
+}
+
+template <typename WT>
+__global__ void lstm_place_state_kernel(const float* h, WT* xg, const int32_t* invpcol, int H, int K_pad, int n) {
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= n) return;
+    const int b = idx / H, j = idx - b * H;
+    xg[(size_t)b * K_pad + invpcol[j]] = (WT)h[idx];
+}
+
+int launch_lstm_place_state(const float* h, void* xg, const int32_t* invpcol, int H, int K_pad, int batch,
+                            int wdtype, void* stream) {
+    int n = batch * H;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (wdtype == PIVOT_F16)
+        hipLaunchKernelGGL(lstm_place_state_kernel<_Float16>, dim3((n + 255) / 256), dim3(256), 0, st, h, (_Float16*)xg, invpcol, H, K_pad, n);
+    else
+        hipLaunchKernelGGL(lstm_place_state_kernel<float>, dim3((n + 255) / 256), dim3(256), 0, st, h, (float*)xg, invpcol, H, K_pad, n);
+    HIP_TRY(hipGetLastError());
+    return PIVOT_OK;
+}
+
+}  // namespace pivot

@@ -31,41 +31,54 @@ bool device_supported(const pivot_fc_desc& d, std::string* why) {
     return true;
 }
 
-// Batch rows the widest kernel of this plan stages per launch.
-static int widest_batch_tile(const pivot_fc_desc& d) {
-    if (d.wdtype == PIVOT_F32) return 4;
-    if (d.bw % 32 == 0 && d.bh % 16 == 0) return 16;
-    if (d.bh % 32 == 0 && d.bw % 16 == 0) return 32;
-    return 4;
-}
-
 int max_chunk_tiles(const pivot_fc_desc& d) {
-    const int lds_budget = 32 * 1024;
-    int per_tile = d.bw * widest_batch_tile(d) * elem_size(d.wdtype);
+    // the vector kernel stages up to 4 batch rows of the chunk's x-segments in LDS
+    const int lds_budget = 48 * 1024;
+    int per_tile = d.bw * 4 * elem_size(d.wdtype);
     return std::max(1, lds_budget / std::max(1, per_tile));
 }
 
-int choose_chunk_tiles(const HostPlan& hp) {
-    // About three work items per compute unit, but none smaller than 4 KB of
-    // tile values, and never more than LDS can stage.
-    const int target_items = 256 * 3;
-    int tile_bytes = hp.d.bh * hp.d.bw * elem_size(hp.d.wdtype);
-    int ct = (hp.T + target_items - 1) / target_items;
-    ct = std::max(ct, (4096 + tile_bytes - 1) / tile_bytes);
-    ct = std::max(ct, 1);
-    return std::min(ct, max_chunk_tiles(hp.d));
-}
+void choose_schedule(HostPlan& hp) {
+    const pivot_fc_desc& d = hp.d;
+    const size_t tile_bytes = (size_t)d.bh * d.bw * elem_size(d.wdtype);
+    int max_row = 0;
+    for (int i = 0; i < hp.nbr; ++i) max_row = std::max(max_row, hp.row_ptr[i + 1] - hp.row_ptr[i]);
+    const int avg_row = hp.nbr ? (hp.T + hp.nbr - 1) / hp.nbr : 0;
 
-int choose_wg_waves(const HostPlan& hp) {
-    // One wavefront keeps about 8 KB of tile values in flight; give the
-    // largest work item enough wavefronts to have all of it in flight at once.
-    size_t tile_bytes = (size_t)hp.d.bh * hp.d.bw * elem_size(hp.d.wdtype);
-    size_t big = 0;
-    for (int j = 0; j < hp.nchunks; ++j)
-        big = std::max(big, (size_t)(hp.chunks[4 * j + 2] - hp.chunks[4 * j + 1]) * tile_bytes);
-    if (big <= 4 * 8192) return 4;
-    if (big <= 8 * 8192) return 8;
-    return 16;
+    // Row slices: every slice is an independent work item with no reduction
+    // across slices, so slicing is the cheapest way to get more of them.
+    int sl = d.row_slices;
+    if (sl == 0) {
+        sl = 1;
+        while (sl < 8 && hp.nbr * sl < 512 && fc_row_slices(d.wdtype, d.bh, d.bw, 1, sl * 2) == sl * 2) sl *= 2;
+    }
+    if (d.device >= 0) sl = fc_row_slices(d.wdtype, d.bh, d.bw, 1, sl);
+    hp.row_slices = sl;
+
+    // Chunk size: a work item of 16 wavefronts keeps 128 KB of tile values in
+    // flight, which bounds what is worth giving to one; block rows are cut
+    // further only while that yields fewer than one work item per compute unit
+    // and the pieces stay above 16 KB.
+    int ct = d.chunk_tiles;
+    if (ct == 0) {
+        const size_t slice_bytes = std::max<size_t>(1, tile_bytes / sl);
+        int cap = (int)std::max<size_t>(1, (128 * 1024) / slice_bytes);
+        cap = std::min(cap, max_chunk_tiles(d));
+        cap = std::min(cap, std::max(4 * avg_row, 8));
+        int parts = std::max(1, (max_row + cap - 1) / cap);
+        while ((size_t)hp.nbr * sl * parts < 256 && (size_t)(max_row / (parts * 2)) * slice_bytes >= 16 * 1024) parts *= 2;
+        ct = std::max(1, (max_row + parts - 1) / parts);
+    }
+    if (d.device >= 0) ct = std::min(ct, max_chunk_tiles(d));
+    build_schedule(hp, ct);
+
+    int nw = d.wg_waves;
+    if (nw == 0) {
+        // one wavefront keeps about 8 KB in flight
+        size_t big = (size_t)std::min(ct, std::max(max_row, 1)) * (tile_bytes / sl);
+        nw = big <= 4 * 8192 ? 4 : (big <= 8 * 8192 ? 8 : 16);
+    }
+    hp.wg_waves = nw;
 }
 
 void build_schedule(HostPlan& hp, int chunk_tiles) {
@@ -151,6 +164,7 @@ int build_host_plan(const pivot_fc_desc& d, const void* W, int w_space, const ui
     if (d.chunk_tiles < 0) { set_error("chunk_tiles must be >= 0"); return PIVOT_E_SHAPE; }
     if (d.flags != 0) { set_error("flags must be 0"); return PIVOT_E_UNSUPPORTED; }
     if (d.wg_waves != 0 && d.wg_waves != 4 && d.wg_waves != 8 && d.wg_waves != 16) { set_error("wg_waves must be 0, 4, 8 or 16"); return PIVOT_E_UNSUPPORTED; }
+    if (d.row_slices != 0 && d.row_slices != 1 && d.row_slices != 2 && d.row_slices != 4 && d.row_slices != 8) { set_error("row_slices must be 0, 1, 2, 4 or 8"); return PIVOT_E_UNSUPPORTED; }
 
     hp.d = d;
     hp.nbr = (d.M + d.bh - 1) / d.bh;
@@ -192,11 +206,7 @@ int build_host_plan(const pivot_fc_desc& d, const void* W, int w_space, const ui
         for (int t = 0; t < hp.T; ++t)
             for (int c = 0; c < d.bw; ++c) hp.xidx[(size_t)t * d.bw + c] = hp.pcol_pad[(size_t)hp.col_idx[t] * d.bw + c];
 
-        int ct = d.chunk_tiles;
-        if (ct == 0) ct = choose_chunk_tiles(hp);
-        if (d.device >= 0) ct = std::min(ct, max_chunk_tiles(d));
-        build_schedule(hp, ct);
-        hp.wg_waves = d.wg_waves ? d.wg_waves : choose_wg_waves(hp);
+        choose_schedule(hp);
     } catch (const std::bad_alloc&) {
         set_error("out of host memory while building the plan");
         return PIVOT_E_ALLOC;

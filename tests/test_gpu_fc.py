@@ -27,6 +27,17 @@ def test_every_tile_shape_ragged_small(bh, bw, wdtype):
         G.check_fc(p, chunk_tiles=ct)
 
 
+@pytest.mark.parametrize("wdtype,bh,bw", [(WL.F32, 32, 32), (WL.F32, 64, 16), (WL.F16, 64, 16), (WL.F16, 64, 64)])
+@pytest.mark.parametrize("waves", [4, 8, 16])
+@pytest.mark.parametrize("slices", [1, 2, 4, 8])
+def test_row_slices_and_wave_counts(wdtype, bh, bw, waves, slices):
+    for batch in (1, 4, 16):
+        p = WL.gen_fc(3 * bh - 5, 12 * bw - 3, bh, bw, 0.7, seed=31, wdtype=wdtype, batch=batch, act=WL.ACT_RELU)
+        p.tile_mask[1, :] = 0
+        G.check_fc(p, chunk_tiles=5, wg_waves=waves, row_slices=slices)     # split rows
+        G.check_fc(p, chunk_tiles=12, wg_waves=waves, row_slices=slices)    # whole rows
+
+
 @pytest.mark.parametrize("batch", [1, 2, 3, 4, 5, 8])
 def test_batches_fp32(batch):
     p = WL.gen_fc(200, 328, 16, 16, 0.5, seed=7, batch=batch, act=WL.ACT_NONE)
