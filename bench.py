@@ -22,6 +22,8 @@ import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
+# kernel arguments in device memory (a ROCm runtime setting; must precede HIP start-up)
+os.environ.setdefault("HIP_FORCE_DEV_KERNARG", "1")
 
 HBM_PEAK_GBS = 8000.0            # MI355X published HBM3E peak
 COLD_FOOTPRINT = 2 * (256 + 32) * (1 << 20)   # rotate through >= 2 x (Infinity Cache + all L2)
@@ -47,6 +49,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run a few plain 64 MiB device copies, so that a rocprofv3 --pmc run of this "
+                         "command has a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (the layer is a single-device kernel); "
@@ -96,6 +101,13 @@ def main():
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
         return e0.elapsed_time(e1) / n, wall / n * 1e3      # ms per step (device events), ms per step (host clock)
+
+    if args.pmc_calibration:
+        ca = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
+        cb = torch.ones(64 << 20, dtype=torch.uint8, device="cuda")
+        for _ in range(5):
+            ca.copy_(cb)
+        torch.cuda.synchronize()
 
     cold_ms, cold_wall_ms = timed(K, True, Wm)
     warm_ms, _ = timed(K, False, Wm)
@@ -160,7 +172,8 @@ def main():
         "config": {"workload": "configs[1]: FC 4096x9216 (AlexNet fc6 shape) fp32 batch 1, 32x32 tiles, "
                                "29 of 288 tiles kept per block row (balanced), uniform random P_r/P_c, ReLU",
                    "seed": args.seed, "kept_fraction": round(kept, 5), "tiles": p.T,
-                   "chunk_tiles": view["chunk_tiles"], "work_items": view["nchunks"], "wg_waves": view["wg_waves"],
+                   "chunk_tiles": view["chunk_tiles"], "work_items": view["nchunks"] * view["row_slices"], "row_slices": view["row_slices"],
+                   "wg_waves": view["wg_waves"],
                    "cold_copies": ncopies},
         "warm_us": round(warm_us, 3),
         "cold_host_clock_us": round(cold_wall_ms * 1e3, 3),

@@ -73,6 +73,10 @@ def lib():
     if not os.path.exists(LIB_PATH):
         raise RuntimeError("libpivotfc.so is not built: run `python -m paper_1712_01084_amd.build` "
                            "(there is no CPU fallback)")
+    # Kernel arguments in device memory instead of host memory: the first
+    # scalar load of every wavefront then stays on the device (about 1 us per
+    # launch on MI355X).  Only effective if set before the HIP runtime starts.
+    os.environ.setdefault("HIP_FORCE_DEV_KERNARG", "1")
     try:
         import torch  # noqa: F401  -- so that the library binds to the HIP runtime torch already loaded
     except Exception:

@@ -22,7 +22,9 @@ SOURCES = ["pivot_gemv_f32.hip", "pivot_gemv_f16.hip", "pivot_mfma_f16.hip", "pi
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"), "-I", CSRC,
           "-Wall", "-Wno-unused-function"]
 # packed fp32 instructions are kept off for every device compile
-DEVICE = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+# the leading kernel arguments are preloaded into SGPRs (up to 14 dwords on gfx950)
+DEVICE = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+          "-mllvm", "-amdgpu-kernarg-preload-count=16"]
 
 
 def _hipcc():
@@ -32,9 +34,10 @@ def _hipcc():
     raise RuntimeError("hipcc not found")
 
 
-def _compile(src):
-    obj = os.path.join(OBJDIR, os.path.splitext(src)[0] + ".o")
-    cmd = [_hipcc()] + COMMON + DEVICE + ["-c", os.path.join(CSRC, src), "-o", obj]
+def _compile(src, objdir=None, device_flags=None):
+    objdir = objdir or OBJDIR
+    obj = os.path.join(objdir, os.path.splitext(src)[0] + ".o")
+    cmd = [_hipcc()] + COMMON + (DEVICE if device_flags is None else device_flags) + ["-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     out = "\n".join(l for l in r.stdout.splitlines() if "packed-fp32-ops" not in l)
     if r.returncode != 0:
@@ -42,20 +45,24 @@ def _compile(src):
     return obj, out
 
 
-def build(verbose=False):
-    os.makedirs(OBJDIR, exist_ok=True)
+def build(verbose=False, out=None, objdir=None, device_flags=None):
+    """Compiles every source and links the shared library.  ``out``, ``objdir``
+    and ``device_flags`` let an experiment build a variant beside the product."""
+    objdir = objdir or OBJDIR
+    os.makedirs(objdir, exist_ok=True)
     with ThreadPoolExecutor(max_workers=7) as ex:
-        results = list(ex.map(_compile, SOURCES))
+        results = list(ex.map(lambda s: _compile(s, objdir, device_flags), SOURCES))
     if verbose:
         for _, out in results:
             if out.strip():
                 print(out)
     objs = [o for o, _ in results]
-    cmd = [_hipcc(), "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB] + objs + ["-Wl,-rpath,/opt/rocm/lib"]
+    out = out or LIB
+    cmd = [_hipcc(), "-shared", "-fPIC", "--offload-arch=gfx950", "-o", out] + objs + ["-Wl,-rpath,/opt/rocm/lib"]
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed: %s\n%s" % (" ".join(cmd), r.stdout))
-    return LIB
+    return out
 
 
 if __name__ == "__main__":

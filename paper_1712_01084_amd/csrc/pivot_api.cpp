@@ -196,6 +196,7 @@ int prepare(const pivot_fc_plan_t* plan, int batch, void* ws, size_t ws_bytes, F
     L.M_pad = h.M_pad; L.K_pad = h.K_pad; L.bh = h.d.bh; L.bw = h.d.bw; L.wdtype = h.d.wdtype; L.act = h.d.act;
     L.nchunks = h.nchunks; L.nbr = h.nbr; L.chunk_tiles = h.chunk_tiles; L.wg_waves = h.wg_waves;
     L.row_slices = h.row_slices;
+    L.uniform_ct = h.uniform_ct; L.uniform_parts = h.uniform_parts;
     L.batch = batch;
     int nbt = fc_batch_tile(h.d.wdtype, h.d.bh, h.d.bw, batch);
     int ngy = (batch + nbt - 1) / nbt;

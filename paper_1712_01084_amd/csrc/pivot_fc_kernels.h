@@ -50,7 +50,17 @@ struct FcArgs {
     int batch, act, out_f16, nchunks, nbr, xs_stride;
     int bh_full;                // rows of a whole tile (the kernels' BH is the height of one row slice)
     int tile_elems;             // bh_full * bw
+    int uniform_ct;             // > 0: every chunk has exactly this many tiles and chunk i starts at tile i*uniform_ct,
+    int uniform_parts;          //      uniform_parts chunks per block row: the descriptor is computed, not loaded
 };
+
+// The seven pointers every wavefront needs first are separate leading kernel
+// arguments: with kernel-argument preloading they arrive in SGPRs with the
+// wave, so the first dependent load can be issued at once.
+#define PIVOT_LEAD_PARAMS const int4* __restrict__ p_chunks, const int32_t* __restrict__ p_part_base, \
+    const int32_t* __restrict__ p_idx, const void* __restrict__ p_vals, const float* __restrict__ p_bias, \
+    const int32_t* __restrict__ p_scatter, const void* __restrict__ p_x
+#define PIVOT_LEAD_ARGS(a, idx) (a).chunks, (a).part_base, (idx), (a).vals, (a).bias_p, (a).scatter, (a).x
 
 // Per-dtype / per-path launchers, each in its own translation unit.
 int launch_gemv_f32(const FcArgs& a, int bhs, int bw, int nb, int nw, dim3 grid, size_t smem, hipStream_t st);
@@ -99,12 +109,12 @@ struct RowPre {
     static constexpr int CNT = (N + NT - 1) / NT;
     float bias[CNT];
     int   dst[CNT];
-    __device__ __forceinline__ void load(const FcArgs& a, int row0, int tid) {
+    __device__ __forceinline__ void load(const float* bias_p, const int32_t* scatter, int row0, int tid) {
         #pragma unroll
         for (int k = 0; k < CNT; ++k) {
             const int row = row0 + (tid + k * NT) % BH;
-            bias[k] = a.bias_p[row];
-            dst[k] = a.scatter[row];
+            bias[k] = bias_p[row];
+            dst[k] = scatter[row];
         }
     }
 };
@@ -124,8 +134,8 @@ struct XStage {
     static constexpr int XP = 4;
     static constexpr int STEP = NT / NB;
     int src[XP];
-    __device__ __forceinline__ void load_idx(const FcArgs& a, int tile_begin, int ne, int tid) {
-        const int32_t* xi = a.xidx + (size_t)tile_begin * BW;
+    __device__ __forceinline__ void load_idx(const int32_t* xidx, int tile_begin, int ne, int tid) {
+        const int32_t* xi = xidx + (size_t)tile_begin * BW;
         const int emax = ne > 0 ? ne - 1 : 0;       // index arrays carry 16 bytes of padding: xi[0] is readable
         #pragma unroll
         for (int k = 0; k < XP; ++k) {
@@ -133,10 +143,11 @@ struct XStage {
             src[k] = xi[e < emax ? e : emax];
         }
     }
-    __device__ __forceinline__ void gather(const FcArgs& a, WT* xs, int tile_begin, int ne, int b0, int tid) {
+    __device__ __forceinline__ void gather(const FcArgs& a, const int32_t* xidx, const void* x, WT* xs,
+                                           int tile_begin, int ne, int b0, int tid) {
         const int b = tid % NB;
         const bool row_ok = (b0 + b) < a.batch;
-        const WT* xrow = reinterpret_cast<const WT*>(a.x) + (long long)(row_ok ? b0 + b : 0) * a.ldx;
+        const WT* xrow = reinterpret_cast<const WT*>(x) + (long long)(row_ok ? b0 + b : 0) * a.ldx;
         WT* xsrow = xs + b * a.xs_stride;
         const int dump = a.xs_stride - 1;
         WT v[XP];
@@ -147,7 +158,7 @@ struct XStage {
             const int e = tid / NB + k * STEP;
             xsrow[e < ne ? e : dump] = (src[k] >= 0 && row_ok) ? v[k] : WT(0);
         }
-        const int32_t* xi = a.xidx + (size_t)tile_begin * BW;
+        const int32_t* xi = xidx + (size_t)tile_begin * BW;
         for (int e = tid / NB + XP * STEP; e < ne; e += STEP) {
             const int sidx = xi[e];
             WT vv = WT(0);
@@ -156,6 +167,28 @@ struct XStage {
         }
     }
 };
+
+// The work item's descriptor: loaded from the schedule, or computed when the
+// schedule is uniform (balanced pruning: every block row keeps the same
+// number of tiles), which takes one dependent load off the critical path.
+struct Chunk { int br, tile_begin, ntiles, slot, first, nparts; };
+__device__ __forceinline__ Chunk load_chunk(const FcArgs& a, const int4* chunks, const int32_t* part_base) {
+    Chunk c;
+    if (a.uniform_ct > 0) {
+        c.br = blockIdx.x / a.uniform_parts;
+        c.tile_begin = blockIdx.x * a.uniform_ct;
+        c.ntiles = a.uniform_ct;
+        c.slot = blockIdx.x;
+        c.first = c.br * a.uniform_parts;
+        c.nparts = a.uniform_parts;
+    } else {
+        const int4 cd = chunks[blockIdx.x];
+        c.br = cd.x; c.tile_begin = cd.y; c.ntiles = cd.z - cd.y; c.slot = cd.w;
+        c.first = part_base[c.br];
+        c.nparts = part_base[c.br + 1] - c.first;
+    }
+    return c;
+}
 
 // Everything after the per-wave sums are in LDS `red[w*N + idx]`, idx = j*BH + r
 // (j = batch column of this launch tile, r = row inside the row slice):
@@ -218,7 +251,7 @@ __device__ __forceinline__ void finish_rows(const FcArgs& a, const float* red, i
 // covers RPW rows per load.
 // ---------------------------------------------------------------------------
 template <typename WT, int BH, int BW, int NB, int NW>
-__global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(FcArgs a) {
+__global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(PIVOT_LEAD_PARAMS, FcArgs a) {
     using V = typename Elem<WT>::vec;
     constexpr int VEC = Elem<WT>::VEC;
     constexpr int NT  = NW * 64;
@@ -238,24 +271,23 @@ __global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(FcArgs a) {
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int b0 = blockIdx.y * NB, slice = blockIdx.z;
-    const int4 cd = a.chunks[blockIdx.x];
-    const int br = cd.x, tile_begin = cd.y, ntiles = cd.z - cd.y, slot = cd.w;
+    const Chunk ck = load_chunk(a, p_chunks, p_part_base);
+    const int br = ck.br, tile_begin = ck.tile_begin, ntiles = ck.ntiles, slot = ck.slot;
+    const int first = ck.first, nparts = ck.nparts;
     const int ngroups = (ntiles + TPL - 1) / TPL;
-    const int first = a.part_base[br];
-    const int nparts = a.part_base[br + 1] - first;
     const int row0 = br * a.bh_full + slice * BH;
 
     // order of issue = order of arrival: gather indices, epilogue operands, then the weights
     XStage<WT, BW, NB, NT> xst;
-    xst.load_idx(a, tile_begin, ntiles * BW, tid);
+    xst.load_idx(p_idx, tile_begin, ntiles * BW, tid);
     RowPre<BH, N, NT> rp;
-    rp.load(a, row0, tid);
+    rp.load(p_bias, p_scatter, row0, tid);
 
     const int s  = lane / LPR;                          // row within the wave-load
     const int cg = lane % LPR;                          // column group
     const int ts = (TPL > 1) ? s / BH : 0;              // tile within the group
     const size_t gstride = (size_t)TPL * a.tile_elems;  // elements between groups of tiles
-    const WT* vbase = reinterpret_cast<const WT*>(a.vals) + (size_t)tile_begin * a.tile_elems
+    const WT* vbase = reinterpret_cast<const WT*>(p_vals) + (size_t)tile_begin * a.tile_elems
                       + (size_t)slice * BH * BW + lane * VEC;
 
     // Loads are unconditional (group index clamped; the value array is padded by
@@ -274,7 +306,7 @@ __global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(FcArgs a) {
     };
 
     issue(wave);
-    xst.gather(a, xs, tile_begin, ntiles * BW, b0, tid);
+    xst.gather(a, p_idx, p_x, xs, tile_begin, ntiles * BW, b0, tid);
     lds_barrier();
 
     float acc[NL][NB];
@@ -355,7 +387,7 @@ template <> struct Mfma<1> {
 };
 
 template <int KIND, int BH, int BW, int NW>
-__global__ void __launch_bounds__(NW * 64) fc_mfma_kernel(FcArgs a) {
+__global__ void __launch_bounds__(NW * 64) fc_mfma_kernel(PIVOT_LEAD_PARAMS, FcArgs a) {
     using MF = Mfma<KIND>;
     using acc_t = typename MF::acc_t;
     constexpr int MR = MF::MR, MK = MF::MK, NBT = MF::NBT, CV = MF::CV;
@@ -375,22 +407,21 @@ __global__ void __launch_bounds__(NW * 64) fc_mfma_kernel(FcArgs a) {
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int b0 = blockIdx.y * NBT, slice = blockIdx.z;
-    const int4 cd = a.chunks[blockIdx.x];
-    const int br = cd.x, tile_begin = cd.y, ntiles = cd.z - cd.y, slot = cd.w;
-    const int first = a.part_base[br];
-    const int nparts = a.part_base[br + 1] - first;
+    const Chunk ck = load_chunk(a, p_chunks, p_part_base);
+    const int br = ck.br, tile_begin = ck.tile_begin, ntiles = ck.ntiles, slot = ck.slot;
+    const int first = ck.first, nparts = ck.nparts;
     const int row0 = br * a.bh_full + slice * BH;
 
     RowPre<BH, N, NT> rp;
-    rp.load(a, row0, tid);
+    rp.load(p_bias, p_scatter, row0, tid);
 
     const int li = lane % MR;                           // A row / B column of this lane
     const int lg = lane / MR;                           // k group of 8
-    const _Float16* vbase = reinterpret_cast<const _Float16*>(a.vals) + (size_t)tile_begin * a.tile_elems
+    const _Float16* vbase = reinterpret_cast<const _Float16*>(p_vals) + (size_t)tile_begin * a.tile_elems
                             + (size_t)slice * BH * BW + li * BW + lg * 8;
     const int brow = (b0 + li < a.batch) ? b0 + li : a.batch - 1;
-    const _Float16* xb = reinterpret_cast<const _Float16*>(a.x) + (long long)brow * a.ldx + lg * 8;
-    const int32_t* ci_base = a.col_idx + tile_begin;    // wave-uniform: scalar loads, their own counter
+    const _Float16* xb = reinterpret_cast<const _Float16*>(p_x) + (long long)brow * a.ldx + lg * 8;
+    const int32_t* ci_base = p_idx + tile_begin;    // wave-uniform: scalar loads, their own counter
 
     const int tmax = ntiles > 0 ? ntiles - 1 : 0;       // clamped, unconditional loads (see fc_gemv_kernel)
     f16x8 w[U][LT];

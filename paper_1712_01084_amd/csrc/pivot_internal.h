@@ -24,6 +24,8 @@ struct HostPlan {
     pivot_fc_desc d{};
     int nbr = 0, nbc = 0, M_pad = 0, K_pad = 0, T = 0, chunk_tiles = 0, nchunks = 0, wg_waves = 4, row_slices = 1;
     int max_parts = 1;                 // largest number of pieces of one block row
+    int uniform_ct = 0, uniform_parts = 0;  // set when every block row keeps the same number of tiles and every
+                                       // chunk is full: chunk i = tiles [i*ct, (i+1)*ct) of block row i / parts
     std::vector<int32_t> row_ptr, col_idx, invprow, invpcol, prow_pad, pcol_pad;
     std::vector<int32_t> xidx;         // T*bw: xidx[t*bw+c] = pcol_pad[col_idx[t]*bw+c]
     std::vector<int32_t> chunks;       // nchunks x 4
@@ -77,6 +79,7 @@ struct FcLaunch {
                                 // natural-order x, the block-space column itself for x already in block order
     const int32_t* scatter;     // [M_pad] block-space row -> index into y (-1 = padding row, not stored)
     int M_pad, K_pad, bh, bw, wdtype, act, nchunks, nbr, chunk_tiles, wg_waves, row_slices;
+    int uniform_ct, uniform_parts;  // > 0: regular schedule, the kernels compute the chunk descriptor
     int x_block_order;          // 1: x is [batch][K_pad] in block order (what the matrix-core kernel needs)
     // data
     const void* x; int64_t ldx;

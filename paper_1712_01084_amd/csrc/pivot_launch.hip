@@ -82,6 +82,7 @@ int launch_fc(const FcLaunch& L) {
     a.ldx = L.ldx; a.ldy = L.ldy; a.batch = L.batch; a.act = L.act; a.out_f16 = L.out_f16;
     a.nchunks = L.nchunks; a.nbr = L.nbr;
     a.bh_full = L.bh; a.tile_elems = L.bh * L.bw;
+    a.uniform_ct = L.uniform_ct; a.uniform_parts = L.uniform_parts;
     dim3 grid(L.nchunks, ngy, sl);
     hipStream_t st = reinterpret_cast<hipStream_t>(L.stream);
 

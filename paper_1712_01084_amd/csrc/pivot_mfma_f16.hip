@@ -5,9 +5,9 @@ namespace pivot {
 
 template <int KIND, int BH, int BW>
 static int launch_t(const FcArgs& a, int nw, dim3 grid, size_t smem, hipStream_t st) {
-    if (nw == 16)     hipLaunchKernelGGL((fc_mfma_kernel<KIND, BH, BW, 16>), grid, dim3(16 * 64), smem, st, a);
-    else if (nw == 8) hipLaunchKernelGGL((fc_mfma_kernel<KIND, BH, BW, 8>), grid, dim3(8 * 64), smem, st, a);
-    else              hipLaunchKernelGGL((fc_mfma_kernel<KIND, BH, BW, 4>), grid, dim3(4 * 64), smem, st, a);
+    if (nw == 16)     hipLaunchKernelGGL((fc_mfma_kernel<KIND, BH, BW, 16>), grid, dim3(16 * 64), smem, st, PIVOT_LEAD_ARGS(a, a.col_idx), a);
+    else if (nw == 8) hipLaunchKernelGGL((fc_mfma_kernel<KIND, BH, BW, 8>), grid, dim3(8 * 64), smem, st, PIVOT_LEAD_ARGS(a, a.col_idx), a);
+    else              hipLaunchKernelGGL((fc_mfma_kernel<KIND, BH, BW, 4>), grid, dim3(4 * 64), smem, st, PIVOT_LEAD_ARGS(a, a.col_idx), a);
     HIP_TRY(hipGetLastError());
     return PIVOT_OK;
 }

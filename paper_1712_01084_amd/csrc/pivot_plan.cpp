@@ -98,6 +98,17 @@ void build_schedule(HostPlan& hp, int chunk_tiles) {
         hp.part_base[i + 1] = (int32_t)cs.size();
         hp.max_parts = std::max(hp.max_parts, (int)cs.size() - first);
     }
+    // regular schedule: same number of tiles in every block row, all chunks full
+    hp.uniform_ct = hp.uniform_parts = 0;
+    if (hp.nbr > 0 && hp.T > 0 && hp.T % hp.nbr == 0) {
+        const int per_row = hp.T / hp.nbr;
+        bool same = per_row % chunk_tiles == 0 || per_row <= chunk_tiles;
+        for (int i = 0; i < hp.nbr && same; ++i) same = (hp.row_ptr[i + 1] - hp.row_ptr[i]) == per_row;
+        if (same) {
+            hp.uniform_ct = std::min(per_row, chunk_tiles);
+            hp.uniform_parts = per_row / hp.uniform_ct;
+        }
+    }
     std::stable_sort(cs.begin(), cs.end(), [](const C& a, const C& b) { return (a.e - a.b) > (b.e - b.b); });
     hp.nchunks = (int)cs.size();
     hp.chunks.resize((size_t)hp.nchunks * 4);
