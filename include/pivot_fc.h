@@ -215,9 +215,9 @@ int    pivot_mlp_run(const pivot_mlp_plan_t* plan, const void* x_dev, int64_t ld
  * Recurrent use: an LSTM whose gate matrix (4H x (H+I), gate order i,f,g,o,
  * input [h_{t-1}; x_t]) is a pruned layer.  The recurrence is a PBP layer
  * back-to-back with itself through a point-wise cell, so the boundary fusion
- * of Section 4.2.1 applies: the cell reads the gates in block order through
- * invprow and writes h_t straight into the block-order input of the next
- * step through invpcol; all x_t are placed once up front.
+ * of Section 4.2.1 applies: the cell writes h_t straight into the block-order
+ * input of the next step through invpcol, so no step gathers its input; all
+ * x_t are placed once up front.
  *
  *   xs_dev   device, [steps][batch][I] of wdtype
  *   h_dev    device, [batch][H] fp32: h_0 on entry, h_steps on return

@@ -411,7 +411,7 @@ LstmLayout lstm_layout(const pivot_fc_plan_t* p, int steps, int batch) {
     LstmLayout m{};
     m.scratch = align_up(fc_workspace_bytes(p->host, batch), 256);
     m.z_off = m.scratch;
-    m.xg_off = m.z_off + align_up((size_t)batch * p->host.M_pad * 4, 256);
+    m.xg_off = m.z_off + align_up((size_t)batch * p->host.d.M * 4, 256);
     m.xg_step = align_up((size_t)batch * p->host.K_pad * elem_size(p->host.d.wdtype), 256);
     m.total = m.xg_off + m.xg_step * (size_t)(steps > 0 ? steps : 1);
     return m;
@@ -460,11 +460,11 @@ int pivot_lstm_run(const pivot_fc_plan_t* plan, int H, int I, const void* xs_dev
         if (rc != PIVOT_OK) return rc;
         L.xidx = plan->dev.xidx_blk; L.x_block_order = 1;
         L.x = xg + m.xg_step * (size_t)t; L.ldx = h.K_pad;
-        L.scatter = plan->dev.rowid_pad;
-        L.y = z; L.ldy = h.M_pad; L.out_f16 = 0; L.stream = stream;
+        L.scatter = plan->dev.prow_pad;      // gates land in natural order for the cell
+        L.y = z; L.ldy = h.d.M; L.out_f16 = 0; L.stream = stream;
         if ((rc = launch_fc(L)) != PIVOT_OK) return rc;
         LstmCellLaunch C{};
-        C.z = z; C.invprow = plan->dev.invprow; C.invpcol = plan->dev.invpcol;
+        C.z = z; C.invpcol = plan->dev.invpcol;
         C.h = h_dev; C.c = c_dev;
         C.xg_next = (t + 1 < steps) ? (void*)(xg + m.xg_step * (size_t)(t + 1)) : nullptr;
         C.z_dbg = (t + 1 == steps) ? z_dbg : nullptr;

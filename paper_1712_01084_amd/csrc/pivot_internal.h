@@ -109,8 +109,7 @@ int    launch_dense(const void* W, int wdtype, int M, int K, const void* x, int6
                     const float* bias, void* y, int64_t ldy, int batch, int act, void* stream);
 
 struct LstmCellLaunch {
-    const float* z;             // [batch][M_pad] gate pre-activations in block order (bias included)
-    const int32_t* invprow;     // natural gate row -> block-space row
+    const float* z;             // [batch][4H] gate pre-activations in natural order (bias included)
     const int32_t* invpcol;     // natural input column -> block-space column
     float* h; float* c;         // [batch][H]
     void* xg_next;              // [batch][K_pad] of wdtype: next step's block-order input, or NULL

@@ -136,17 +136,21 @@ __global__ void lstm_cell_kernel(LstmCellLaunch L) {
     const int idx = blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= L.batch * L.H) return;
     const int b = idx / L.H, j = idx - b * L.H;
-    const float* z = L.z + (size_t)b * L.M_pad;
-    const float zi = z[L.invprow[j]];
-    const float zf = z[L.invprow[L.H + j]];
-    const float zg = z[L.invprow[2 * L.H + j]];
-    const float zo = z[L.invprow[3 * L.H + j]];
+    // the layer kernel scattered the gate pre-activations into natural order: coalesced reads here
+    const float* z = L.z + (size_t)b * 4 * L.H;
+    const float zi = z[j];
+    const float zf = z[L.H + j];
+    const float zg = z[2 * L.H + j];
+    const float zo = z[3 * L.H + j];
+    const int dstc = L.xg_next ? L.invpcol[j] : 0;
     const float c = sigmoidf_(zf) * L.c[idx] + sigmoidf_(zi) * tanhf(zg);
     const float h = sigmoidf_(zo) * tanhf(c);
     L.c[idx] = c;
     L.h[idx] = h;
     if (L.xg_next) {
-        const size_t o = (size_t)b * L.K_pad + L.invpcol[j];
+        // boundary fusion (Section 4.2.1 applied to the recurrence): h_t goes straight to its
+        // block-order position in the next step's input
+        const size_t o = (size_t)b * L.K_pad + dstc;
         if (L.wdtype == PIVOT_F16) reinterpret_cast<_Float16*>(L.xg_next)[o] = (_Float16)h;
         else                       reinterpret_cast<float*>(L.xg_next)[o] = h;
     }
