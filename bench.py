@@ -10,7 +10,9 @@ HBM.  The workload is the AlexNet-fc6-shaped layer of the workload list
 The headline value is the cache-cold time per layer: consecutive steps rotate
 through enough separate device copies of the plan and of x that no byte a step
 reads is still in the L2 or the 256 MB Infinity Cache.  The warm time (same
-copy back to back) is reported beside it.  Prints ONE JSON line.
+copy back to back) is reported beside it.  The steps are replayed from HIP
+graphs (see bench_util.py) so that the GPU, not the Python launch loop, is
+what is timed.  Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -62,6 +64,7 @@ def main():
     import torch
     from paper_1712_01084_amd import binding as B
     from paper_1712_01084_amd import workloads as WL
+    import bench_util as BU
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -85,22 +88,9 @@ def main():
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
     B.pivot_workspace_init(ws.data_ptr(), ws_bytes, st)
 
-    def run_steps(n, rotate):
-        for i in range(n):
-            j = i % ncopies if rotate else 0
-            B.pivot_fc_run(plans[j], xs[j].data_ptr(), p.K, ys[j].data_ptr(), p.M, 1, ws.data_ptr(), ws_bytes, st)
-
-    def timed(n, rotate, warm):
-        run_steps(warm, rotate)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        t0 = time.perf_counter()
-        e0.record()
-        run_steps(n, rotate)
-        e1.record()
-        torch.cuda.synchronize()
-        wall = time.perf_counter() - t0
-        return e0.elapsed_time(e1) / n, wall / n * 1e3      # ms per step (device events), ms per step (host clock)
+    def step(i, stream, rotate=True):
+        j = i % ncopies if rotate else 0
+        B.pivot_fc_run(plans[j], xs[j].data_ptr(), p.K, ys[j].data_ptr(), p.M, 1, ws.data_ptr(), ws_bytes, stream)
 
     if args.pmc_calibration:
         ca = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
@@ -109,20 +99,48 @@ def main():
             ca.copy_(cb)
         torch.cuda.synchronize()
 
-    cold_ms, cold_wall_ms = timed(K, True, Wm)
-    warm_ms, _ = timed(K, False, Wm)
+    # The K timed steps are replays of captured graphs of plain kernel launches, so that the host's
+    # launch cost (about 5 us per call through Python, more than the GPU needs) is not what is timed.
+    # A graph holds a whole number of rotations through the cold copies; K = full replays + one
+    # remainder graph, exactly K launches between the two events.
+    def timed(K_, W_, rotate):
+        per = ncopies * max(1, 80 // ncopies) if rotate else 100
+        per = min(per, K_)
+        full, rem = divmod(K_, per)
+        g_full = BU.capture(lambda i, s: step(i, s, rotate), per)
+        g_rem = BU.capture(lambda i, s: step(i, s, rotate), rem) if rem else None
+        for _ in range(max(1, W_ // per)):
+            g_full.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(full):
+            g_full.replay()
+        if g_rem is not None:
+            g_rem.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        return e0.elapsed_time(e1) / K_, wall / K_ * 1e3
 
-    # launch floor: an empty kernel back to back on the same stream
-    for _ in range(100):
-        B.pivot_null_run(st)
+    cold_ms, cold_wall_ms = timed(K, Wm, True)
+    warm_ms, _ = timed(K, Wm, False)
+
+    # the same K steps launched eagerly from Python (host-bound for small layers; reported for reference)
+    for i in range(Wm):
+        step(i, st)
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
-    for _ in range(2000):
-        B.pivot_null_run(st)
+    for i in range(K):
+        step(i, st)
     e1.record()
     torch.cuda.synchronize()
-    null_us = e0.elapsed_time(e1) / 2000 * 1e3
+    eager_cold_us = e0.elapsed_time(e1) / K * 1e3
+
+    # launch floor: an empty kernel back to back on the same stream
+    null_us = BU.graph_time(lambda i, s: B.pivot_null_run(s), 200, replays=10)
 
     # the same layer dense on the GPU: this library's streaming kernel, cold, and torch.mv as a guard
     dense_bytes = p.dense_bytes(1)
@@ -133,18 +151,11 @@ def main():
     bd = torch.from_numpy(p.bias).cuda()
     yd = torch.empty((1, p.M), dtype=torch.float32, device="cuda")
 
-    def dense_steps(n):
-        for i in range(n):
-            j = i % nd
-            B.pivot_dense_run(Wds[j].data_ptr(), wd, p.M, p.K, xs[j].data_ptr(), p.K, bd.data_ptr(), yd.data_ptr(),
-                              p.M, 1, p.act, st)
-
-    dense_steps(2 * nd)
-    torch.cuda.synchronize()
-    nde = 200
-    e0.record(); dense_steps(nde); e1.record(); torch.cuda.synchronize()
-    dense_us = e0.elapsed_time(e1) / nde * 1e3
+    dense_us = BU.graph_time(lambda i, s: B.pivot_dense_run(Wds[i % nd].data_ptr(), wd, p.M, p.K, xs[i % ncopies].data_ptr(),
+                                                            p.K, bd.data_ptr(), yd.data_ptr(), p.M, 1, p.act, s),
+                             8 * nd, replays=5)
     xv = xs[0][0]
+    nde = 200
     for j in range(2 * nd):
         torch.mv(Wds[j % nd], xv)
     torch.cuda.synchronize()
@@ -177,6 +188,8 @@ def main():
                    "cold_copies": ncopies},
         "warm_us": round(warm_us, 3),
         "cold_host_clock_us": round(cold_wall_ms * 1e3, 3),
+        "cold_eager_python_launch_us": round(eager_cold_us, 3),
+        "timing": "HIP events around replays of captured graphs of plain launches (exactly K launches)",
         "null_kernel_us": round(null_us, 3),
         "dense_gpu_us": {"own_kernel_cold": round(dense_us, 3), "torch_mv_cold": round(torch_mv_us, 3)},
         "speedup_vs_dense": round(dense_best_us / cold_us, 3),

@@ -22,6 +22,7 @@ import torch
 
 from paper_1712_01084_amd import binding as B
 from paper_1712_01084_amd import workloads as WL
+import bench_util as BU
 
 HBM = 8000.0
 COLD_FOOTPRINT = 2 * (256 + 32) * (1 << 20)
@@ -43,19 +44,9 @@ def workspace(n):
     return ws
 
 
-def ev_time(fn, iters):
-    """Median over 3 repeats of (HIP-event time of `iters` back-to-back calls) / iters, in us."""
-    fn(max(8, iters // 4))
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    ts = []
-    for _ in range(3):
-        e0.record()
-        fn(iters)
-        e1.record()
-        torch.cuda.synchronize()
-        ts.append(e0.elapsed_time(e1) * 1e3 / iters)
-    return float(np.median(ts))
+def gt(enqueue, n_launch, replays=4):
+    """GPU-side us per launch: replays of a captured graph of n_launch plain launches (bench_util.py)."""
+    return BU.graph_time(enqueue, n_launch, replays=replays, repeats=3)
 
 
 def emit(name, us_cold, us_warm, alg_bytes, dense_us=None, extra=None):
@@ -86,14 +77,13 @@ def time_fc(p, iters, name, dense=True):
     ws = workspace(B.pivot_fc_workspace_bytes(plan0, batch))
 
     def go(rot):
-        def f(n):
-            for i in range(n):
-                j = i % ncopies if rot else 0
-                B.pivot_fc_run(plans[j], xs[j].data_ptr(), p.K, yd.data_ptr(), p.M, batch, ws.data_ptr(), ws.numel(), st)
+        def f(i, s):
+            j = i % ncopies if rot else 0
+            B.pivot_fc_run(plans[j], xs[j].data_ptr(), p.K, yd.data_ptr(), p.M, batch, ws.data_ptr(), ws.numel(), s)
         return f
 
-    cold = ev_time(go(True), max(iters, ncopies))
-    warm = ev_time(go(False), iters)
+    cold = gt(go(True), ncopies * max(1, 64 // ncopies))
+    warm = gt(go(False), 100)
     dense_us = None
     if dense:
         Wnat = np.empty_like(p.Wp)
@@ -102,18 +92,22 @@ def time_fc(p, iters, name, dense=True):
         Wds = [torch.from_numpy(Wnat).cuda() for _ in range(nd)]
         bd = torch.from_numpy(p.bias).cuda()
 
-        def god(n):
-            for i in range(n):
-                B.pivot_dense_run(Wds[i % nd].data_ptr(), wd(p), p.M, p.K, xs[i % ncopies].data_ptr(), p.K,
-                                  bd.data_ptr(), yd.data_ptr(), p.M, batch, p.act, st)
+        def god(i, s):
+            B.pivot_dense_run(Wds[i % nd].data_ptr(), wd(p), p.M, p.K, xs[i % ncopies].data_ptr(), p.K,
+                              bd.data_ptr(), yd.data_ptr(), p.M, batch, p.act, s)
 
-        own = ev_time(god, max(40, 2 * nd))
-
-        def got(n):
-            for i in range(n):
-                torch.matmul(xs[i % ncopies], Wds[i % nd].t())
-
-        lib = ev_time(got, max(40, 2 * nd))
+        own = gt(god, 4 * nd)
+        # rocBLAS through torch, launched eagerly (its launch cost is below these kernels' run time)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for i in range(2 * nd):
+            torch.matmul(xs[i % ncopies], Wds[i % nd].t())
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(8 * nd):
+            torch.matmul(xs[i % ncopies], Wds[i % nd].t())
+        e1.record()
+        torch.cuda.synchronize()
+        lib = e0.elapsed_time(e1) * 1e3 / (8 * nd)
         dense_us = min(own, lib)
         del Wds
     emit(name, cold, warm, alg, dense_us,
@@ -138,14 +132,13 @@ def time_chain(probs, iters, name):
     ws = workspace(B.pivot_mlp_workspace_bytes(sets[0][1], 1))
 
     def go(rot):
-        def f(n):
-            for i in range(n):
-                j = i % ncopies if rot else 0
-                B.pivot_mlp_run(sets[j][1], xs[j].data_ptr(), probs[0].K, yd.data_ptr(), M, 1, ws.data_ptr(), ws.numel(), st)
+        def f(i, s):
+            j = i % ncopies if rot else 0
+            B.pivot_mlp_run(sets[j][1], xs[j].data_ptr(), probs[0].K, yd.data_ptr(), M, 1, ws.data_ptr(), ws.numel(), s)
         return f
 
-    cold = ev_time(go(True), max(iters // 2, 2 * ncopies))
-    warm = ev_time(go(False), iters // 2)
+    cold = gt(go(True), ncopies * max(1, 24 // ncopies))
+    warm = gt(go(False), 40)
     emit(name, cold, warm, alg, None, {"launches": len(probs)})
     for plans, mlp in sets:
         B.pivot_mlp_plan_destroy(mlp)
@@ -164,12 +157,11 @@ def time_lstm(lp, name):
     cd = torch.zeros((batch, lp.H), device="cuda")
     ws = workspace(B.pivot_lstm_workspace_bytes(plan, lp.H, lp.I, steps, batch))
 
-    def go(n):
-        for _ in range(n):
-            B.pivot_lstm_run(plan, lp.H, lp.I, xsd.data_ptr(), hd.data_ptr(), cd.data_ptr(), None, steps, batch,
-                             ws.data_ptr(), ws.numel(), st)
+    def go(i, s):
+        B.pivot_lstm_run(plan, lp.H, lp.I, xsd.data_ptr(), hd.data_ptr(), cd.data_ptr(), None, steps, batch,
+                         ws.data_ptr(), ws.numel(), s)
 
-    total = ev_time(go, 5)
+    total = gt(go, 1, replays=5)
     alg = p.algorithmic_bytes(batch)
     emit(name, None, total / steps, alg, None,
          {"steps": steps, "total_us": round(total, 1), "note": "per-step time of the whole loop (matvec + cell); weights "
@@ -189,10 +181,7 @@ def main():
     st = torch.cuda.current_stream().cuda_stream
 
     def null_us():
-        def f(n):
-            for _ in range(n):
-                B.pivot_null_run(st)
-        return ev_time(f, 2000)
+        return gt(lambda i, s: B.pivot_null_run(s), 200, replays=10)
 
     print(json.dumps({"case": "null kernel back to back", "us": round(null_us(), 2)}), flush=True)
     if "1" in which:

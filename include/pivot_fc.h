@@ -240,6 +240,17 @@ int  pivot_dense_run(const void* W_dev, int wdtype, int M, int K,
                      const void* x_dev, int64_t ldx, const float* bias_dev,
                      void* y_dev, int64_t ldy, int batch, int act, void* stream);
 
+/*
+ * The generic sparse comparator: y = act(A x + b), A given in plain CSR
+ * (natural coordinates, all on the device: row_ptr [M+1], col [nnz],
+ * val [nnz] of wdtype), x [K] of wdtype, bias [M] fp32 or NULL, y [M] fp32,
+ * batch 1.  This is the kind of routine a pruned layer is usually handed to;
+ * the paper's second speedup column (Table 1a) is measured against one.
+ */
+int  pivot_csr_run(const int32_t* row_ptr_dev, const int32_t* col_dev, const void* val_dev, int wdtype,
+                   int M, int64_t nnz, const void* x_dev, const float* bias_dev, float* y_dev,
+                   int act, void* stream);
+
 /* Measurement aid: enqueues one empty kernel (a single wavefront that does
  * nothing), so that a harness can report the launch floor of the device next
  * to the layer times (the paper averages whole calls, Section 5.1). */

@@ -476,6 +476,14 @@ int pivot_lstm_run(const pivot_fc_plan_t* plan, int H, int I, const void* xs_dev
 
 int pivot_null_run(void* stream) { return launch_null(stream); }
 
+int pivot_csr_run(const int32_t* row_ptr_dev, const int32_t* col_dev, const void* val_dev, int wdtype, int M,
+                  int64_t nnz, const void* x_dev, const float* bias_dev, float* y_dev, int act, void* stream) {
+    if (!row_ptr_dev || !x_dev || !y_dev || (nnz > 0 && (!col_dev || !val_dev))) { set_error("row_ptr, col, val, x and y are required"); return PIVOT_E_NULL; }
+    if (M < 1 || nnz < 0) { set_error("bad shape"); return PIVOT_E_SHAPE; }
+    if (wdtype != PIVOT_F32 && wdtype != PIVOT_F16) { set_error("unknown wdtype"); return PIVOT_E_UNSUPPORTED; }
+    return launch_csr(row_ptr_dev, col_dev, val_dev, wdtype, M, nnz, x_dev, bias_dev, y_dev, act, stream);
+}
+
 int pivot_dense_run(const void* W_dev, int wdtype, int M, int K, const void* x_dev, int64_t ldx,
                     const float* bias_dev, void* y_dev, int64_t ldy, int batch, int act, void* stream) {
     if (!W_dev || !x_dev || !y_dev) { set_error("W_dev, x_dev and y_dev are required"); return PIVOT_E_NULL; }

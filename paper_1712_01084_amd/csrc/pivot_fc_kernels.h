@@ -158,12 +158,24 @@ struct XStage {
             const int e = tid / NB + k * STEP;
             xsrow[e < ne ? e : dump] = (src[k] >= 0 && row_ok) ? v[k] : WT(0);
         }
+        // longer chunks: further rounds of XP elements per thread, each round's loads issued together
         const int32_t* xi = xidx + (size_t)tile_begin * BW;
-        for (int e = tid / NB + XP * STEP; e < ne; e += STEP) {
-            const int sidx = xi[e];
-            WT vv = WT(0);
-            if (sidx >= 0 && row_ok) vv = xrow[sidx];
-            xsrow[e] = vv;
+        const int emax = ne > 0 ? ne - 1 : 0;
+        for (int e0 = tid / NB + XP * STEP; e0 < ne; e0 += XP * STEP) {
+            int s2[XP];
+            #pragma unroll
+            for (int k = 0; k < XP; ++k) {
+                const int e = e0 + k * STEP;
+                s2[k] = xi[e < emax ? e : emax];
+            }
+            WT v2[XP];
+            #pragma unroll
+            for (int k = 0; k < XP; ++k) v2[k] = xrow[s2[k] > 0 ? s2[k] : 0];
+            #pragma unroll
+            for (int k = 0; k < XP; ++k) {
+                const int e = e0 + k * STEP;
+                xsrow[e < ne ? e : dump] = (s2[k] >= 0 && row_ok) ? v2[k] : WT(0);
+            }
         }
     }
 };

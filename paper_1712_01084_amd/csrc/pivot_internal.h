@@ -108,6 +108,9 @@ int    launch_null(void* stream);
 int    launch_dense(const void* W, int wdtype, int M, int K, const void* x, int64_t ldx,
                     const float* bias, void* y, int64_t ldy, int batch, int act, void* stream);
 
+int    launch_csr(const int32_t* row_ptr, const int32_t* col, const void* val, int wdtype, int M, int64_t nnz,
+                  const void* x, const float* bias, float* y, int act, void* stream);
+
 struct LstmCellLaunch {
     const float* z;             // [batch][4H] gate pre-activations in natural order (bias included)
     const int32_t* invpcol;     // natural input column -> block-space column

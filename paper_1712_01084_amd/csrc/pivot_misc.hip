@@ -13,16 +13,16 @@ namespace pivot {
 template <typename WT>
 __global__ void gather_x_kernel(const WT* x, long long ldx, const int32_t* pcol_pad, WT* xg, int K_pad, int batch) {
     const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    const int b = blockIdx.y;
     if (c >= K_pad) return;
     const int src = pcol_pad[c];
-    for (int b = 0; b < batch; ++b)
-        xg[(size_t)b * K_pad + c] = (src >= 0) ? x[(size_t)b * ldx + src] : WT(0);
+    xg[(size_t)b * K_pad + c] = (src >= 0) ? x[(size_t)b * ldx + src] : WT(0);
 }
 
 int launch_gather_x(const void* x, int64_t ldx, const int32_t* pcol_pad, void* xg, int K_pad, int batch,
                     int wdtype, void* stream) {
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    dim3 grid((K_pad + 255) / 256);
+    dim3 grid((K_pad + 255) / 256, batch);
     if (wdtype == PIVOT_F16)
         hipLaunchKernelGGL(gather_x_kernel<_Float16>, grid, dim3(256), 0, st, (const _Float16*)x, (long long)ldx, pcol_pad, (_Float16*)xg, K_pad, batch);
     else
@@ -125,6 +125,47 @@ int launch_dense(const void* W, int wdtype, int M, int K, const void* x, int64_t
     if (batch == 1) return launch_dense_t<_Float16, 1, 4>(W, M, K, x, ldx, bias, y, ldy, batch, act, st);
     if (batch <= 4) return launch_dense_t<_Float16, 4, 2>(W, M, K, x, ldx, bias, y, ldy, batch, act, st);
     return launch_dense_t<_Float16, 16, 1>(W, M, K, x, ldx, bias, y, ldy, batch, act, st);
+}
+
+// ---------------------------------------------------------------------------
+// generic sparse comparator: y = act(A x + b) with A in plain CSR (the kind of
+// routine a pruned layer is usually handed to; Section 5.1 compares against
+// one).  L lanes share a row; L is the power of two nearest the mean row length.
+// ---------------------------------------------------------------------------
+template <typename WT, int L>
+__global__ void __launch_bounds__(256) csr_spmv_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col,
+                                                       const WT* __restrict__ val, const WT* __restrict__ x,
+                                                       const float* __restrict__ bias, float* __restrict__ y, int M, int act) {
+    const int gid = blockIdx.x * blockDim.x + threadIdx.x;
+    const int row = gid / L, sub = gid % L;
+    const bool ok = row < M;
+    const int b = ok ? row_ptr[row] : 0, e = ok ? row_ptr[row + 1] : 0;
+    float acc = 0.f;
+    for (int k = b + sub; k < e; k += L) acc = fmaf((float)val[k], (float)x[col[k]], acc);
+    acc = group_sum<L>(acc);
+    if (ok && sub == 0) y[row] = apply_act(acc + (bias ? bias[row] : 0.f), act);
+}
+
+template <typename WT>
+static int launch_csr_t(const int32_t* row_ptr, const int32_t* col, const void* val, int M, int64_t nnz, const void* x,
+                        const float* bias, float* y, int act, hipStream_t st) {
+    const double mean = M > 0 ? (double)nnz / M : 0;
+    int L = 1;
+    while (L < 64 && L * 1.5 < mean) L *= 2;
+#define CSR_CASE(L_)                                                                                                     \
+    case L_: hipLaunchKernelGGL((csr_spmv_kernel<WT, L_>), dim3((unsigned)(((size_t)M * L_ + 255) / 256)), dim3(256), 0, \
+                                st, row_ptr, col, (const WT*)val, (const WT*)x, bias, y, M, act); break;
+    switch (L) { CSR_CASE(1) CSR_CASE(2) CSR_CASE(4) CSR_CASE(8) CSR_CASE(16) CSR_CASE(32) default: CSR_CASE(64) }
+#undef CSR_CASE
+    HIP_TRY(hipGetLastError());
+    return PIVOT_OK;
+}
+
+int launch_csr(const int32_t* row_ptr, const int32_t* col, const void* val, int wdtype, int M, int64_t nnz, const void* x,
+               const float* bias, float* y, int act, void* stream) {
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (wdtype == PIVOT_F32) return launch_csr_t<float>(row_ptr, col, val, M, nnz, x, bias, y, act, st);
+    return launch_csr_t<_Float16>(row_ptr, col, val, M, nnz, x, bias, y, act, st);
 }
 
 // ---------------------------------------------------------------------------

@@ -43,30 +43,28 @@ void choose_schedule(HostPlan& hp) {
     const size_t tile_bytes = (size_t)d.bh * d.bw * elem_size(d.wdtype);
     int max_row = 0;
     for (int i = 0; i < hp.nbr; ++i) max_row = std::max(max_row, hp.row_ptr[i + 1] - hp.row_ptr[i]);
-    const int avg_row = hp.nbr ? (hp.T + hp.nbr - 1) / hp.nbr : 0;
 
-    // Row slices: every slice is an independent work item with no reduction
-    // across slices, so slicing is the cheapest way to get more of them.
+    // Measured on MI355X (GPU-side time of back-to-back launches): a block row that
+    // is cut in pieces pays about 1.2 us for the hand-over between workgroups, 16
+    // wavefronts per workgroup about 0.7 us more than 4, and the best point is about
+    // one workgroup per compute unit.  So: slice rows (no hand-over) until there are
+    // about 256 work items, keep block rows whole unless LDS forces a cut or a work
+    // item would stream 256 KB or more while compute units sit idle, and size the
+    // workgroup to the bytes it streams.
     int sl = d.row_slices;
     if (sl == 0) {
         sl = 1;
-        while (sl < 8 && hp.nbr * sl < 512 && fc_row_slices(d.wdtype, d.bh, d.bw, 1, sl * 2) == sl * 2) sl *= 2;
+        while (sl < 8 && hp.nbr * sl < 256 && fc_row_slices(d.wdtype, d.bh, d.bw, 1, sl * 2) == sl * 2) sl *= 2;
     }
     if (d.device >= 0) sl = fc_row_slices(d.wdtype, d.bh, d.bw, 1, sl);
     hp.row_slices = sl;
 
-    // Chunk size: a work item of 16 wavefronts keeps 128 KB of tile values in
-    // flight, which bounds what is worth giving to one; block rows are cut
-    // further only while that yields fewer than one work item per compute unit
-    // and the pieces stay above 16 KB.
+    const size_t slice_bytes = std::max<size_t>(1, tile_bytes / sl);
     int ct = d.chunk_tiles;
     if (ct == 0) {
-        const size_t slice_bytes = std::max<size_t>(1, tile_bytes / sl);
-        int cap = (int)std::max<size_t>(1, (128 * 1024) / slice_bytes);
-        cap = std::min(cap, max_chunk_tiles(d));
-        cap = std::min(cap, std::max(4 * avg_row, 8));
+        const int cap = max_chunk_tiles(d);
         int parts = std::max(1, (max_row + cap - 1) / cap);
-        while ((size_t)hp.nbr * sl * parts < 256 && (size_t)(max_row / (parts * 2)) * slice_bytes >= 16 * 1024) parts *= 2;
+        while ((size_t)hp.nbr * sl * parts < 256 && (size_t)max_row * slice_bytes / parts >= 256 * 1024) parts *= 2;
         ct = std::max(1, (max_row + parts - 1) / parts);
     }
     if (d.device >= 0) ct = std::min(ct, max_chunk_tiles(d));
@@ -74,9 +72,8 @@ void choose_schedule(HostPlan& hp) {
 
     int nw = d.wg_waves;
     if (nw == 0) {
-        // one wavefront keeps about 8 KB in flight
-        size_t big = (size_t)std::min(ct, std::max(max_row, 1)) * (tile_bytes / sl);
-        nw = big <= 4 * 8192 ? 4 : (big <= 8 * 8192 ? 8 : 16);
+        const size_t big = (size_t)std::min(ct, std::max(max_row, 1)) * slice_bytes;
+        nw = big <= 48 * 1024 ? 4 : (big <= 256 * 1024 ? 8 : 16);
     }
     hp.wg_waves = nw;
 }

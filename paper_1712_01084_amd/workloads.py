@@ -182,7 +182,10 @@ def gen_fc(M, K, bh, bw, frac, seed, *, mask="uniform", wdtype=F32, batch=1,
            prow=None, pcol=None, rng=None, draw_x=True) -> FCProblem:
     rng = np.random.default_rng(seed) if rng is None else rng
     nbr, nbc = -(-M // bh), -(-K // bw)
-    if mask == "uniform":
+    if isinstance(mask, np.ndarray):
+        tm = np.ascontiguousarray(mask, dtype=np.uint8)
+        assert tm.shape == (nbr, nbc)
+    elif mask == "uniform":
         tm = mask_uniform(rng, nbr, nbc, frac)
     elif mask == "balanced":
         tm = mask_balanced(rng, nbr, nbc, frac)
@@ -193,9 +196,6 @@ def gen_fc(M, K, bh, bw, frac, seed, *, mask="uniform", wdtype=F32, batch=1,
     elif mask == "blockdiag":
         assert nbr == nbc
         tm = mask_block_diagonal(nbr)
-    elif isinstance(mask, np.ndarray):
-        tm = np.ascontiguousarray(mask, dtype=np.uint8)
-        assert tm.shape == (nbr, nbc)
     else:
         raise ValueError(mask)
     if prow is None:
@@ -295,12 +295,32 @@ def config5(seed=0, batch=8, H=2048, I=1024, steps=256, frac=0.125):
     return LSTMProblem(fc, H, I, xs, h0, c0)
 
 
-def paper_grid_case(size, fill, seed=0, wdtype=F32, batch=1):
-    """Square block-diagonal matrix with 1/fill identical square blocks of
-    edge size*fill (Section 5: size 512 at 6.25 % is 16 blocks of 32x32)."""
+def paper_grid_case(size, fill, seed=0, wdtype=F32, batch=1, perms="random", act=ACT_NONE):
+    """The paper's experiment structure (Section 5): a square matrix with 1/fill
+    identical square blocks of edge size*fill on the diagonal, no two sharing
+    rows or columns (size 512 at 6.25 % is 16 blocks of 32x32).  Blocks larger
+    than the largest device tile (64) are cut into 64x64 tiles; blocks smaller
+    than the smallest (8) share an 8x8 tile on the diagonal, with zeros between
+    them (the values outside the true blocks are zeroed here)."""
     nblk = int(round(1.0 / fill))
     edge = size // nblk
-    assert edge * nblk == size
-    return gen_fc(size, size, edge, edge, fill, seed, mask="blockdiag",
-                  wdtype=wdtype, batch=batch, act=ACT_NONE,
-                  name="grid_%d_%g" % (size, fill * 100))
+    assert edge * nblk == size and edge >= 1
+    tile = min(max(edge, 8), 64)
+    nbr = -(-size // tile)
+    idx = np.arange(nbr)
+    if edge >= tile:
+        per = edge // tile
+        mask = (idx[:, None] // per == idx[None, :] // per).astype(np.uint8)
+    else:
+        mask = np.eye(nbr, dtype=np.uint8)
+    p = gen_fc(size, size, tile, tile, fill, seed, mask=mask, wdtype=wdtype, batch=batch, act=act, perms=perms,
+               name="grid_%d_%g" % (size, fill * 100))
+    if edge < tile:
+        r = np.arange(size)
+        p.Wp[(r[:, None] // edge) != (r[None, :] // edge)] = 0
+    p.meta.update(block_edge=edge, n_blocks=nblk, fill=fill)
+    return p
+
+
+PAPER_GRID_SIZES = (64, 128, 256, 512, 1024, 2048, 4096)
+PAPER_GRID_FILLS = (0.03125, 0.0625, 0.125, 0.25)

@@ -22,6 +22,24 @@ def test_paper_dimension_example_block_diagonal():
     assert np.array_equal(p.tile_mask, np.eye(int(nblk), dtype=np.uint8))
     # no two blocks share rows or columns; kept coefficients = fill * size^2
     assert p.T * p.bh * p.bw == int(float(fill) / 100.0 * int(size) ** 2)
+    assert p.meta["block_edge"] == int(edge) and p.meta["n_blocks"] == int(nblk)
+
+
+def test_paper_grid_large_and_small_blocks():
+    big = WL.paper_grid_case(1024, 0.25)                 # 4 blocks of 256x256 -> 64x64 tiles, 4x4 tiles per block
+    assert (big.bh, big.bw, big.nbr) == (64, 64, 16) and big.T == 4 * 16
+    assert np.all(big.tile_mask[:4, :4] == 1) and np.all(big.tile_mask[:4, 4:] == 0)
+    assert big.T * 64 * 64 == 1024 * 1024 // 4
+    small = WL.paper_grid_case(64, 0.03125)              # 32 blocks of 2x2 inside 8x8 tiles on the diagonal
+    assert (small.bh, small.nbr, small.T) == (8, 8, 8)
+    nz = small.Wp != 0
+    r = np.arange(64)
+    assert not np.any(nz & ((r[:, None] // 2) != (r[None, :] // 2)))      # nothing outside the 2x2 blocks
+    assert int(nz.sum()) <= 32 * 4 and not nz[0, 2] and not nz[2, 0]
+    for size in WL.PAPER_GRID_SIZES:
+        for fill in WL.PAPER_GRID_FILLS:
+            nblk = int(round(1 / fill))
+            assert size % nblk == 0
 
 
 def test_linear_speedup_is_reciprocal_fill():
