@@ -327,21 +327,35 @@ __global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(PIVOT_LEAD_PARAMS, FcA
         #pragma unroll
         for (int b = 0; b < NB; ++b) acc[j][b] = 0.f;
 
-    for (int g0 = wave; g0 < ngroups; g0 += NW * U) {
+    auto consume = [&](int u, int g) {
+        const int tl = g * TPL + ts;
+        #pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const V xv = *reinterpret_cast<const V*>(xs + b * a.xs_stride + tl * BW + cg * VEC);
+            #pragma unroll
+            for (int j = 0; j < NL; ++j) acc[j][b] = dot_vec(w[u][j], xv, acc[j][b]);
+        }
+    };
+    // All rounds but the last: every group is complete, and each register slot is
+    // refilled as soon as it has been consumed, so the wave keeps its 8 loads in
+    // flight instead of draining them once per round.
+    int g0 = wave;
+    for (; g0 + NW * U < ngroups; g0 += NW * U) {
         #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int g = g0 + u * NW;
-            const int tl = g * TPL + ts;
-            if (g < ngroups && tl < ntiles) {
-                #pragma unroll
-                for (int b = 0; b < NB; ++b) {
-                    const V xv = *reinterpret_cast<const V*>(xs + b * a.xs_stride + tl * BW + cg * VEC);
-                    #pragma unroll
-                    for (int j = 0; j < NL; ++j) acc[j][b] = dot_vec(w[u][j], xv, acc[j][b]);
-                }
-            }
+            consume(u, g);
+            const int gn = g + NW * U;
+            const int gc = gn < gmax ? gn : gmax;
+            #pragma unroll
+            for (int j = 0; j < NL; ++j) w[u][j] = load16<V>(vbase + gc * gstride + j * 64 * VEC);
         }
-        if (g0 + NW * U < ngroups) issue(g0 + NW * U);
+    }
+    // last round: may be partial
+    #pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int g = g0 + u * NW;
+        if (g < ngroups && g * TPL + ts < ntiles) consume(u, g);
     }
 
     // lanes -> rows
@@ -465,19 +479,38 @@ __global__ void __launch_bounds__(NW * 64) fc_mfma_kernel(PIVOT_LEAD_PARAMS, FcA
     #pragma unroll
     for (int rb = 0; rb < RB; ++rb) acc[rb] = acc_t(0);
 
-    if (wave < ntiles) issue(wave);
-    for (int t0 = wave; t0 < ntiles; t0 += NW * U) {
+    // One tile's loads: block column (scalar), A fragments, B fragments.
+    auto fill = [&](int u, int t) {
+        const int tc = t < tmax ? t : tmax;
+        const int ci = ci_base[tc];
+        #pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+            #pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+                w[u][rb * KS + ks] = load16<f16x8>(vbase + (size_t)tc * a.tile_elems + rb * MR * BW + ks * MK);
+        #pragma unroll
+        for (int ks = 0; ks < KS; ++ks) xv[u][ks] = load16<f16x8>(xb + (size_t)ci * BW + ks * MK);
+    };
+    auto consume = [&](int u) {
+        #pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+            #pragma unroll
+            for (int rb = 0; rb < RB; ++rb) acc[rb] = MF::run(w[u][rb * KS + ks], xv[u][ks], acc[rb]);
+    };
+
+    issue(wave);
+    // all rounds but the last: consume a slot and refill it at once (loads stay in flight)
+    int t0 = wave;
+    for (; t0 + NW * U < ntiles; t0 += NW * U) {
         #pragma unroll
         for (int u = 0; u < U; ++u) {
-            if (t0 + u * NW < ntiles) {
-                #pragma unroll
-                for (int ks = 0; ks < KS; ++ks)
-                    #pragma unroll
-                    for (int rb = 0; rb < RB; ++rb) acc[rb] = MF::run(w[u][rb * KS + ks], xv[u][ks], acc[rb]);
-            }
+            consume(u);
+            fill(u, t0 + u * NW + NW * U);
         }
-        if (t0 + NW * U < ntiles) issue(t0 + NW * U);
     }
+    #pragma unroll
+    for (int u = 0; u < U; ++u)
+        if (t0 + u * NW < ntiles) consume(u);
 
     // waves -> one sum: rounds of (up to) 4 writers into a 4-slot LDS buffer
     auto put = [&](int w_slot) {
