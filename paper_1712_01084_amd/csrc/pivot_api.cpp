@@ -193,12 +193,12 @@ int prepare(const pivot_fc_plan_t* plan, int batch, void* ws, size_t ws_bytes, F
     if (reinterpret_cast<uintptr_t>(ws) % 16 != 0) { set_error("workspace must be 16-byte aligned"); return PIVOT_E_WORKSPACE; }
     const DevPlan& d = plan->dev;
     L.vals = d.vals; L.col_idx = d.col_idx; L.chunks = d.chunks; L.part_base = d.part_base; L.bias_p = d.bias_p;
-    L.M_pad = h.M_pad; L.K_pad = h.K_pad; L.bh = h.d.bh; L.bw = h.d.bw; L.wdtype = h.d.wdtype; L.act = h.d.act;
+    L.M_pad = h.M_pad; L.K_pad = h.K_pad; L.bh = h.d.bh; L.bw = h.d.bw; L.wdtype = h.d.wdtype; L.layout = h.d.layout; L.T = h.T; L.act = h.d.act;
     L.nchunks = h.nchunks; L.nbr = h.nbr; L.chunk_tiles = h.chunk_tiles; L.wg_waves = h.wg_waves;
     L.row_slices = h.row_slices;
     L.uniform_ct = h.uniform_ct; L.uniform_parts = h.uniform_parts;
     L.batch = batch;
-    int nbt = fc_batch_tile(h.d.wdtype, h.d.bh, h.d.bw, batch);
+    int nbt = fc_batch_tile(h.d.layout, h.d.wdtype, h.d.bh, h.d.bw, batch);
     int ngy = (batch + nbt - 1) / nbt;
     L.tickets = reinterpret_cast<uint32_t*>(ws);
     L.partials = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + fc_ticket_bytes(h.nbr, ngy, h.row_slices));
@@ -211,7 +211,7 @@ int prepare(const pivot_fc_plan_t* plan, int batch, void* ws, size_t ws_bytes, F
 int natural_input(const pivot_fc_plan_t* plan, const void* x_dev, int64_t ldx, int batch, void* xg, void* stream,
                   FcLaunch& L) {
     const HostPlan& h = plan->host;
-    if (fc_uses_matrix_cores(h.d.wdtype, h.d.bh, h.d.bw, batch)) {
+    if (fc_uses_matrix_cores(h.d.layout, h.d.wdtype, h.d.bh, h.d.bw, batch)) {
         int rc = launch_gather_x(x_dev, ldx, plan->dev.pcol_pad, xg, h.K_pad, batch, h.d.wdtype, stream);
         if (rc != PIVOT_OK) return rc;
         L.x = xg; L.ldx = h.K_pad; L.xidx = plan->dev.xidx_blk; L.x_block_order = 1;

@@ -52,6 +52,7 @@ struct FcArgs {
     int tile_elems;             // bh_full * bw
     int uniform_ct;             // > 0: every chunk has exactly this many tiles and chunk i starts at tile i*uniform_ct,
     int uniform_parts;          //      uniform_parts chunks per block row: the descriptor is computed, not loaded
+    int T;                      // kept tiles in the whole plan (the CBR layout strides by it)
 };
 
 // The seven pointers every wavefront needs first are separate leading kernel
@@ -66,6 +67,7 @@ struct FcArgs {
 int launch_gemv_f32(const FcArgs& a, int bhs, int bw, int nb, int nw, dim3 grid, size_t smem, hipStream_t st);
 int launch_gemv_f16(const FcArgs& a, int bhs, int bw, int nb, int nw, dim3 grid, size_t smem, hipStream_t st);
 int launch_mfma_f16(const FcArgs& a, int kind, int bhs, int bw, int nw, dim3 grid, size_t smem, hipStream_t st);
+int launch_colmajor(const FcArgs& a, int layout, int wdtype, int bh, int bw, int nw, dim3 grid, size_t smem, hipStream_t st);
 
 #define PIVOT_SHAPES(X) \
     X(8, 8) X(8, 16) X(8, 32) X(8, 64) \

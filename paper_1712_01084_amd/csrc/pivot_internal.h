@@ -78,7 +78,7 @@ struct FcLaunch {
     const int32_t* xidx;        // [T*bw]: index into x of column c of tile t (-1 = padding): through pcol for
                                 // natural-order x, the block-space column itself for x already in block order
     const int32_t* scatter;     // [M_pad] block-space row -> index into y (-1 = padding row, not stored)
-    int M_pad, K_pad, bh, bw, wdtype, act, nchunks, nbr, chunk_tiles, wg_waves, row_slices;
+    int M_pad, K_pad, bh, bw, wdtype, layout, T, act, nchunks, nbr, chunk_tiles, wg_waves, row_slices;
     int uniform_ct, uniform_parts;  // > 0: regular schedule, the kernels compute the chunk descriptor
     int x_block_order;          // 1: x is [batch][K_pad] in block order (what the matrix-core kernel needs)
     // data
@@ -92,9 +92,9 @@ struct FcLaunch {
 };
 
 // Batch rows one launch of the layer kernel covers (grid.y repeats it).
-int    fc_batch_tile(int wdtype, int bh, int bw, int batch);
-bool   fc_uses_matrix_cores(int wdtype, int bh, int bw, int batch);
-int    fc_row_slices(int wdtype, int bh, int bw, int batch, int want);
+int    fc_batch_tile(int layout, int wdtype, int bh, int bw, int batch);
+bool   fc_uses_matrix_cores(int layout, int wdtype, int bh, int bw, int batch);
+int    fc_row_slices(int layout, int wdtype, int bh, int bw, int batch, int want);
 // Workspace of one layer application: [arrival counters][partials of split rows][x in block order (matrix path)]
 size_t fc_ticket_bytes(int nbr, int ngy, int slices);
 size_t fc_partial_bytes(const HostPlan& hp, int batch);

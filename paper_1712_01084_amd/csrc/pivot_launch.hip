@@ -11,25 +11,28 @@ static int mfma_kind(int wdtype, int bh, int bw) {
     return -1;
 }
 
-bool fc_uses_matrix_cores(int wdtype, int bh, int bw, int batch) {
-    return batch >= 8 && mfma_kind(wdtype, bh, bw) >= 0;
+bool fc_uses_matrix_cores(int layout, int wdtype, int bh, int bw, int batch) {
+    // the matrix-core kernel reads A fragments from row-major (BRC) tiles only
+    return layout == PIVOT_BRC && batch >= 8 && mfma_kind(wdtype, bh, bw) >= 0;
 }
 
-int fc_batch_tile(int wdtype, int bh, int bw, int batch) {
-    if (fc_uses_matrix_cores(wdtype, bh, bw, batch)) return mfma_kind(wdtype, bh, bw) == 0 ? 16 : 32;
+int fc_batch_tile(int layout, int wdtype, int bh, int bw, int batch) {
+    if (layout != PIVOT_BRC) return 1;       // the column-major kernels take one batch row per launch row
+    if (fc_uses_matrix_cores(layout, wdtype, bh, bw, batch)) return mfma_kind(wdtype, bh, bw) == 0 ? 16 : 32;
     return batch >= 3 ? 4 : batch;
 }
 
 // Largest number of row slices <= want that the chosen kernel supports: a
 // slice of the vector kernel must hold at least one 1 KB wave-load and 8 rows,
 // a slice of the matrix kernel whole MFMA row blocks.
-int fc_row_slices(int wdtype, int bh, int bw, int batch, int want) {
+int fc_row_slices(int layout, int wdtype, int bh, int bw, int batch, int want) {
+    if (layout != PIVOT_BRC) return 1;       // a row slice is contiguous only in row-major tiles
     int sl = want < 1 ? 1 : want;
     while (sl > 1) {
         bool ok = (bh % sl == 0);
         const int bhs = bh / sl;
         if (ok) {
-            if (fc_uses_matrix_cores(wdtype, bh, bw, batch)) {
+            if (fc_uses_matrix_cores(layout, wdtype, bh, bw, batch)) {
                 const int mr = mfma_kind(wdtype, bh, bw) == 0 ? 16 : 32;
                 ok = (bhs % mr == 0);
             } else {
@@ -48,29 +51,29 @@ size_t fc_ticket_bytes(int nbr, int ngy, int slices) { return (size_t)4 * kTicke
 
 size_t fc_partial_bytes(const HostPlan& hp, int batch) {
     if (hp.max_parts <= 1) return 0;
-    const int nbt = fc_batch_tile(hp.d.wdtype, hp.d.bh, hp.d.bw, batch);
+    const int nbt = fc_batch_tile(hp.d.layout, hp.d.wdtype, hp.d.bh, hp.d.bw, batch);
     const int ngy = (batch + nbt - 1) / nbt;
     return align_up((size_t)4 * hp.nchunks * hp.d.bh * nbt * ngy, 256);
 }
 
 size_t fc_workspace_bytes(const HostPlan& hp, int batch) {
     if (batch < 1) return 0;
-    const int nbt = fc_batch_tile(hp.d.wdtype, hp.d.bh, hp.d.bw, batch);
+    const int nbt = fc_batch_tile(hp.d.layout, hp.d.wdtype, hp.d.bh, hp.d.bw, batch);
     const int ngy = (batch + nbt - 1) / nbt;
     // counters are sized for the plan's slice count (a launch may use fewer)
     return fc_ticket_bytes(hp.nbr, ngy, hp.row_slices) + fc_partial_bytes(hp, batch);
 }
 
 size_t fc_gather_bytes(const HostPlan& hp, int batch) {
-    if (!fc_uses_matrix_cores(hp.d.wdtype, hp.d.bh, hp.d.bw, batch)) return 0;
+    if (!fc_uses_matrix_cores(hp.d.layout, hp.d.wdtype, hp.d.bh, hp.d.bw, batch)) return 0;
     return align_up((size_t)batch * hp.K_pad * elem_size(hp.d.wdtype), 256);
 }
 
 int launch_fc(const FcLaunch& L) {
-    const bool mc = fc_uses_matrix_cores(L.wdtype, L.bh, L.bw, L.batch);
-    const int nbt = fc_batch_tile(L.wdtype, L.bh, L.bw, L.batch);
+    const bool mc = fc_uses_matrix_cores(L.layout, L.wdtype, L.bh, L.bw, L.batch);
+    const int nbt = fc_batch_tile(L.layout, L.wdtype, L.bh, L.bw, L.batch);
     const int ngy = (L.batch + nbt - 1) / nbt;
-    const int sl = fc_row_slices(L.wdtype, L.bh, L.bw, L.batch, L.row_slices);
+    const int sl = fc_row_slices(L.layout, L.wdtype, L.bh, L.bw, L.batch, L.row_slices);
     const int bhs = L.bh / sl;
     const int nw = (L.wg_waves == 16 || L.wg_waves == 8) ? L.wg_waves : 4;
     const int es = elem_size(L.wdtype);
@@ -83,6 +86,7 @@ int launch_fc(const FcLaunch& L) {
     a.nchunks = L.nchunks; a.nbr = L.nbr;
     a.bh_full = L.bh; a.tile_elems = L.bh * L.bw;
     a.uniform_ct = L.uniform_ct; a.uniform_parts = L.uniform_parts;
+    a.T = L.T;
     dim3 grid(L.nchunks, ngy, sl);
     hipStream_t st = reinterpret_cast<hipStream_t>(L.stream);
 
@@ -99,6 +103,7 @@ int launch_fc(const FcLaunch& L) {
     size_t red_bytes = (size_t)nw * bhs * nbt * 4;
     size_t smem = align_up(xs_bytes > red_bytes ? xs_bytes : red_bytes, 16);
     if (smem > 64 * 1024) { set_error("chunk does not fit in LDS (%zu bytes)", smem); return PIVOT_E_UNSUPPORTED; }
+    if (L.layout != PIVOT_BRC) return launch_colmajor(a, L.layout, L.wdtype, L.bh, L.bw, nw, grid, smem, st);
     if (L.wdtype == PIVOT_F32) return launch_gemv_f32(a, bhs, L.bw, nbt, nw, grid, smem, st);
     return launch_gemv_f16(a, bhs, L.bw, nbt, nw, grid, smem, st);
 }

@@ -25,7 +25,6 @@ static bool is_pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
 
 bool device_supported(const pivot_fc_desc& d, std::string* why) {
     auto fail = [&](const char* m) { if (why) *why = m; return false; };
-    if (d.layout != PIVOT_BRC) return fail("the device kernels read the BRC layout only");
     if (!is_pow2(d.bh) || !is_pow2(d.bw)) return fail("tile sides must be powers of two on the device path");
     if (d.bh < 8 || d.bh > 64 || d.bw < 8 || d.bw > 64) return fail("tile sides must lie in 8..64 on the device path");
     return true;
@@ -54,9 +53,9 @@ void choose_schedule(HostPlan& hp) {
     int sl = d.row_slices;
     if (sl == 0) {
         sl = 1;
-        while (sl < 8 && hp.nbr * sl < 256 && fc_row_slices(d.wdtype, d.bh, d.bw, 1, sl * 2) == sl * 2) sl *= 2;
+        while (sl < 8 && hp.nbr * sl < 256 && fc_row_slices(d.layout, d.wdtype, d.bh, d.bw, 1, sl * 2) == sl * 2) sl *= 2;
     }
-    if (d.device >= 0) sl = fc_row_slices(d.wdtype, d.bh, d.bw, 1, sl);
+    if (d.device >= 0) sl = fc_row_slices(d.layout, d.wdtype, d.bh, d.bw, 1, sl);
     hp.row_slices = sl;
 
     const size_t slice_bytes = std::max<size_t>(1, tile_bytes / sl);

@@ -18,11 +18,11 @@ def tdtype(p):
     return torch.float32 if p.wdtype == WL.F32 else torch.float16
 
 
-def dev_plan(p, chunk_tiles=0, natural=False, wg_waves=0, row_slices=0):
+def dev_plan(p, chunk_tiles=0, natural=False, wg_waves=0, row_slices=0, layout=B.PIVOT_BRC):
     W = O.unpivot_weights(p.Wp, p.prow, p.pcol) if natural else p.Wp
     return B.pivot_fc_plan(p.M, p.K, p.bh, p.bw, wd(p), W,
                            B.PIVOT_W_NATURAL if natural else B.PIVOT_W_PIVOTED,
-                           p.tile_mask, p.prow, p.pcol, p.bias, act=p.act,
+                           p.tile_mask, p.prow, p.pcol, p.bias, act=p.act, layout=layout,
                            chunk_tiles=chunk_tiles, device=0, wg_waves=wg_waves, row_slices=row_slices)
 
 
@@ -55,8 +55,8 @@ def oracle_of(p, x=None):
     return O.oracle_fc(p.Wp, p.tile_mask, p.prow, p.pcol, p.bias, x, p.bh, p.bw, p.act, return_scale=True)
 
 
-def check_fc(p, chunk_tiles=0, natural=False, repeats=2, x=None, wg_waves=0, row_slices=0):
-    plan = dev_plan(p, chunk_tiles=chunk_tiles, natural=natural, wg_waves=wg_waves, row_slices=row_slices)
+def check_fc(p, chunk_tiles=0, natural=False, repeats=2, x=None, wg_waves=0, row_slices=0, layout=B.PIVOT_BRC):
+    plan = dev_plan(p, chunk_tiles=chunk_tiles, natural=natural, wg_waves=wg_waves, row_slices=row_slices, layout=layout)
     try:
         y = run_fc(plan, p, x=x, repeats=repeats)
     finally:

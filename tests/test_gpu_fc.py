@@ -38,6 +38,26 @@ def test_row_slices_and_wave_counts(wdtype, bh, bw, waves, slices):
         G.check_fc(p, chunk_tiles=12, wg_waves=waves, row_slices=slices)    # whole rows
 
 
+@pytest.mark.parametrize("layout", [B.PIVOT_BCR, B.PIVOT_CBR])
+@pytest.mark.parametrize("wdtype", [WL.F32, WL.F16])
+@pytest.mark.parametrize("bh,bw", SHAPES)
+def test_column_major_layouts_every_tile_shape(bh, bw, wdtype, layout):
+    M, K = 5 * bh - 3, 9 * bw - 5
+    for batch, ct, waves in ((1, 2, 4), (3, 9, 8), (1, 4, 16)):
+        p = WL.gen_fc(M, K, bh, bw, 0.6, seed=200 + bh + bw, wdtype=wdtype, batch=batch, act=WL.ACT_RELU)
+        p.tile_mask[2, :] = 0
+        G.check_fc(p, chunk_tiles=ct, wg_waves=waves, layout=layout)
+
+
+@pytest.mark.parametrize("layout", [B.PIVOT_BCR, B.PIVOT_CBR])
+def test_column_major_layouts_full_configs(layout):
+    G.check_fc(WL.config1(seed=0), layout=layout)
+    G.check_fc(WL.config2(seed=0), layout=layout)
+    G.check_fc(WL.config3(seed=0, frac=0.25, batch=1), layout=layout)
+    G.check_fc(WL.config3(seed=0, frac=0.1, batch=16), layout=layout)      # batch 16 through the vector kernel
+    G.check_fc(WL.paper_grid_case(1024, 0.125, seed=1), layout=layout)
+
+
 @pytest.mark.parametrize("batch", [1, 2, 3, 4, 5, 8])
 def test_batches_fp32(batch):
     p = WL.gen_fc(200, 328, 16, 16, 0.5, seed=7, batch=batch, act=WL.ACT_NONE)

@@ -112,7 +112,8 @@ def test_error_paths_return_codes():
     assert code(chunk_tiles=-2) == B.PIVOT_E_SHAPE
     # shapes the device kernels do not cover are refused before any GPU call
     assert code(device=0) == B.PIVOT_E_UNSUPPORTED            # 4x4 tiles
-    assert code(device=0, bh=8, bw=8, M=16, K=16, tile_mask=np.ones((2, 2), np.uint8), layout=B.PIVOT_CBR) == B.PIVOT_E_UNSUPPORTED
+    assert code(device=0, bh=8, bw=6, M=16, K=12, W=p.Wp[:, :12].copy(), pcol=np.arange(12, dtype=np.int32),
+                tile_mask=np.ones((2, 2), np.uint8)) == B.PIVOT_E_UNSUPPORTED   # not a power of two
     B.pivot_fc_plan_destroy(None)                             # NULL-safe
 
 
