@@ -241,6 +241,24 @@ int  pivot_dense_run(const void* W_dev, int wdtype, int M, int K,
                      void* y_dev, int64_t ldy, int batch, int act, void* stream);
 
 /*
+ * pivot_feedback_search - the producer of pivot_fc_plan's inputs: feed-back
+ * PBP pruning (Section 3.2).  From the magnitudes |W| of a trained dense layer
+ * it picks prow and pcol by `levels` rounds of bisection: every block's rows
+ * and columns are split in halves so that the upper-left and lower-right
+ * sub-blocks hold as much magnitude as a greedy alternating search finds (the
+ * off-diagonal sub-blocks are what pruning then deletes, so every level halves
+ * the fill-in).  The search starts from prow0 / pcol0 (the paper starts from
+ * random permutations; the caller draws them) and is deterministic.  All
+ * pointers are host memory.  absW is M*K row-major, non-negative.  On return
+ * W'[r][c] = W[prow_out[r]][pcol_out[c]] has its kept mass in 2^levels diagonal
+ * blocks whose row ranges follow from halving [0,M) `levels` times (floor
+ * first), columns likewise; *captured_mass (optional) is the sum of absW there.
+ */
+int  pivot_feedback_search(const float* absW, int M, int K, int levels, int max_iter,
+                           const int32_t* prow0, const int32_t* pcol0,
+                           int32_t* prow_out, int32_t* pcol_out, double* captured_mass);
+
+/*
  * The generic sparse comparator: y = act(A x + b), A given in plain CSR
  * (natural coordinates, all on the device: row_ptr [M+1], col [nnz],
  * val [nnz] of wdtype), x [K] of wdtype, bias [M] fp32 or NULL, y [M] fp32,

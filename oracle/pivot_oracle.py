@@ -22,7 +22,11 @@ Parity status of every function here: pinned by tests/test_oracle_*.py
 (exact rational brute force through explicit permutation matrices, the
 paper's printed index-array example, reduction to a library matvec, closed
 forms), except the free-running 256-step LSTM trajectory, which is
-"parity unpinned" beyond the per-step check.
+"parity unpinned" beyond the per-step check.  The feed-back permutation
+search at the end of the file is a heuristic the paper only outlines; its
+pins (tests/test_feedback_search.py) are brute force over all splits of tiny
+matrices, exact recovery of a planted block structure and the paper's printed
+fill-in factors.
 """
 from __future__ import annotations
 
@@ -387,3 +391,102 @@ def oracle_mlp_plan(prows, pcols, Mpads):
         qs.append(q)
         dsts.append(dst)
     return qs, dsts
+
+
+# ----------------------------------------------------------------------------
+# feed-back PBP pruning (Section 3.2): the producer of prow / pcol.
+#
+# The paper gives the objective and the search style, not a procedure: from the
+# magnitudes of a trained dense layer, starting from random permutations, a
+# greedy search picks P_row / P_col that maximise the magnitude inside the
+# upper-left and lower-right sub-blocks; the off-diagonal sub-blocks are
+# deleted (half the coefficients of the block); the same is repeated on every
+# sub-block (three times for 12.5 % fill-in, twice for 25 %).
+#
+# Reading used here (a heuristic, so the steps are written out in order):
+# a block is a list of rows R and a list of columns C in their current order,
+# with halves R1|R2 and C1|C2 of sizes floor(n/2) and the rest.  One greedy
+# half-step re-chooses R1 as the |R1| rows with the largest
+# gain(r) = mass(r, C1) - mass(r, C2) (ties: earlier in the list first; both
+# halves keep the list's relative order), which is the best R1 for the given
+# column split; the next half-step does the same for the columns.  Half-steps
+# alternate until neither changes anything (or max_iter rounds).  Sums are
+# float64, added in list order.
+# ----------------------------------------------------------------------------
+
+def _best_half(gain, n1):
+    """Positions chosen for the first half: the n1 largest gains, earlier
+    position first among equals."""
+    order = sorted(range(len(gain)), key=lambda i: (-gain[i], i))
+    return set(order[:n1])
+
+
+def _seq_sum(A):
+    """Row sums added strictly left to right in float64."""
+    if A.shape[1] == 0:
+        return np.zeros(A.shape[0])
+    return np.cumsum(A.astype(np.float64), axis=1)[:, -1]
+
+
+def feedback_half_step(absW, own, other, n1, o1, rows_side):
+    """One greedy half-step.  Returns the re-ordered list of ``own``."""
+    own = list(own)
+    other = list(other)
+    A = absW[np.ix_(own, other)] if rows_side else absW[np.ix_(other, own)].T
+    gain = _seq_sum(A[:, :o1]) - _seq_sum(A[:, o1:])
+    first = _best_half(gain.tolist(), n1)
+    return [own[i] for i in range(len(own)) if i in first] + [own[i] for i in range(len(own)) if i not in first]
+
+
+def feedback_search(absW, levels, prow0, pcol0, max_iter=50):
+    """Recursive greedy bisection.  Returns (prow, pcol): W'[r][c] =
+    W[prow[r]][pcol[c]] keeps its mass in 2**levels diagonal blocks."""
+    absW = np.asarray(absW)
+
+    def bisect(R, C, lv):
+        if lv == 0 or len(R) < 2 or len(C) < 2:
+            return R, C
+        r1, c1 = len(R) // 2, len(C) // 2
+        for _ in range(max_iter):
+            R2 = feedback_half_step(absW, R, C, r1, c1, True)
+            C2 = feedback_half_step(absW, C, R2, c1, r1, False)
+            moved = (R2 != R) or (C2 != C)
+            R, C = R2, C2
+            if not moved:
+                break
+        Ra, Ca = bisect(R[:r1], C[:c1], lv - 1)
+        Rb, Cb = bisect(R[r1:], C[c1:], lv - 1)
+        return Ra + Rb, Ca + Cb
+
+    R, C = bisect([int(v) for v in prow0], [int(v) for v in pcol0], levels)
+    return np.array(R, dtype=np.int32), np.array(C, dtype=np.int32)
+
+
+def feedback_block_ranges(n, levels):
+    """[begin, end) of the 2**levels diagonal blocks along one axis of length n
+    (each range halved floor-first; a range shorter than 2 is not split)."""
+    ranges = [(0, n)]
+    for _ in range(levels):
+        nxt = []
+        for b, e in ranges:
+            if e - b < 2:
+                nxt.append((b, e))
+            else:
+                m = b + (e - b) // 2
+                nxt += [(b, m), (m, e)]
+        ranges = nxt
+    return ranges
+
+
+def feedback_captured_mass(absW, prow, pcol, levels):
+    """Magnitude kept after deleting the off-diagonal sub-blocks at every level."""
+    M, K = absW.shape
+    Wp = np.asarray(absW, dtype=np.float64)[np.ix_(prow, pcol)]
+
+    # a block that cannot be halved on one axis is not halved on the other either
+    def rec(rb, re, cb, ce, lv):
+        if lv == 0 or re - rb < 2 or ce - cb < 2:
+            return float(Wp[rb:re, cb:ce].sum())
+        rm, cm = rb + (re - rb) // 2, cb + (ce - cb) // 2
+        return rec(rb, rm, cb, cm, lv - 1) + rec(rm, re, cm, ce, lv - 1)
+    return rec(0, M, 0, K, levels)

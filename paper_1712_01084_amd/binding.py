@@ -29,7 +29,7 @@ EXPORTS = [
     "pivot_mlp_plan", "pivot_mlp_plan_host_view", "pivot_mlp_plan_destroy",
     "pivot_mlp_workspace_bytes", "pivot_mlp_run",
     "pivot_lstm_workspace_bytes", "pivot_lstm_run",
-    "pivot_dense_run", "pivot_csr_run", "pivot_null_run",
+    "pivot_dense_run", "pivot_csr_run", "pivot_null_run", "pivot_feedback_search",
 ]
 
 
@@ -106,6 +106,7 @@ def lib():
     L.pivot_lstm_run.argtypes = [vp, i32, i32, vp, vp, vp, vp, i32, i32, vp, sz, vp]
     L.pivot_dense_run.argtypes = [vp, i32, i32, i32, vp, i64, vp, vp, i64, i32, i32, vp]
     L.pivot_null_run.argtypes = [vp]
+    L.pivot_feedback_search.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp, C.POINTER(C.c_double)]
     L.pivot_csr_run.argtypes = [vp, vp, vp, i32, i32, i64, vp, vp, vp, i32, vp]
     _lib = L
     return L
@@ -244,3 +245,17 @@ def pivot_null_run(stream=None):
 
 def pivot_csr_run(row_ptr_ptr, col_ptr, val_ptr, wdtype, M, nnz, x_ptr, bias_ptr, y_ptr, act, stream=None):
     _check(lib().pivot_csr_run(row_ptr_ptr, col_ptr, val_ptr, wdtype, M, nnz, x_ptr, bias_ptr, y_ptr, act, stream))
+
+
+def pivot_feedback_search(absW, levels, prow0, pcol0, max_iter=50):
+    """Host numpy in, (prow, pcol, captured_mass) out."""
+    absW = np.ascontiguousarray(absW, dtype=np.float32)
+    M, K = absW.shape
+    prow0 = np.ascontiguousarray(prow0, dtype=np.int32)
+    pcol0 = np.ascontiguousarray(pcol0, dtype=np.int32)
+    prow = np.empty(M, dtype=np.int32)
+    pcol = np.empty(K, dtype=np.int32)
+    mass = C.c_double(0.0)
+    _check(lib().pivot_feedback_search(_np_ptr(absW), M, K, levels, max_iter, _np_ptr(prow0), _np_ptr(pcol0),
+                                       _np_ptr(prow), _np_ptr(pcol), C.byref(mass)))
+    return prow, pcol, mass.value
