@@ -84,8 +84,19 @@ typedef struct pivot_fc_desc {
     int32_t device;       /* HIP device ordinal, or -1 for a host-only plan (no GPU use) */
     int32_t wg_waves;     /* wavefronts per work item: 4, 8 or 16; 0 = the library chooses */
     int32_t row_slices;   /* independent work items per tile height: 1, 2, 4 or 8; 0 = the library chooses */
-    int32_t flags;        /* reserved, must be 0                                         */
+    int32_t flags;        /* PIVOT_PLAN_* bits, 0 = defaults                             */
 } pivot_fc_desc;
+
+/* By default the vector kernel (batch <= 4) first copies the whole of x into
+ * LDS with loads that depend on nothing and gathers from there whenever x is
+ * small enough (rows of 16-byte vectors, at most 8 vectors per thread, 64 KB of
+ * LDS); otherwise each gathered element is a dependent load x[index] from
+ * global memory.  This bit forces the second form (for measurements).       */
+#define PIVOT_PLAN_GATHER_FROM_GLOBAL 1
+/* pivot_lstm_run normally runs the whole sequence in one launch when the plan
+ * allows it (see there); this bit forces one layer launch and one cell launch
+ * per step instead (for measurements and as the reference of the parity test). */
+#define PIVOT_PLAN_LSTM_LAUNCH_PER_STEP 2
 
 typedef struct pivot_fc_plan pivot_fc_plan_t;
 typedef struct pivot_mlp_plan pivot_mlp_plan_t;
@@ -224,8 +235,21 @@ int    pivot_mlp_run(const pivot_mlp_plan_t* plan, const void* x_dev, int64_t ld
  *   c_dev    device, [batch][H] fp32: c_0 on entry, c_steps on return
  *   z_dbg    device, optional [batch][4H] fp32: gate pre-activations of the
  *            last step in natural order (NULL to skip)
+ *
+ * Two forms.  Plans with fp16 16x32 BRC tiles, batch <= 16, batch*K_pad <= 131072
+ * and at most 16 kept tiles per wavefront of a full-device grid run the whole
+ * sequence in ONE launch: the kept tiles stay in registers for all steps, the
+ * steps are separated by grid-wide barriers (a counter in the workspace), and
+ * per step only h, x_t and the gate sums move.  Its workgroups wait for each
+ * other, so nothing else should occupy the device while it runs; a wait that
+ * does not end within about a second gives up, every workgroup leaves, h/c
+ * are left unwritten and the status word reads 1.  Every other plan (or
+ * PIVOT_PLAN_LSTM_LAUNCH_PER_STEP) runs one layer launch and one cell launch
+ * per step.  pivot_lstm_status synchronises the stream and returns the status
+ * word of the last pivot_lstm_run on this workspace (0 = completed).
  */
 size_t pivot_lstm_workspace_bytes(const pivot_fc_plan_t* plan, int H, int I, int steps, int batch);
+int    pivot_lstm_status(const pivot_fc_plan_t* plan, int steps, int batch, const void* ws_dev, void* stream, int* status);
 int    pivot_lstm_run(const pivot_fc_plan_t* plan, int H, int I, const void* xs_dev,
                       float* h_dev, float* c_dev, float* z_dbg, int steps, int batch,
                       void* ws_dev, size_t ws_bytes, void* stream);

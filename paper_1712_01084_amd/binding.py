@@ -14,6 +14,8 @@ LIB_PATH = os.path.join(_HERE, "libpivotfc.so")
 
 PIVOT_F32, PIVOT_F16 = 0, 1
 PIVOT_BRC, PIVOT_BCR, PIVOT_CBR = 0, 1, 2
+PIVOT_PLAN_GATHER_FROM_GLOBAL = 1
+PIVOT_PLAN_LSTM_LAUNCH_PER_STEP = 2
 PIVOT_ACT_NONE, PIVOT_ACT_RELU = 0, 1
 PIVOT_W_NATURAL, PIVOT_W_PIVOTED = 0, 1
 PIVOT_MLP_KEEP_FINAL_BLOCK_ORDER = 1
@@ -28,7 +30,7 @@ EXPORTS = [
     "pivot_fc_workspace_bytes", "pivot_workspace_init", "pivot_fc_run",
     "pivot_mlp_plan", "pivot_mlp_plan_host_view", "pivot_mlp_plan_destroy",
     "pivot_mlp_workspace_bytes", "pivot_mlp_run",
-    "pivot_lstm_workspace_bytes", "pivot_lstm_run",
+    "pivot_lstm_workspace_bytes", "pivot_lstm_run", "pivot_lstm_status",
     "pivot_dense_run", "pivot_csr_run", "pivot_null_run", "pivot_feedback_search",
 ]
 
@@ -104,6 +106,7 @@ def lib():
     L.pivot_lstm_workspace_bytes.argtypes = [vp, i32, i32, i32, i32]
     L.pivot_lstm_workspace_bytes.restype = sz
     L.pivot_lstm_run.argtypes = [vp, i32, i32, vp, vp, vp, vp, i32, i32, vp, sz, vp]
+    L.pivot_lstm_status.argtypes = [vp, i32, i32, vp, vp, C.POINTER(C.c_int)]
     L.pivot_dense_run.argtypes = [vp, i32, i32, i32, vp, i64, vp, vp, i64, i32, i32, vp]
     L.pivot_null_run.argtypes = [vp]
     L.pivot_feedback_search.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp, C.POINTER(C.c_double)]
@@ -233,6 +236,13 @@ def pivot_lstm_workspace_bytes(plan, H, I, steps, batch):
 
 def pivot_lstm_run(plan, H, I, xs_ptr, h_ptr, c_ptr, z_dbg_ptr, steps, batch, ws_ptr, ws_bytes, stream=None):
     _check(lib().pivot_lstm_run(plan, H, I, xs_ptr, h_ptr, c_ptr, z_dbg_ptr, steps, batch, ws_ptr, ws_bytes, stream))
+
+
+def pivot_lstm_status(plan, steps, batch, ws_ptr, stream=None):
+    """Synchronises the stream; 0 = the last pivot_lstm_run on this workspace completed."""
+    st = C.c_int(-1)
+    _check(lib().pivot_lstm_status(plan, steps, batch, ws_ptr, stream, C.byref(st)))
+    return st.value
 
 
 def pivot_dense_run(W_ptr, wdtype, M, K, x_ptr, ldx, bias_ptr, y_ptr, ldy, batch, act, stream=None):

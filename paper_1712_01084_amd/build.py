@@ -16,7 +16,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJDIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libpivotfc.so")
 
-SOURCES = ["pivot_gemv_f32.hip", "pivot_gemv_f16.hip", "pivot_mfma_f16.hip", "pivot_colmajor.hip", "pivot_misc.hip", "pivot_launch.hip",
+SOURCES = ["pivot_gemv_f32.hip", "pivot_gemv_f16.hip", "pivot_mfma_f16.hip", "pivot_colmajor.hip", "pivot_misc.hip", "pivot_lstm_persist.hip", "pivot_launch.hip",
            "pivot_plan.cpp", "pivot_search.cpp", "pivot_api.cpp"]
 
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"), "-I", CSRC,
@@ -53,9 +53,9 @@ def build(verbose=False, out=None, objdir=None, device_flags=None):
     with ThreadPoolExecutor(max_workers=8) as ex:
         results = list(ex.map(lambda s: _compile(s, objdir, device_flags), SOURCES))
     if verbose:
-        for _, out in results:
-            if out.strip():
-                print(out)
+        for _, log in results:
+            if log.strip():
+                print(log)
     objs = [o for o, _ in results]
     out = out or LIB
     cmd = [_hipcc(), "-shared", "-fPIC", "--offload-arch=gfx950", "-o", out] + objs + ["-Wl,-rpath,/opt/rocm/lib"]

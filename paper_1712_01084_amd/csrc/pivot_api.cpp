@@ -62,6 +62,7 @@ int upload(pivot_fc_plan_t* p) {
         {h.xidx.data(),      h.xidx.size() * 4,             (void**)&d.xidx},
         {xblk.data(),        xblk.size() * 4,               (void**)&d.xidx_blk},
         {rowid.data(),       rowid.size() * 4,              (void**)&d.rowid_pad},
+        {h.row_ptr.data(),   h.row_ptr.size() * 4,          (void**)&d.row_ptr},
     };
     size_t total = 0;
     // every array is followed by zeroed padding: 16 KB after the tile values (clamped
@@ -193,6 +194,7 @@ int prepare(const pivot_fc_plan_t* plan, int batch, void* ws, size_t ws_bytes, F
     if (reinterpret_cast<uintptr_t>(ws) % 16 != 0) { set_error("workspace must be 16-byte aligned"); return PIVOT_E_WORKSPACE; }
     const DevPlan& d = plan->dev;
     L.vals = d.vals; L.col_idx = d.col_idx; L.chunks = d.chunks; L.part_base = d.part_base; L.bias_p = d.bias_p;
+    L.K = h.d.K; L.x_resident = (h.d.flags & PIVOT_PLAN_GATHER_FROM_GLOBAL) ? 0 : 1;
     L.M_pad = h.M_pad; L.K_pad = h.K_pad; L.bh = h.d.bh; L.bw = h.d.bw; L.wdtype = h.d.wdtype; L.layout = h.d.layout; L.T = h.T; L.act = h.d.act;
     L.nchunks = h.nchunks; L.nbr = h.nbr; L.chunk_tiles = h.chunk_tiles; L.wg_waves = h.wg_waves;
     L.row_slices = h.row_slices;
@@ -405,13 +407,16 @@ int pivot_mlp_run(const pivot_mlp_plan_t* plan, const void* x_dev, int64_t ldx, 
 
 namespace {
 
-struct LstmLayout { size_t scratch, z_off, xg_off, xg_step, total; };
+// [launch-per-step scratch][gate pre-activations][control words + partials of the one-launch form][inputs of all steps]
+struct LstmLayout { size_t scratch, z_off, ctl_off, part_off, xg_off, xg_step, total; };
 
 LstmLayout lstm_layout(const pivot_fc_plan_t* p, int steps, int batch) {
     LstmLayout m{};
     m.scratch = align_up(fc_workspace_bytes(p->host, batch), 256);
     m.z_off = m.scratch;
-    m.xg_off = m.z_off + align_up((size_t)batch * p->host.d.M * 4, 256);
+    m.ctl_off = m.z_off + align_up((size_t)batch * p->host.d.M * 4, 256);
+    m.part_off = m.ctl_off + kLstmCtlBytes;
+    m.xg_off = m.part_off + lstm_persist_partial_bytes(p->host, batch);
     m.xg_step = align_up((size_t)batch * p->host.K_pad * elem_size(p->host.d.wdtype), 256);
     m.total = m.xg_off + m.xg_step * (size_t)(steps > 0 ? steps : 1);
     return m;
@@ -442,6 +447,22 @@ int pivot_lstm_run(const pivot_fc_plan_t* plan, int H, int I, const void* xs_dev
     float* z = reinterpret_cast<float*>(ws + m.z_off);
     char* xg = ws + m.xg_off;
     int rc;
+    if (!(h.d.flags & PIVOT_PLAN_LSTM_LAUNCH_PER_STEP) && lstm_persist_supported(h, H, batch, plan->device, nullptr, nullptr)) {
+        // one launch for the whole sequence
+        if ((rc = launch_fill_zero(ws + m.ctl_off, m.xg_off - m.ctl_off, stream)) != PIVOT_OK) return rc;   // control words + partials
+        LstmPersistLaunch P{};
+        P.hp = &h;
+        P.vals = plan->dev.vals; P.col_idx = plan->dev.col_idx; P.row_ptr = plan->dev.row_ptr;
+        P.invprow = plan->dev.invprow; P.invpcol = plan->dev.invpcol; P.pcol_pad = plan->dev.pcol_pad; P.bias_p = plan->dev.bias_p;
+        P.xs = xs_dev; P.xg = xg; P.xg_step_elems = m.xg_step / elem_size(h.d.wdtype);
+        P.partials = ws + m.part_off;
+        P.ctl = reinterpret_cast<uint32_t*>(ws + m.ctl_off);
+        P.h = h_dev; P.c = c_dev; P.z_dbg = z_dbg;
+        P.H = H; P.I = I; P.batch = batch; P.steps = steps; P.device = plan->device; P.stream = stream;
+        return launch_lstm_persist(P);
+    }
+    // one layer launch and one cell launch per step
+    if ((rc = launch_fill_zero(ws + m.ctl_off, kLstmCtlBytes, stream)) != PIVOT_OK) return rc;
     // block-order inputs of all steps: padding zero, x_t placed once, h_0 placed into step 0
     if ((rc = launch_fill_zero(xg, m.xg_step * (size_t)steps, stream)) != PIVOT_OK) return rc;
     if (m.xg_step != (size_t)batch * h.K_pad * elem_size(h.d.wdtype)) {
@@ -471,6 +492,18 @@ int pivot_lstm_run(const pivot_fc_plan_t* plan, int H, int I, const void* xs_dev
         C.H = H; C.M_pad = h.M_pad; C.K_pad = h.K_pad; C.batch = batch; C.wdtype = h.d.wdtype; C.stream = stream;
         if ((rc = launch_lstm_cell(C)) != PIVOT_OK) return rc;
     }
+    return PIVOT_OK;
+}
+
+int pivot_lstm_status(const pivot_fc_plan_t* plan, int steps, int batch, const void* ws_dev, void* stream, int* status) {
+    if (!plan || !ws_dev || !status) { set_error("plan, ws_dev and status are required"); return PIVOT_E_NULL; }
+    if (plan->device < 0) { set_error("host-only plan"); return PIVOT_E_NO_DEVICE; }
+    LstmLayout m = lstm_layout(plan, steps, batch);
+    uint32_t word = 0;
+    DeviceGuard g(plan->device);
+    API_HIP(hipStreamSynchronize(reinterpret_cast<hipStream_t>(stream)), (void)0);
+    API_HIP(hipMemcpy(&word, reinterpret_cast<const char*>(ws_dev) + m.ctl_off + 1024, 4, hipMemcpyDeviceToHost), (void)0);
+    *status = (int)word;
     return PIVOT_OK;
 }
 

@@ -81,7 +81,7 @@ __global__ void __launch_bounds__(NW * 64) fc_colmajor_kernel(PIVOT_LEAD_PARAMS,
     #pragma unroll
     for (int u = 0; u < U; ++u) fill(u, wave + u * NW);
 
-    xst.gather(a, p_idx, p_x, xs, tile_begin, ncols, b0, tid);
+    xst.template gather<false>(a, p_idx, reinterpret_cast<const WT*>(p_x), xs, tile_begin, ncols, b0, tid);
     lds_barrier();
 
     float acc[VEC];

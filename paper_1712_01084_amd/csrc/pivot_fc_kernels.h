@@ -53,6 +53,8 @@ struct FcArgs {
     int uniform_ct;             // > 0: every chunk has exactly this many tiles and chunk i starts at tile i*uniform_ct,
     int uniform_parts;          //      uniform_parts chunks per block row: the descriptor is computed, not loaded
     int T;                      // kept tiles in the whole plan (the CBR layout strides by it)
+    int xn_vecs;                // x-resident vector kernel: 16-byte vectors per row of x (row length / VEC)
+    int xn_stride;              //   elements between the LDS copies of consecutive batch rows (the row length)
 };
 
 // The seven pointers every wavefront needs first are separate leading kernel
@@ -64,8 +66,8 @@ struct FcArgs {
 #define PIVOT_LEAD_ARGS(a, idx) (a).chunks, (a).part_base, (idx), (a).vals, (a).bias_p, (a).scatter, (a).x
 
 // Per-dtype / per-path launchers, each in its own translation unit.
-int launch_gemv_f32(const FcArgs& a, int bhs, int bw, int nb, int nw, dim3 grid, size_t smem, hipStream_t st);
-int launch_gemv_f16(const FcArgs& a, int bhs, int bw, int nb, int nw, dim3 grid, size_t smem, hipStream_t st);
+int launch_gemv_f32(const FcArgs& a, int bhs, int bw, int nb, int nw, int xres, dim3 grid, size_t smem, hipStream_t st);
+int launch_gemv_f16(const FcArgs& a, int bhs, int bw, int nb, int nw, int xres, dim3 grid, size_t smem, hipStream_t st);
 int launch_mfma_f16(const FcArgs& a, int kind, int bhs, int bw, int nw, dim3 grid, size_t smem, hipStream_t st);
 int launch_colmajor(const FcArgs& a, int layout, int wdtype, int bh, int bw, int nw, dim3 grid, size_t smem, hipStream_t st);
 
@@ -145,11 +147,15 @@ struct XStage {
             src[k] = xi[e < emax ? e : emax];
         }
     }
-    __device__ __forceinline__ void gather(const FcArgs& a, const int32_t* xidx, const void* x, WT* xs,
+    // SRC_LDS = false: `x` is the global x (one dependent global load per element).
+    // SRC_LDS = true:  `x` is the whole of x already copied into LDS (row b at
+    // b * a.xn_stride), so the gather costs no second trip to memory.
+    template <bool SRC_LDS>
+    __device__ __forceinline__ void gather(const FcArgs& a, const int32_t* xidx, const WT* x, WT* xs,
                                            int tile_begin, int ne, int b0, int tid) {
         const int b = tid % NB;
         const bool row_ok = (b0 + b) < a.batch;
-        const WT* xrow = reinterpret_cast<const WT*>(x) + (long long)(row_ok ? b0 + b : 0) * a.ldx;
+        const WT* xrow = SRC_LDS ? x + b * a.xn_stride : x + (long long)(row_ok ? b0 + b : 0) * a.ldx;
         WT* xsrow = xs + b * a.xs_stride;
         const int dump = a.xs_stride - 1;
         WT v[XP];
@@ -178,6 +184,46 @@ struct XStage {
                 const int e = e0 + k * STEP;
                 xsrow[e < ne ? e : dump] = (s2[k] >= 0 && row_ok) ? v2[k] : WT(0);
             }
+        }
+    }
+};
+
+// The whole of x copied into LDS with coalesced 16-byte loads that depend on
+// nothing (x-resident variant): issued first, together with the gather
+// indices, so that both arrive after ONE trip to memory and the gather itself
+// runs LDS to LDS.  Without it the gather is a chain of two dependent trips
+// (index, then x[index]) whose second leg queues behind the weight stream.
+// A thread holds up to XN vectors; the launcher only picks this variant when
+// NB rows of x fit (NB * xn_vecs <= XN * NT) and rows are 16-byte aligned.
+// Slots past the end load vector 0 again and are written to a dump vector.
+template <typename WT, int NB, int NT>
+struct XRes {
+    using V = typename Elem<WT>::vec;
+    static constexpr int VEC = Elem<WT>::VEC;
+    static constexpr int XN = 8;
+    V v[XN];
+    __device__ __forceinline__ void load(const FcArgs& a, const void* x, int b0, int tid) {
+        const int total = NB * a.xn_vecs;
+        #pragma unroll
+        for (int j = 0; j < XN; ++j) {
+            const int id = tid + j * NT;
+            const int b = (NB == 1) ? 0 : id / a.xn_vecs;
+            const int i = (NB == 1) ? id : id - b * a.xn_vecs;
+            const bool ok = id < total && (b0 + b) < a.batch;
+            const WT* row = reinterpret_cast<const WT*>(x) + (long long)(ok ? b0 + b : 0) * a.ldx;
+            v[j] = load16<V>(row + (size_t)(ok ? i : 0) * VEC);
+        }
+    }
+    __device__ __forceinline__ void store(const FcArgs& a, WT* xn, int b0, int tid) {
+        const int total = NB * a.xn_vecs;
+        const int dump = NB * a.xn_stride;              // one spare vector after the last row
+        #pragma unroll
+        for (int j = 0; j < XN; ++j) {
+            const int id = tid + j * NT;
+            const int b = (NB == 1) ? 0 : id / a.xn_vecs;
+            const int i = (NB == 1) ? id : id - b * a.xn_vecs;
+            const bool ok = id < total && (b0 + b) < a.batch;
+            *reinterpret_cast<V*>(xn + (ok ? b * a.xn_stride + i * VEC : dump)) = v[j];
         }
     }
 };
@@ -264,7 +310,7 @@ __device__ __forceinline__ void finish_rows(const FcArgs& a, const float* red, i
 // stream, i.e. VEC columns of one tile row; LPR lanes cover a row, a wave
 // covers RPW rows per load.
 // ---------------------------------------------------------------------------
-template <typename WT, int BH, int BW, int NB, int NW>
+template <typename WT, int BH, int BW, int NB, int NW, bool XR>
 __global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(PIVOT_LEAD_PARAMS, FcArgs a) {
     using V = typename Elem<WT>::vec;
     constexpr int VEC = Elem<WT>::VEC;
@@ -279,7 +325,9 @@ __global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(PIVOT_LEAD_PARAMS, FcA
 
     extern __shared__ __align__(16) char smem[];
     __shared__ int s_flag;
-    WT* xs = reinterpret_cast<WT*>(smem);
+    // LDS: [x-resident copy of x: NB rows + a dump vector][staged x-segments]; the sums reuse it afterwards
+    WT* xn = reinterpret_cast<WT*>(smem);
+    WT* xs = XR ? xn + NB * a.xn_stride + VEC : xn;
     float* red = reinterpret_cast<float*>(smem);        // reused after the stream phase
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -291,7 +339,9 @@ __global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(PIVOT_LEAD_PARAMS, FcA
     const int ngroups = (ntiles + TPL - 1) / TPL;
     const int row0 = br * a.bh_full + slice * BH;
 
-    // order of issue = order of arrival: gather indices, epilogue operands, then the weights
+    // order of issue = order of arrival: (x,) gather indices, epilogue operands, then the weights
+    XRes<WT, NB, NT> xres;
+    if constexpr (XR) xres.load(a, p_x, b0, tid);
     XStage<WT, BW, NB, NT> xst;
     xst.load_idx(p_idx, tile_begin, ntiles * BW, tid);
     RowPre<BH, N, NT> rp;
@@ -320,7 +370,13 @@ __global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(PIVOT_LEAD_PARAMS, FcA
     };
 
     issue(wave);
-    xst.gather(a, p_idx, p_x, xs, tile_begin, ntiles * BW, b0, tid);
+    if constexpr (XR) {
+        xres.store(a, xn, b0, tid);
+        lds_barrier();
+        xst.template gather<true>(a, p_idx, xn, xs, tile_begin, ntiles * BW, b0, tid);
+    } else {
+        xst.template gather<false>(a, p_idx, reinterpret_cast<const WT*>(p_x), xs, tile_begin, ntiles * BW, b0, tid);
+    }
     lds_barrier();
 
     float acc[NL][NB];

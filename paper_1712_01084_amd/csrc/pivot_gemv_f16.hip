@@ -3,26 +3,26 @@
 
 namespace pivot {
 
-template <int BH, int BW, int NB>
+template <int BH, int BW, int NB, bool XR>
 static int launch_t(const FcArgs& a, int nw, dim3 grid, size_t smem, hipStream_t st) {
-    if (nw == 16)     hipLaunchKernelGGL((fc_gemv_kernel<_Float16, BH, BW, NB, 16>), grid, dim3(16 * 64), smem, st, PIVOT_LEAD_ARGS(a, a.xidx), a);
-    else if (nw == 8) hipLaunchKernelGGL((fc_gemv_kernel<_Float16, BH, BW, NB, 8>), grid, dim3(8 * 64), smem, st, PIVOT_LEAD_ARGS(a, a.xidx), a);
-    else              hipLaunchKernelGGL((fc_gemv_kernel<_Float16, BH, BW, NB, 4>), grid, dim3(4 * 64), smem, st, PIVOT_LEAD_ARGS(a, a.xidx), a);
+    if (nw == 16)     hipLaunchKernelGGL((fc_gemv_kernel<_Float16, BH, BW, NB, 16, XR>), grid, dim3(16 * 64), smem, st, PIVOT_LEAD_ARGS(a, a.xidx), a);
+    else if (nw == 8) hipLaunchKernelGGL((fc_gemv_kernel<_Float16, BH, BW, NB, 8, XR>), grid, dim3(8 * 64), smem, st, PIVOT_LEAD_ARGS(a, a.xidx), a);
+    else              hipLaunchKernelGGL((fc_gemv_kernel<_Float16, BH, BW, NB, 4, XR>), grid, dim3(4 * 64), smem, st, PIVOT_LEAD_ARGS(a, a.xidx), a);
     HIP_TRY(hipGetLastError());
     return PIVOT_OK;
 }
 
 template <int BH, int BW>
-static int launch_nb(const FcArgs& a, int nb, int nw, dim3 grid, size_t smem, hipStream_t st) {
+static int launch_nb(const FcArgs& a, int nb, int nw, int xres, dim3 grid, size_t smem, hipStream_t st) {
     switch (nb) {
-        case 1: return launch_t<BH, BW, 1>(a, nw, grid, smem, st);
-        case 2: return launch_t<BH, BW, 2>(a, nw, grid, smem, st);
-        default: return launch_t<BH, BW, 4>(a, nw, grid, smem, st);
+        case 1: return xres ? launch_t<BH, BW, 1, true>(a, nw, grid, smem, st) : launch_t<BH, BW, 1, false>(a, nw, grid, smem, st);
+        case 2: return xres ? launch_t<BH, BW, 2, true>(a, nw, grid, smem, st) : launch_t<BH, BW, 2, false>(a, nw, grid, smem, st);
+        default: return xres ? launch_t<BH, BW, 4, true>(a, nw, grid, smem, st) : launch_t<BH, BW, 4, false>(a, nw, grid, smem, st);
     }
 }
 
-int launch_gemv_f16(const FcArgs& a, int bhs, int bw, int nb, int nw, dim3 grid, size_t smem, hipStream_t st) {
-#define X(BH_, BW_) if (bhs == BH_ && bw == BW_) return launch_nb<BH_, BW_>(a, nb, nw, grid, smem, st);
+int launch_gemv_f16(const FcArgs& a, int bhs, int bw, int nb, int nw, int xres, dim3 grid, size_t smem, hipStream_t st) {
+#define X(BH_, BW_) if (bhs == BH_ && bw == BW_) return launch_nb<BH_, BW_>(a, nb, nw, xres, grid, smem, st);
     PIVOT_SHAPES(X)
 #undef X
     set_error("no vector kernel for %dx%d row slices", bhs, bw);

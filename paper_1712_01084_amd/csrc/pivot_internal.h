@@ -50,6 +50,7 @@ struct DevPlan {
     int32_t* xidx = nullptr;      // gather index for natural-order x
     int32_t* xidx_blk = nullptr;  // same for x already in block order: col_idx[t]*bw+c
     int32_t* rowid_pad = nullptr; // [M_pad] r for r < M, -1 in padding: stores that stay in block order
+    int32_t* row_ptr = nullptr;   // [nbr+1] (persistent recurrent kernel: work split and piece lookup)
 };
 
 // Builds every host array.  Returns PIVOT_OK or an error code (error text set).
@@ -81,6 +82,8 @@ struct FcLaunch {
     int M_pad, K_pad, bh, bw, wdtype, layout, T, act, nchunks, nbr, chunk_tiles, wg_waves, row_slices;
     int uniform_ct, uniform_parts;  // > 0: regular schedule, the kernels compute the chunk descriptor
     int x_block_order;          // 1: x is [batch][K_pad] in block order (what the matrix-core kernel needs)
+    int K;                      // row length of a natural-order x
+    int x_resident;             // 0: never copy the whole of x into LDS; otherwise the launcher decides
     // data
     const void* x; int64_t ldx;
     void*       y; int64_t ldy;
@@ -127,6 +130,24 @@ int launch_lstm_place_inputs(const void* xs, void* xg_all, const int32_t* invpco
 // Places h (fp32, natural) into one block-order input buffer.
 int launch_lstm_place_state(const float* h, void* xg, const int32_t* invpcol, int H, int K_pad,
                             int batch, int wdtype, void* stream);
+
+// The whole recurrent loop in one launch (weights resident in registers, grid barriers between the phases).
+struct LstmPersistLaunch {
+    const HostPlan* hp;
+    const void* vals; const int32_t* col_idx; const int32_t* row_ptr; const int32_t* invprow; const int32_t* invpcol;
+    const int32_t* pcol_pad; const float* bias_p;
+    const void* xs;                    // [steps][batch][I]
+    void* xg; size_t xg_step_elems;    // block-order inputs of all steps (written here)
+    void* partials;                    // lstm_persist_partial_bytes, zeroed
+    uint32_t* ctl;                     // kLstmCtlBytes, zeroed: progress word per workgroup, status word at [256]
+    float* h; float* c; float* z_dbg;
+    int H, I, batch, steps, device;
+    void* stream;
+};
+bool   lstm_persist_supported(const HostPlan& hp, int H, int batch, int device, int* grid_out, int* L_out);
+size_t lstm_persist_partial_bytes(const HostPlan& hp, int batch);
+constexpr size_t kLstmCtlBytes = 2048;
+int    launch_lstm_persist(const LstmPersistLaunch& P);
 
 }  // namespace pivot
 

@@ -101,11 +101,25 @@ int launch_fc(const FcLaunch& L) {
     a.xs_stride = L.chunk_tiles * L.bw + 16 / es;
     size_t xs_bytes = (size_t)nbt * a.xs_stride * es;
     size_t red_bytes = (size_t)nw * bhs * nbt * 4;
-    size_t smem = align_up(xs_bytes > red_bytes ? xs_bytes : red_bytes, 16);
+    // x-resident variant: every work item first copies the whole of x (nbt rows) into LDS with independent
+    // coalesced loads and gathers from there.  Taken when the rows are 16-byte vectors, a thread has to hold at
+    // most 8 of them, and everything fits in 64 KB of LDS.
+    const int vec = 16 / es;
+    const int xlen = L.x_block_order ? L.K_pad : L.K;
+    int xres = 0;
+    size_t xn_bytes = 0;
+    if (L.layout == PIVOT_BRC && L.x_resident != 0 && xlen % vec == 0 && L.ldx % vec == 0 &&
+        (reinterpret_cast<uintptr_t>(L.x) & 15) == 0 && (size_t)nbt * (xlen / vec) <= (size_t)8 * nw * 64) {
+        xn_bytes = (size_t)nbt * xlen * es + 16;
+        if (xn_bytes + xs_bytes <= 64 * 1024 && red_bytes <= 64 * 1024) xres = 1;
+    }
+    a.xn_vecs = xlen / vec; a.xn_stride = xlen;
+    size_t smem = xres ? xn_bytes + xs_bytes : xs_bytes;
+    smem = align_up(smem > red_bytes ? smem : red_bytes, 16);
     if (smem > 64 * 1024) { set_error("chunk does not fit in LDS (%zu bytes)", smem); return PIVOT_E_UNSUPPORTED; }
     if (L.layout != PIVOT_BRC) return launch_colmajor(a, L.layout, L.wdtype, L.bh, L.bw, nw, grid, smem, st);
-    if (L.wdtype == PIVOT_F32) return launch_gemv_f32(a, bhs, L.bw, nbt, nw, grid, smem, st);
-    return launch_gemv_f16(a, bhs, L.bw, nbt, nw, grid, smem, st);
+    if (L.wdtype == PIVOT_F32) return launch_gemv_f32(a, bhs, L.bw, nbt, nw, xres, grid, smem, st);
+    return launch_gemv_f16(a, bhs, L.bw, nbt, nw, xres, grid, smem, st);
 }
 
 }  // namespace pivot

@@ -18,12 +18,12 @@ def tdtype(p):
     return torch.float32 if p.wdtype == WL.F32 else torch.float16
 
 
-def dev_plan(p, chunk_tiles=0, natural=False, wg_waves=0, row_slices=0, layout=B.PIVOT_BRC):
+def dev_plan(p, chunk_tiles=0, natural=False, wg_waves=0, row_slices=0, layout=B.PIVOT_BRC, flags=0):
     W = O.unpivot_weights(p.Wp, p.prow, p.pcol) if natural else p.Wp
     return B.pivot_fc_plan(p.M, p.K, p.bh, p.bw, wd(p), W,
                            B.PIVOT_W_NATURAL if natural else B.PIVOT_W_PIVOTED,
                            p.tile_mask, p.prow, p.pcol, p.bias, act=p.act, layout=layout,
-                           chunk_tiles=chunk_tiles, device=0, wg_waves=wg_waves, row_slices=row_slices)
+                           chunk_tiles=chunk_tiles, device=0, wg_waves=wg_waves, row_slices=row_slices, flags=flags)
 
 
 def workspace(nbytes):

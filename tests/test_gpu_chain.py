@@ -95,18 +95,22 @@ def _lstm_gpu(lp, plan, xs, h, c, want_z=True):
     cd = torch.from_numpy(np.ascontiguousarray(c, dtype=np.float32)).cuda()
     zd = torch.full((batch, 4 * H), float("nan"), dtype=torch.float32, device="cuda")
     ws = G.workspace(B.pivot_lstm_workspace_bytes(plan, H, I, steps, batch))
+    st = torch.cuda.current_stream().cuda_stream
     B.pivot_lstm_run(plan, H, I, xsd.data_ptr(), hd.data_ptr(), cd.data_ptr(), zd.data_ptr() if want_z else None,
-                     steps, batch, ws.data_ptr(), ws.numel(), torch.cuda.current_stream().cuda_stream)
+                     steps, batch, ws.data_ptr(), ws.numel(), st)
+    assert B.pivot_lstm_status(plan, steps, batch, ws.data_ptr(), st) == 0      # also synchronises
     torch.cuda.synchronize()
     return hd.cpu().numpy().astype(np.float64), cd.cpu().numpy().astype(np.float64), zd.cpu().numpy().astype(np.float64)
 
 
-def _check_lstm_steps(lp, record, tol):
+def _check_lstm_steps(lp, record, tol, per_step=False):
+    # per_step=False: the library's choice (one launch for the whole sequence where the plan allows it);
+    # per_step=True: one layer launch and one cell launch per step
     p = lp.fc
     Wd = O.dense_masked_natural(p.Wp, p.tile_mask, p.prow, p.pcol, p.bh, p.bw)
     sd = np.float16 if p.wdtype == WL.F16 else np.float32
     h_end, c_end, rec = O.oracle_lstm(Wd, p.bias, lp.xs, lp.h0, lp.c0, lp.H, state_dtype=sd, record=record)
-    plan = G.dev_plan(p)
+    plan = G.dev_plan(p, flags=B.PIVOT_PLAN_LSTM_LAUNCH_PER_STEP if per_step else 0)
     try:
         H = lp.H
         for t in record:
@@ -123,6 +127,8 @@ def _check_lstm_steps(lp, record, tol):
             assert np.all(np.abs(h - h_ref) <= tol * Do / 4 + bc + 1e-5), ("h", t)
         # free-running trajectory: reported, not gated beyond sanity ("parity unpinned")
         h, c, _ = _lstm_gpu(lp, plan, lp.xs, lp.h0, lp.c0, want_z=False)
+        h2, c2, _ = _lstm_gpu(lp, plan, lp.xs, lp.h0, lp.c0, want_z=False)
+        assert np.array_equal(h, h2) and np.array_equal(c, c2)          # fixed summation order: bit-identical reruns
         dh, dc = float(np.abs(h - h_end).max()), float(np.abs(c - c_end).max())
         print("lstm free run %d steps: max|dh| = %.3g, max|dc| = %.3g" % (lp.xs.shape[0], dh, dc))
         assert np.isfinite(h).all() and np.isfinite(c).all()
@@ -131,15 +137,41 @@ def _check_lstm_steps(lp, record, tol):
         B.pivot_fc_plan_destroy(plan)
 
 
+@pytest.mark.parametrize("per_step", [False, True])
 @pytest.mark.parametrize("batch", [1, 2, 8])
-def test_lstm_small(batch):
+def test_lstm_small(batch, per_step):
     lp = WL.config5(seed=3, batch=batch, H=64, I=32, steps=6, frac=0.5)
     lp.h0 = np.random.default_rng(1).standard_normal(lp.h0.shape).astype(np.float32) * 0.5
     lp.c0 = np.random.default_rng(2).standard_normal(lp.c0.shape).astype(np.float32)
-    dh, dc = _check_lstm_steps(lp, record=(0, 1, 5), tol=2e-3)
+    dh, dc = _check_lstm_steps(lp, record=(0, 1, 5), tol=2e-3, per_step=per_step)
     assert dh < 0.05 and dc < 0.05
 
 
-def test_lstm_config5_full():
+@pytest.mark.parametrize("H,I,batch,frac", [(96, 40, 3, 0.3), (256, 128, 16, 0.2), (80, 8, 5, 1.0)])
+def test_lstm_one_launch_ragged_shapes(H, I, batch, frac):
+    # K = H+I not a multiple of the tile width (padding columns), empty and split block rows, every tile kept
+    lp = WL.config5(seed=5, batch=batch, H=H, I=I, steps=9, frac=frac)
+    lp.h0 = np.random.default_rng(3).standard_normal(lp.h0.shape).astype(np.float32) * 0.5
+    lp.c0 = np.random.default_rng(4).standard_normal(lp.c0.shape).astype(np.float32)
+    dh, dc = _check_lstm_steps(lp, record=(0, 3, 8), tol=2e-3)
+    assert dh < 0.05 and dc < 0.05
+
+
+def test_lstm_one_launch_agrees_with_launch_per_step():
+    lp = WL.config5(seed=7, batch=8, H=256, I=128, steps=20, frac=0.25)
+    outs = []
+    for flags in (0, B.PIVOT_PLAN_LSTM_LAUNCH_PER_STEP):
+        plan = G.dev_plan(lp.fc, flags=flags)
+        try:
+            outs.append(_lstm_gpu(lp, plan, lp.xs, lp.h0, lp.c0, want_z=True))
+        finally:
+            B.pivot_fc_plan_destroy(plan)
+    (h1, c1, z1), (h2, c2, z2) = outs
+    # same inputs, same rounding points, different (fixed) summation orders
+    assert np.abs(h1 - h2).max() < 2e-3 and np.abs(c1 - c2).max() < 4e-3 and np.abs(z1 - z2).max() < 2e-2
+
+
+@pytest.mark.parametrize("per_step", [False, True])
+def test_lstm_config5_full(per_step):
     lp = WL.config5(seed=0)
-    _check_lstm_steps(lp, record=(0, 1, 17, 255), tol=2e-3)
+    _check_lstm_steps(lp, record=(0, 1, 17, 255), tol=2e-3, per_step=per_step)
