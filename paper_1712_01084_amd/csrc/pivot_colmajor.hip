@@ -34,7 +34,7 @@ __global__ void __launch_bounds__(NW * 64) fc_colmajor_kernel(PIVOT_LEAD_PARAMS,
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int b0 = blockIdx.y;
-    const Chunk ck = load_chunk(a, p_chunks, p_part_base);
+    const Chunk ck = load_chunk(a.uniform_ct, a.uniform_parts, p_chunks, p_part_base);
     const int br = ck.br, tile_begin = ck.tile_begin, ntiles = ck.ntiles, slot = ck.slot;
     const int first = ck.first, nparts = ck.nparts;
     const int row0 = br * BH;
@@ -81,7 +81,7 @@ __global__ void __launch_bounds__(NW * 64) fc_colmajor_kernel(PIVOT_LEAD_PARAMS,
     #pragma unroll
     for (int u = 0; u < U; ++u) fill(u, wave + u * NW);
 
-    xst.template gather<false>(a, p_idx, reinterpret_cast<const WT*>(p_x), xs, tile_begin, ncols, b0, tid);
+    xst.template gather<false>(a.batch, a.ldx, 0, a.xs_stride, p_idx, reinterpret_cast<const WT*>(p_x), xs, tile_begin, ncols, b0, tid);
     lds_barrier();
 
     float acc[VEC];

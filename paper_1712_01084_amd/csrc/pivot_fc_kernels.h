@@ -65,6 +65,18 @@ struct FcArgs {
     const int32_t* __restrict__ p_scatter, const void* __restrict__ p_x
 #define PIVOT_LEAD_ARGS(a, idx) (a).chunks, (a).part_base, (idx), (a).vals, (a).bias_p, (a).scatter, (a).x
 
+// The vector kernel goes further: everything it needs before its loads can be
+// issued (four pointers and six scalars = the 14 dwords that are preloaded
+// into SGPRs) comes first, so that no load waits for a fetch of the argument
+// block; bias, scatter index and the rest of FcArgs are first touched after
+// the weight stream has been issued.  q_ct_parts = uniform_ct | uniform_parts << 16,
+// q_bh_batch = bh_full | batch << 8.
+#define PIVOT_GEMV_PARAMS const int4* __restrict__ p_chunks, const int32_t* __restrict__ p_idx, \
+    const void* __restrict__ p_vals, const void* __restrict__ p_x, \
+    int q_ct_parts, int q_bh_batch, int q_xn_vecs, int q_xs_stride, int q_ldx, int q_pad
+#define PIVOT_GEMV_ARGS(a) (a).chunks, (a).xidx, (a).vals, (a).x, ((a).uniform_ct | ((a).uniform_parts << 16)), \
+    ((a).bh_full | ((a).batch << 8)), (a).xn_vecs, (a).xs_stride, (int)(a).ldx, 0
+
 // Per-dtype / per-path launchers, each in its own translation unit.
 int launch_gemv_f32(const FcArgs& a, int bhs, int bw, int nb, int nw, int xres, dim3 grid, size_t smem, hipStream_t st);
 int launch_gemv_f16(const FcArgs& a, int bhs, int bw, int nb, int nw, int xres, dim3 grid, size_t smem, hipStream_t st);
@@ -151,13 +163,15 @@ struct XStage {
     // SRC_LDS = true:  `x` is the whole of x already copied into LDS (row b at
     // b * a.xn_stride), so the gather costs no second trip to memory.
     template <bool SRC_LDS>
-    __device__ __forceinline__ void gather(const FcArgs& a, const int32_t* xidx, const WT* x, WT* xs,
+    __device__ __forceinline__ void gather(int batch, long long ldx, int xn_stride, int xs_stride,
+                                           const int32_t* xidx, const WT* x, WT* xs,
                                            int tile_begin, int ne, int b0, int tid) {
         const int b = tid % NB;
-        const bool row_ok = (b0 + b) < a.batch;
-        const WT* xrow = SRC_LDS ? x + b * a.xn_stride : x + (long long)(row_ok ? b0 + b : 0) * a.ldx;
-        WT* xsrow = xs + b * a.xs_stride;
-        const int dump = a.xs_stride - 1;
+        const bool row_ok = (b0 + b) < batch;
+        const WT* xrow = SRC_LDS ? x + b * xn_stride
+                                 : x + (long long)(row_ok ? b0 + b : 0) * ldx;
+        WT* xsrow = xs + b * xs_stride;
+        const int dump = xs_stride - 1;
         WT v[XP];
         #pragma unroll
         for (int k = 0; k < XP; ++k) v[k] = xrow[src[k] > 0 ? src[k] : 0];
@@ -202,28 +216,29 @@ struct XRes {
     static constexpr int VEC = Elem<WT>::VEC;
     static constexpr int XN = 8;
     V v[XN];
-    __device__ __forceinline__ void load(const FcArgs& a, const void* x, int b0, int tid) {
-        const int total = NB * a.xn_vecs;
+    __device__ __forceinline__ void load(int batch, int ldx, int xn_vecs, const void* x, int b0, int tid) {
+        const int total = NB * xn_vecs;
         #pragma unroll
         for (int j = 0; j < XN; ++j) {
             const int id = tid + j * NT;
-            const int b = (NB == 1) ? 0 : id / a.xn_vecs;
-            const int i = (NB == 1) ? id : id - b * a.xn_vecs;
-            const bool ok = id < total && (b0 + b) < a.batch;
-            const WT* row = reinterpret_cast<const WT*>(x) + (long long)(ok ? b0 + b : 0) * a.ldx;
+            const int b = (NB == 1) ? 0 : id / xn_vecs;
+            const int i = (NB == 1) ? id : id - b * xn_vecs;
+            const bool ok = id < total && (b0 + b) < batch;
+            const WT* row = reinterpret_cast<const WT*>(x) + (long long)(ok ? b0 + b : 0) * ldx;
             v[j] = load16<V>(row + (size_t)(ok ? i : 0) * VEC);
         }
     }
-    __device__ __forceinline__ void store(const FcArgs& a, WT* xn, int b0, int tid) {
-        const int total = NB * a.xn_vecs;
-        const int dump = NB * a.xn_stride;              // one spare vector after the last row
+    __device__ __forceinline__ void store(int batch, int xn_vecs, WT* xn, int b0, int tid) {
+        const int total = NB * xn_vecs;
+        const int xn_stride = xn_vecs * VEC;
+        const int dump = NB * xn_stride;                // one spare vector after the last row
         #pragma unroll
         for (int j = 0; j < XN; ++j) {
             const int id = tid + j * NT;
-            const int b = (NB == 1) ? 0 : id / a.xn_vecs;
-            const int i = (NB == 1) ? id : id - b * a.xn_vecs;
-            const bool ok = id < total && (b0 + b) < a.batch;
-            *reinterpret_cast<V*>(xn + (ok ? b * a.xn_stride + i * VEC : dump)) = v[j];
+            const int b = (NB == 1) ? 0 : id / xn_vecs;
+            const int i = (NB == 1) ? id : id - b * xn_vecs;
+            const bool ok = id < total && (b0 + b) < batch;
+            *reinterpret_cast<V*>(xn + (ok ? b * xn_stride + i * VEC : dump)) = v[j];
         }
     }
 };
@@ -232,15 +247,15 @@ struct XRes {
 // schedule is uniform (balanced pruning: every block row keeps the same
 // number of tiles), which takes one dependent load off the critical path.
 struct Chunk { int br, tile_begin, ntiles, slot, first, nparts; };
-__device__ __forceinline__ Chunk load_chunk(const FcArgs& a, const int4* chunks, const int32_t* part_base) {
+__device__ __forceinline__ Chunk load_chunk(int uniform_ct, int uniform_parts, const int4* chunks, const int32_t* part_base) {
     Chunk c;
-    if (a.uniform_ct > 0) {
-        c.br = blockIdx.x / a.uniform_parts;
-        c.tile_begin = blockIdx.x * a.uniform_ct;
-        c.ntiles = a.uniform_ct;
+    if (uniform_ct > 0) {
+        c.br = blockIdx.x / uniform_parts;
+        c.tile_begin = blockIdx.x * uniform_ct;
+        c.ntiles = uniform_ct;
         c.slot = blockIdx.x;
-        c.first = c.br * a.uniform_parts;
-        c.nparts = a.uniform_parts;
+        c.first = c.br * uniform_parts;
+        c.nparts = uniform_parts;
     } else {
         const int4 cd = chunks[blockIdx.x];
         c.br = cd.x; c.tile_begin = cd.y; c.ntiles = cd.z - cd.y; c.slot = cd.w;
@@ -311,7 +326,7 @@ __device__ __forceinline__ void finish_rows(const FcArgs& a, const float* red, i
 // covers RPW rows per load.
 // ---------------------------------------------------------------------------
 template <typename WT, int BH, int BW, int NB, int NW, bool XR>
-__global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(PIVOT_LEAD_PARAMS, FcArgs a) {
+__global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(PIVOT_GEMV_PARAMS, FcArgs a) {
     using V = typename Elem<WT>::vec;
     constexpr int VEC = Elem<WT>::VEC;
     constexpr int NT  = NW * 64;
@@ -327,31 +342,33 @@ __global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(PIVOT_LEAD_PARAMS, FcA
     __shared__ int s_flag;
     // LDS: [x-resident copy of x: NB rows + a dump vector][staged x-segments]; the sums reuse it afterwards
     WT* xn = reinterpret_cast<WT*>(smem);
-    WT* xs = XR ? xn + NB * a.xn_stride + VEC : xn;
+    WT* xs = XR ? xn + NB * q_xn_vecs * VEC + VEC : xn;
     float* red = reinterpret_cast<float*>(smem);        // reused after the stream phase
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int b0 = blockIdx.y * NB, slice = blockIdx.z;
-    const Chunk ck = load_chunk(a, p_chunks, p_part_base);
+    // only the preloaded arguments are used up to the point where the weight stream has been issued
+    const int q_uniform_ct = q_ct_parts & 0xFFFF, q_uniform_parts = q_ct_parts >> 16;
+    const int q_bh_full = q_bh_batch & 0xFF, q_batch = q_bh_batch >> 8;
+    const Chunk ck = load_chunk(q_uniform_ct, q_uniform_parts, p_chunks, a.part_base);
     const int br = ck.br, tile_begin = ck.tile_begin, ntiles = ck.ntiles, slot = ck.slot;
     const int first = ck.first, nparts = ck.nparts;
     const int ngroups = (ntiles + TPL - 1) / TPL;
-    const int row0 = br * a.bh_full + slice * BH;
+    const int row0 = br * q_bh_full + slice * BH;
+    const int tile_elems = q_bh_full * BW;
 
-    // order of issue = order of arrival: (x,) gather indices, epilogue operands, then the weights
+    // order of issue = order of arrival: (x,) gather indices, then the weights, then the epilogue operands
     XRes<WT, NB, NT> xres;
-    if constexpr (XR) xres.load(a, p_x, b0, tid);
+    if constexpr (XR) xres.load(q_batch, q_ldx, q_xn_vecs, p_x, b0, tid);
     XStage<WT, BW, NB, NT> xst;
     xst.load_idx(p_idx, tile_begin, ntiles * BW, tid);
-    RowPre<BH, N, NT> rp;
-    rp.load(p_bias, p_scatter, row0, tid);
 
     const int s  = lane / LPR;                          // row within the wave-load
     const int cg = lane % LPR;                          // column group
     const int ts = (TPL > 1) ? s / BH : 0;              // tile within the group
-    const size_t gstride = (size_t)TPL * a.tile_elems;  // elements between groups of tiles
-    const WT* vbase = reinterpret_cast<const WT*>(p_vals) + (size_t)tile_begin * a.tile_elems
+    const size_t gstride = (size_t)TPL * tile_elems;    // elements between groups of tiles
+    const WT* vbase = reinterpret_cast<const WT*>(p_vals) + (size_t)tile_begin * tile_elems
                       + (size_t)slice * BH * BW + lane * VEC;
 
     // Loads are unconditional (group index clamped; the value array is padded by
@@ -370,12 +387,16 @@ __global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(PIVOT_LEAD_PARAMS, FcA
     };
 
     issue(wave);
+    RowPre<BH, N, NT> rp;
+    rp.load(a.bias_p, a.scatter, row0, tid);
+    // every load above is issued before anything below waits for one of them
+    __builtin_amdgcn_sched_barrier(0);
     if constexpr (XR) {
-        xres.store(a, xn, b0, tid);
+        xres.store(q_batch, q_xn_vecs, xn, b0, tid);
         lds_barrier();
-        xst.template gather<true>(a, p_idx, xn, xs, tile_begin, ntiles * BW, b0, tid);
+        xst.template gather<true>(q_batch, q_ldx, q_xn_vecs * VEC, q_xs_stride, p_idx, xn, xs, tile_begin, ntiles * BW, b0, tid);
     } else {
-        xst.template gather<false>(a, p_idx, reinterpret_cast<const WT*>(p_x), xs, tile_begin, ntiles * BW, b0, tid);
+        xst.template gather<false>(q_batch, q_ldx, 0, q_xs_stride, p_idx, reinterpret_cast<const WT*>(p_x), xs, tile_begin, ntiles * BW, b0, tid);
     }
     lds_barrier();
 
@@ -389,7 +410,7 @@ __global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(PIVOT_LEAD_PARAMS, FcA
         const int tl = g * TPL + ts;
         #pragma unroll
         for (int b = 0; b < NB; ++b) {
-            const V xv = *reinterpret_cast<const V*>(xs + b * a.xs_stride + tl * BW + cg * VEC);
+            const V xv = *reinterpret_cast<const V*>(xs + b * q_xs_stride + tl * BW + cg * VEC);
             #pragma unroll
             for (int j = 0; j < NL; ++j) acc[j][b] = dot_vec(w[u][j], xv, acc[j][b]);
         }
@@ -491,7 +512,7 @@ __global__ void __launch_bounds__(NW * 64) fc_mfma_kernel(PIVOT_LEAD_PARAMS, FcA
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int b0 = blockIdx.y * NBT, slice = blockIdx.z;
-    const Chunk ck = load_chunk(a, p_chunks, p_part_base);
+    const Chunk ck = load_chunk(a.uniform_ct, a.uniform_parts, p_chunks, p_part_base);
     const int br = ck.br, tile_begin = ck.tile_begin, ntiles = ck.ntiles, slot = ck.slot;
     const int first = ck.first, nparts = ck.nparts;
     const int row0 = br * a.bh_full + slice * BH;

@@ -5,9 +5,9 @@ namespace pivot {
 
 template <int BH, int BW, int NB, bool XR>
 static int launch_t(const FcArgs& a, int nw, dim3 grid, size_t smem, hipStream_t st) {
-    if (nw == 16)     hipLaunchKernelGGL((fc_gemv_kernel<float, BH, BW, NB, 16, XR>), grid, dim3(16 * 64), smem, st, PIVOT_LEAD_ARGS(a, a.xidx), a);
-    else if (nw == 8) hipLaunchKernelGGL((fc_gemv_kernel<float, BH, BW, NB, 8, XR>), grid, dim3(8 * 64), smem, st, PIVOT_LEAD_ARGS(a, a.xidx), a);
-    else              hipLaunchKernelGGL((fc_gemv_kernel<float, BH, BW, NB, 4, XR>), grid, dim3(4 * 64), smem, st, PIVOT_LEAD_ARGS(a, a.xidx), a);
+    if (nw == 16)     hipLaunchKernelGGL((fc_gemv_kernel<float, BH, BW, NB, 16, XR>), grid, dim3(16 * 64), smem, st, PIVOT_GEMV_ARGS(a), a);
+    else if (nw == 8) hipLaunchKernelGGL((fc_gemv_kernel<float, BH, BW, NB, 8, XR>), grid, dim3(8 * 64), smem, st, PIVOT_GEMV_ARGS(a), a);
+    else              hipLaunchKernelGGL((fc_gemv_kernel<float, BH, BW, NB, 4, XR>), grid, dim3(4 * 64), smem, st, PIVOT_GEMV_ARGS(a), a);
     HIP_TRY(hipGetLastError());
     return PIVOT_OK;
 }

@@ -104,6 +104,8 @@ int launch_fc(const FcLaunch& L) {
     // x-resident variant: every work item first copies the whole of x (nbt rows) into LDS with independent
     // coalesced loads and gathers from there.  Taken when the rows are 16-byte vectors, a thread has to hold at
     // most 8 of them, and everything fits in 64 KB of LDS.
+    if (L.ldx > 0x7fffffffLL) { set_error("ldx too large"); return PIVOT_E_SHAPE; }
+    if (L.uniform_ct > 0xFFFF || L.uniform_parts > 0x7FFF) a.uniform_ct = a.uniform_parts = 0;   // packed into 16 bits each: fall back to loaded descriptors
     const int vec = 16 / es;
     const int xlen = L.x_block_order ? L.K_pad : L.K;
     int xres = 0;
