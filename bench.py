@@ -141,6 +141,8 @@ def main():
 
     # launch floor: an empty kernel back to back on the same stream
     null_us = BU.graph_time(lambda i, s: B.pivot_null_run(s), 200, replays=10)
+    # one launch that only READS the layer's algorithmic bytes, cold and warm: what no single launch can beat
+    floor_cold_us, floor_warm_us = BU.stream_floor(p.algorithmic_bytes(1), COLD_FOOTPRINT)
 
     # the same layer dense on the GPU: this library's streaming kernel, cold, and torch.mv as a guard
     dense_bytes = p.dense_bytes(1)
@@ -191,6 +193,9 @@ def main():
         "cold_eager_python_launch_us": round(eager_cold_us, 3),
         "timing": "HIP events around replays of captured graphs of plain launches (exactly K launches)",
         "null_kernel_us": round(null_us, 3),
+        "read_only_launch_us": {"cold": round(floor_cold_us, 3), "warm": round(floor_warm_us, 3),
+                                "note": "one launch that only reads the same number of bytes (pivot_stream_read_run)"},
+        "cold_vs_read_only_launch": round(floor_cold_us / cold_us, 3),
         "dense_gpu_us": {"own_kernel_cold": round(dense_us, 3), "torch_mv_cold": round(torch_mv_us, 3)},
         "speedup_vs_dense": round(dense_best_us / cold_us, 3),
         "linear_speedup": round(1.0 / kept, 3),

@@ -57,3 +57,28 @@ def time_graph(g, n_launch, replays, warm_replays=2, repeats=1):
 def graph_time(enqueue, n_launch, replays=5, repeats=3):
     g = capture(enqueue, n_launch)
     return time_graph(g, n_launch, replays, repeats=repeats)
+
+
+_floor_cache = {}
+
+
+def stream_floor(nbytes, footprint=2 * (256 + 32) * (1 << 20)):
+    """(cold_us, warm_us) of ONE launch that only reads `nbytes` (pivot_stream_read_run): the measured ceiling
+    for a single launch of that size.  Cold rotates through separate regions of >= `footprint` bytes in total."""
+    from paper_1712_01084_amd import binding as B
+    kb = max(1, int(nbytes) // 1024)
+    if kb in _floor_cache:
+        return _floor_cache[kb]
+    n = kb * 1024
+    stride = -(-n // 4096) * 4096
+    ncopies = int(max(2, min(600, -(-footprint // n))))
+    buf = torch.zeros(ncopies * stride, dtype=torch.uint8, device="cuda")
+    out = torch.empty(2048, dtype=torch.float32, device="cuda")
+    base = buf.data_ptr()
+    cold = graph_time(lambda i, s: B.pivot_stream_read_run(base + (i % ncopies) * stride, n, out.data_ptr(), s),
+                      ncopies * max(1, 64 // ncopies), replays=4)
+    warm = graph_time(lambda i, s: B.pivot_stream_read_run(base, n, out.data_ptr(), s), 100, replays=6)
+    del buf
+    torch.cuda.empty_cache()
+    _floor_cache[kb] = (cold, warm)
+    return cold, warm

@@ -298,6 +298,14 @@ int  pivot_csr_run(const int32_t* row_ptr_dev, const int32_t* col_dev, const voi
  * to the layer times (the paper averages whole calls, Section 5.1). */
 int  pivot_null_run(void* stream);
 
+/* Measurement aid: one launch (256 workgroups of 8 wavefronts, 16 bytes per
+ * lane, eight loads in flight per wavefront) that does nothing but read the
+ * first bytes/1024 KB of buf_dev once and store one float per wavefront to
+ * out_dev (2048 floats).  Its time, cache-cold, is what a single launch of the
+ * layer kernel cannot beat for the same number of bytes on this device: the
+ * measured counterpart of the bandwidth roofline for layers of a few MB. */
+int  pivot_stream_read_run(const void* buf_dev, size_t bytes, float* out_dev, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -31,7 +31,7 @@ EXPORTS = [
     "pivot_mlp_plan", "pivot_mlp_plan_host_view", "pivot_mlp_plan_destroy",
     "pivot_mlp_workspace_bytes", "pivot_mlp_run",
     "pivot_lstm_workspace_bytes", "pivot_lstm_run", "pivot_lstm_status",
-    "pivot_dense_run", "pivot_csr_run", "pivot_null_run", "pivot_feedback_search",
+    "pivot_dense_run", "pivot_csr_run", "pivot_null_run", "pivot_stream_read_run", "pivot_feedback_search",
 ]
 
 
@@ -109,6 +109,7 @@ def lib():
     L.pivot_lstm_status.argtypes = [vp, i32, i32, vp, vp, C.POINTER(C.c_int)]
     L.pivot_dense_run.argtypes = [vp, i32, i32, i32, vp, i64, vp, vp, i64, i32, i32, vp]
     L.pivot_null_run.argtypes = [vp]
+    L.pivot_stream_read_run.argtypes = [vp, sz, vp, vp]
     L.pivot_feedback_search.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp, C.POINTER(C.c_double)]
     L.pivot_csr_run.argtypes = [vp, vp, vp, i32, i32, i64, vp, vp, vp, i32, vp]
     _lib = L
@@ -251,6 +252,10 @@ def pivot_dense_run(W_ptr, wdtype, M, K, x_ptr, ldx, bias_ptr, y_ptr, ldy, batch
 
 def pivot_null_run(stream=None):
     _check(lib().pivot_null_run(stream))
+
+
+def pivot_stream_read_run(buf_ptr, nbytes, out_ptr, stream=None):
+    _check(lib().pivot_stream_read_run(buf_ptr, nbytes, out_ptr, stream))
 
 
 def pivot_csr_run(row_ptr_ptr, col_ptr, val_ptr, wdtype, M, nnz, x_ptr, bias_ptr, y_ptr, act, stream=None):

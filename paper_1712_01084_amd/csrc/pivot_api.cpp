@@ -509,6 +509,12 @@ int pivot_lstm_status(const pivot_fc_plan_t* plan, int steps, int batch, const v
 
 int pivot_null_run(void* stream) { return launch_null(stream); }
 
+int pivot_stream_read_run(const void* buf_dev, size_t bytes, float* out_dev, void* stream) {
+    if (!buf_dev || !out_dev) { set_error("buf_dev and out_dev are required"); return PIVOT_E_NULL; }
+    if (bytes < 1024 || bytes > ((size_t)1 << 40) || (reinterpret_cast<uintptr_t>(buf_dev) & 15) != 0) { set_error("bytes must be >= 1024 and the buffer 16-byte aligned"); return PIVOT_E_SHAPE; }
+    return launch_stream_read(buf_dev, bytes, out_dev, stream);
+}
+
 int pivot_csr_run(const int32_t* row_ptr_dev, const int32_t* col_dev, const void* val_dev, int wdtype, int M,
                   int64_t nnz, const void* x_dev, const float* bias_dev, float* y_dev, int act, void* stream) {
     if (!row_ptr_dev || !x_dev || !y_dev || (nnz > 0 && (!col_dev || !val_dev))) { set_error("row_ptr, col, val, x and y are required"); return PIVOT_E_NULL; }

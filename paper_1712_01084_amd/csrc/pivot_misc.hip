@@ -48,6 +48,42 @@ int launch_null(void* stream) {
     return PIVOT_OK;
 }
 
+// Reads `npieces` KB once: wavefront w reads pieces [w*per, (w+1)*per), 16 bytes per lane and piece, eight
+// pieces in flight, adds everything up and stores one float per wavefront.  Nothing but the read: what one
+// launch of the layer kernel cannot beat for the same number of bytes.
+__global__ void __launch_bounds__(512) stream_read_kernel(const f32x4* __restrict__ base, int npieces, int per_wave,
+                                                           float* __restrict__ out) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int gw = blockIdx.x * (blockDim.x >> 6) + wave;
+    const int last = npieces > 0 ? npieces - 1 : 0;
+    float acc = 0.f;
+    for (int k0 = 0; k0 < per_wave; k0 += 8) {
+        f32x4 w[8];
+        #pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            int piece = gw * per_wave + k0 + u;
+            piece = piece < last ? piece : last;
+            w[u] = base[(size_t)piece * 64 + lane];
+        }
+        #pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (k0 + u < per_wave && gw * per_wave + k0 + u < npieces) acc += w[u].x + w[u].y + w[u].z + w[u].w;
+    }
+    acc = group_sum<64>(acc);
+    if (lane == 0) out[gw] = acc;
+}
+
+int launch_stream_read(const void* buf, size_t bytes, float* out, void* stream) {
+    const int G = 256, W = 8;
+    const int npieces = (int)(bytes / 1024);
+    if (npieces < 1) { set_error("stream read needs at least 1 KB"); return PIVOT_E_SHAPE; }
+    const int per_wave = (npieces + G * W - 1) / (G * W);
+    hipLaunchKernelGGL(stream_read_kernel, dim3(G), dim3(W * 64), 0, reinterpret_cast<hipStream_t>(stream),
+                       reinterpret_cast<const f32x4*>(buf), npieces, per_wave, out);
+    HIP_TRY(hipGetLastError());
+    return PIVOT_OK;
+}
+
 int launch_fill_zero(void* dev, size_t bytes, void* stream) {
     if (bytes == 0) return PIVOT_OK;
     if (bytes % 4 != 0 || (reinterpret_cast<uintptr_t>(dev) % 4) != 0) { set_error("fill needs 4-byte alignment"); return PIVOT_E_SHAPE; }

@@ -174,3 +174,57 @@ def test_config5_gate_matrix_full_batch8():
     p = lp.fc
     p.x = np.random.default_rng(3).standard_normal((8, p.K)).astype(np.float16)
     G.check_fc(p)
+
+
+def test_stream_read_aid_sums_what_it_reads():
+    # the read-only launch used as the measured ceiling: every byte is read exactly once
+    rng = np.random.default_rng(0)
+    for nkb in (1, 7, 2048, 14848):
+        a = rng.integers(-8, 9, size=nkb * 256).astype(np.float32)      # small integers: the sum is exact in fp32
+        buf = torch.from_numpy(a).cuda()
+        out = torch.full((2048,), float("nan"), dtype=torch.float32, device="cuda")
+        B.pivot_stream_read_run(buf.data_ptr(), nkb * 1024, out.data_ptr(), torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        assert float(out.cpu().numpy().astype(np.float64).sum()) == float(a.astype(np.float64).sum())
+    with pytest.raises(B.PivotError):
+        B.pivot_stream_read_run(buf.data_ptr(), 100, out.data_ptr(), None)
+
+
+@pytest.mark.parametrize("wdtype,bh,bw,batch,K", [(WL.F32, 32, 32, 1, 320), (WL.F32, 16, 16, 3, 200), (WL.F16, 64, 16, 4, 264),
+                                                 (WL.F16, 16, 32, 2, 96), (WL.F32, 8, 8, 1, 1024)])
+def test_gather_through_lds_copy_of_x_equals_gather_from_global(wdtype, bh, bw, batch, K):
+    # the two forms of the column gather feed the same arithmetic in the same order: identical bits;
+    # an x whose rows are not whole 16-byte vectors (or misaligned) silently takes the global form
+    p = WL.gen_fc(4 * bh + 5, K, bh, bw, 0.4, seed=31, wdtype=wdtype, batch=batch, act=WL.ACT_RELU)
+    outs = []
+    for flags in (0, B.PIVOT_PLAN_GATHER_FROM_GLOBAL):
+        plan = G.dev_plan(p, flags=flags)
+        try:
+            outs.append(G.run_fc(plan, p))
+        finally:
+            B.pivot_fc_plan_destroy(plan)
+    assert outs[0].tobytes() == outs[1].tobytes()
+    y_ref, D = G.oracle_of(p)
+    assert O.max_scaled_error(outs[0], y_ref, D) <= G.TOL[p.wdtype]
+
+
+def test_lds_copy_of_x_with_odd_row_length_and_offset_pointer():
+    # K = 203 (not a multiple of 4) and an x that starts 4 bytes past a 16-byte boundary: the kernel must fall
+    # back to the global gather on its own, with the same result
+    p = WL.gen_fc(64, 203, 16, 16, 0.5, seed=33, batch=2, act=WL.ACT_NONE)
+    plan = G.dev_plan(p)
+    try:
+        G.check_fc(p)
+        ld = 208
+        xd = torch.zeros(2 * ld + 1, dtype=torch.float32, device="cuda")
+        xv = xd[1:].view(2, ld)
+        xv[:, :p.K] = torch.from_numpy(p.x).cuda()
+        yd = torch.empty((2, p.M), dtype=torch.float32, device="cuda")
+        ws = G.workspace(B.pivot_fc_workspace_bytes(plan, 2))
+        B.pivot_fc_run(plan, xv.data_ptr(), ld, yd.data_ptr(), p.M, 2, ws.data_ptr(), ws.numel(),
+                       torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        y_ref, D = G.oracle_of(p)
+        assert O.max_scaled_error(yd.cpu().numpy(), y_ref, D) <= 1e-5
+    finally:
+        B.pivot_fc_plan_destroy(plan)
