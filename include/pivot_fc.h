@@ -87,12 +87,15 @@ typedef struct pivot_fc_desc {
     int32_t flags;        /* PIVOT_PLAN_* bits, 0 = defaults                             */
 } pivot_fc_desc;
 
-/* By default the vector kernel (batch <= 4) first copies the whole of x into
- * LDS with loads that depend on nothing and gathers from there whenever x is
- * small enough (rows of 16-byte vectors, at most 8 vectors per thread, 64 KB of
- * LDS); otherwise each gathered element is a dependent load x[index] from
- * global memory.  This bit forces the second form (for measurements).       */
+/* The vector kernel (batch <= 4) has two forms of the column gather: each
+ * gathered element a dependent load x[index] from global memory, or the whole
+ * of x first copied into LDS with loads that depend on nothing and the gather
+ * run from there (possible when x is small enough: rows of 16-byte vectors, at
+ * most 8 vectors per thread, 64 KB of LDS).  By default the library takes the
+ * second form when it is possible and a work item streams 48 KB of weights or
+ * more.  These bits force the first form, or the second whenever possible.   */
 #define PIVOT_PLAN_GATHER_FROM_GLOBAL 1
+#define PIVOT_PLAN_GATHER_FROM_LDS_COPY 4
 /* pivot_lstm_run normally runs the whole sequence in one launch when the plan
  * allows it (see there); this bit forces one layer launch and one cell launch
  * per step instead (for measurements and as the reference of the parity test). */

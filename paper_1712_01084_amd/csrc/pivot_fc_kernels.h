@@ -53,6 +53,7 @@ struct FcArgs {
     int uniform_ct;             // > 0: every chunk has exactly this many tiles and chunk i starts at tile i*uniform_ct,
     int uniform_parts;          //      uniform_parts chunks per block row: the descriptor is computed, not loaded
     int T;                      // kept tiles in the whole plan (the CBR layout strides by it)
+    int chunk_tiles;            // the plan's chunk size (vector kernel: fixes the LDS row stride)
     int xn_vecs;                // x-resident vector kernel: 16-byte vectors per row of x (row length / VEC)
     int xn_stride;              //   elements between the LDS copies of consecutive batch rows (the row length)
 };
@@ -65,17 +66,20 @@ struct FcArgs {
     const int32_t* __restrict__ p_scatter, const void* __restrict__ p_x
 #define PIVOT_LEAD_ARGS(a, idx) (a).chunks, (a).part_base, (idx), (a).vals, (a).bias_p, (a).scatter, (a).x
 
-// The vector kernel goes further: everything it needs before its loads can be
-// issued (four pointers and six scalars = the 14 dwords that are preloaded
-// into SGPRs) comes first, so that no load waits for a fetch of the argument
-// block; bias, scatter index and the rest of FcArgs are first touched after
-// the weight stream has been issued.  q_ct_parts = uniform_ct | uniform_parts << 16,
-// q_bh_batch = bh_full | batch << 8.
+// The vector kernel goes further: everything it needs before and while its
+// loads are issued (six pointers and two packed scalars = the 14 dwords that
+// are preloaded into SGPRs) comes first, so that nothing on the way to the
+// first FMA waits for a fetch of the argument block; the rest of FcArgs is
+// first touched in the epilogue (the row stride of x, needed only with more
+// than one batch row, also comes from there).
+// q_ct_parts = tiles per chunk | uniform_parts << 16 (uniform_parts 0: the schedule is not regular, the low half
+//              is then the plan's chunk size); q_misc = bh_full | batch << 7 | xn_vecs << 14.
 #define PIVOT_GEMV_PARAMS const int4* __restrict__ p_chunks, const int32_t* __restrict__ p_idx, \
-    const void* __restrict__ p_vals, const void* __restrict__ p_x, \
-    int q_ct_parts, int q_bh_batch, int q_xn_vecs, int q_xs_stride, int q_ldx, int q_pad
-#define PIVOT_GEMV_ARGS(a) (a).chunks, (a).xidx, (a).vals, (a).x, ((a).uniform_ct | ((a).uniform_parts << 16)), \
-    ((a).bh_full | ((a).batch << 8)), (a).xn_vecs, (a).xs_stride, (int)(a).ldx, 0
+    const void* __restrict__ p_vals, const void* __restrict__ p_x, const float* __restrict__ p_bias, \
+    const int32_t* __restrict__ p_scatter, int q_ct_parts, int q_misc
+#define PIVOT_GEMV_ARGS(a) (a).chunks, (a).xidx, (a).vals, (a).x, (a).bias_p, (a).scatter, \
+    ((a).uniform_ct > 0 ? ((a).uniform_ct | ((a).uniform_parts << 16)) : (a).chunk_tiles), \
+    ((a).bh_full | ((a).batch << 7) | ((a).xn_vecs << 14))
 
 // Per-dtype / per-path launchers, each in its own translation unit.
 int launch_gemv_f32(const FcArgs& a, int bhs, int bw, int nb, int nw, int xres, dim3 grid, size_t smem, hipStream_t st);
@@ -216,7 +220,7 @@ struct XRes {
     static constexpr int VEC = Elem<WT>::VEC;
     static constexpr int XN = 8;
     V v[XN];
-    __device__ __forceinline__ void load(int batch, int ldx, int xn_vecs, const void* x, int b0, int tid) {
+    __device__ __forceinline__ void load(int batch, long long ldx, int xn_vecs, const void* x, int b0, int tid) {
         const int total = NB * xn_vecs;
         #pragma unroll
         for (int j = 0; j < XN; ++j) {
@@ -342,15 +346,17 @@ __global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(PIVOT_GEMV_PARAMS, FcA
     __shared__ int s_flag;
     // LDS: [x-resident copy of x: NB rows + a dump vector][staged x-segments]; the sums reuse it afterwards
     WT* xn = reinterpret_cast<WT*>(smem);
-    WT* xs = XR ? xn + NB * q_xn_vecs * VEC + VEC : xn;
+    WT* xs = XR ? xn + NB * (int)((unsigned)q_misc >> 14) * VEC + VEC : xn;
     float* red = reinterpret_cast<float*>(smem);        // reused after the stream phase
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int b0 = blockIdx.y * NB, slice = blockIdx.z;
     // only the preloaded arguments are used up to the point where the weight stream has been issued
-    const int q_uniform_ct = q_ct_parts & 0xFFFF, q_uniform_parts = q_ct_parts >> 16;
-    const int q_bh_full = q_bh_batch & 0xFF, q_batch = q_bh_batch >> 8;
+    const int q_uniform_parts = q_ct_parts >> 16, q_uniform_ct = q_uniform_parts > 0 ? (q_ct_parts & 0xFFFF) : 0;
+    const int q_bh_full = q_misc & 0x7F, q_batch = (q_misc >> 7) & 0x7F, q_xn_vecs = (int)((unsigned)q_misc >> 14);
+    const int q_xs_stride = (q_ct_parts & 0xFFFF) * BW + VEC;
+    const long long q_ldx = (NB == 1) ? 0 : a.ldx;     // one batch row: row 0 only
     const Chunk ck = load_chunk(q_uniform_ct, q_uniform_parts, p_chunks, a.part_base);
     const int br = ck.br, tile_begin = ck.tile_begin, ntiles = ck.ntiles, slot = ck.slot;
     const int first = ck.first, nparts = ck.nparts;
@@ -388,7 +394,7 @@ __global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(PIVOT_GEMV_PARAMS, FcA
 
     issue(wave);
     RowPre<BH, N, NT> rp;
-    rp.load(a.bias_p, a.scatter, row0, tid);
+    rp.load(p_bias, p_scatter, row0, tid);
     // every load above is issued before anything below waits for one of them
     __builtin_amdgcn_sched_barrier(0);
     if constexpr (XR) {

@@ -83,7 +83,7 @@ struct FcLaunch {
     int uniform_ct, uniform_parts;  // > 0: regular schedule, the kernels compute the chunk descriptor
     int x_block_order;          // 1: x is [batch][K_pad] in block order (what the matrix-core kernel needs)
     int K;                      // row length of a natural-order x
-    int x_resident;             // 0: never copy the whole of x into LDS; otherwise the launcher decides
+    int x_resident;             // 0: never copy the whole of x into LDS; 1: the launcher decides; 2: whenever possible
     // data
     const void* x; int64_t ldx;
     void*       y; int64_t ldy;

@@ -86,7 +86,7 @@ int launch_fc(const FcLaunch& L) {
     a.nchunks = L.nchunks; a.nbr = L.nbr;
     a.bh_full = L.bh; a.tile_elems = L.bh * L.bw;
     a.uniform_ct = L.uniform_ct; a.uniform_parts = L.uniform_parts;
-    a.T = L.T;
+    a.T = L.T; a.chunk_tiles = L.chunk_tiles;
     dim3 grid(L.nchunks, ngy, sl);
     hipStream_t st = reinterpret_cast<hipStream_t>(L.stream);
 
@@ -97,25 +97,29 @@ int launch_fc(const FcLaunch& L) {
         size_t smem = (size_t)rw * bhs * nbt * 4;
         return launch_mfma_f16(a, mfma_kind(L.wdtype, L.bh, L.bw), bhs, L.bw, nw, grid, smem, st);
     }
-    // staged x: nbt rows of chunk_tiles*bw elements, plus 16 bytes whose last element is the dump slot
-    a.xs_stride = L.chunk_tiles * L.bw + 16 / es;
+    if (L.uniform_ct > 0xFFFF || L.uniform_parts > 0x7FFF) a.uniform_ct = a.uniform_parts = 0;   // packed into 16 bits each: fall back to loaded descriptors
+    // staged x: nbt rows of (tiles per chunk)*bw elements, plus 16 bytes whose last element is the dump slot
+    // (the vector kernel derives the same stride from its preloaded arguments)
+    a.xs_stride = (a.uniform_ct > 0 ? a.uniform_ct : L.chunk_tiles) * L.bw + 16 / es;
     size_t xs_bytes = (size_t)nbt * a.xs_stride * es;
     size_t red_bytes = (size_t)nw * bhs * nbt * 4;
     // x-resident variant: every work item first copies the whole of x (nbt rows) into LDS with independent
     // coalesced loads and gathers from there.  Taken when the rows are 16-byte vectors, a thread has to hold at
-    // most 8 of them, and everything fits in 64 KB of LDS.
-    if (L.ldx > 0x7fffffffLL) { set_error("ldx too large"); return PIVOT_E_SHAPE; }
-    if (L.uniform_ct > 0xFFFF || L.uniform_parts > 0x7FFF) a.uniform_ct = a.uniform_parts = 0;   // packed into 16 bits each: fall back to loaded descriptors
+    // most 8 of them, everything fits in 64 KB of LDS, and the work item streams at least 48 KB of weights
+    // (measured: below that the extra LDS pass and barrier cost 0.3 us warm and gain under 0.1 us cold;
+    // above it they gain 0.2-0.4 us cold).
+    if (L.chunk_tiles > 0xFFFF || L.bh > 64 || L.batch > 64) { set_error("shape outside the vector kernel's packed arguments"); return PIVOT_E_UNSUPPORTED; }
     const int vec = 16 / es;
     const int xlen = L.x_block_order ? L.K_pad : L.K;
     int xres = 0;
     size_t xn_bytes = 0;
-    if (L.layout == PIVOT_BRC && L.x_resident != 0 && xlen % vec == 0 && L.ldx % vec == 0 &&
+    const size_t item_bytes = (size_t)(a.uniform_ct > 0 ? a.uniform_ct : L.chunk_tiles) * bhs * L.bw * es;
+    if (L.layout == PIVOT_BRC && L.x_resident != 0 && (L.x_resident == 2 || item_bytes >= 48 * 1024) && xlen % vec == 0 && L.ldx % vec == 0 &&
         (reinterpret_cast<uintptr_t>(L.x) & 15) == 0 && (size_t)nbt * (xlen / vec) <= (size_t)8 * nw * 64) {
         xn_bytes = (size_t)nbt * xlen * es + 16;
         if (xn_bytes + xs_bytes <= 64 * 1024 && red_bytes <= 64 * 1024) xres = 1;
     }
-    a.xn_vecs = xlen / vec; a.xn_stride = xlen;
+    a.xn_vecs = xres ? xlen / vec : 0; a.xn_stride = xlen;
     size_t smem = xres ? xn_bytes + xs_bytes : xs_bytes;
     smem = align_up(smem > red_bytes ? smem : red_bytes, 16);
     if (smem > 64 * 1024) { set_error("chunk does not fit in LDS (%zu bytes)", smem); return PIVOT_E_UNSUPPORTED; }

@@ -55,8 +55,9 @@ def oracle_of(p, x=None):
     return O.oracle_fc(p.Wp, p.tile_mask, p.prow, p.pcol, p.bias, x, p.bh, p.bw, p.act, return_scale=True)
 
 
-def check_fc(p, chunk_tiles=0, natural=False, repeats=2, x=None, wg_waves=0, row_slices=0, layout=B.PIVOT_BRC):
-    plan = dev_plan(p, chunk_tiles=chunk_tiles, natural=natural, wg_waves=wg_waves, row_slices=row_slices, layout=layout)
+def check_fc(p, chunk_tiles=0, natural=False, repeats=2, x=None, wg_waves=0, row_slices=0, layout=B.PIVOT_BRC, flags=0):
+    plan = dev_plan(p, chunk_tiles=chunk_tiles, natural=natural, wg_waves=wg_waves, row_slices=row_slices, layout=layout,
+                    flags=flags)
     try:
         y = run_fc(plan, p, x=x, repeats=repeats)
     finally:

@@ -27,6 +27,17 @@ def test_every_tile_shape_ragged_small(bh, bw, wdtype):
         G.check_fc(p, chunk_tiles=ct)
 
 
+@pytest.mark.parametrize("wdtype", [WL.F32, WL.F16])
+@pytest.mark.parametrize("bh,bw", SHAPES)
+def test_every_tile_shape_with_gather_from_lds_copy(bh, bw, wdtype):
+    # the same cases with the whole of x copied into LDS first (K is a multiple of 8 here, so the form applies)
+    M, K = 5 * bh - 3, 9 * bw + 8
+    for batch, ct in ((1, 2), (3, 4), (4, 9)):
+        p = WL.gen_fc(M, K, bh, bw, 0.6, seed=200 + bh + bw, wdtype=wdtype, batch=batch, act=WL.ACT_RELU)
+        p.tile_mask[2, :] = 0
+        G.check_fc(p, chunk_tiles=ct, flags=B.PIVOT_PLAN_GATHER_FROM_LDS_COPY)
+
+
 @pytest.mark.parametrize("wdtype,bh,bw", [(WL.F32, 32, 32), (WL.F32, 64, 16), (WL.F16, 64, 16), (WL.F16, 64, 64)])
 @pytest.mark.parametrize("waves", [4, 8, 16])
 @pytest.mark.parametrize("slices", [1, 2, 4, 8])
@@ -197,7 +208,7 @@ def test_gather_through_lds_copy_of_x_equals_gather_from_global(wdtype, bh, bw, 
     # an x whose rows are not whole 16-byte vectors (or misaligned) silently takes the global form
     p = WL.gen_fc(4 * bh + 5, K, bh, bw, 0.4, seed=31, wdtype=wdtype, batch=batch, act=WL.ACT_RELU)
     outs = []
-    for flags in (0, B.PIVOT_PLAN_GATHER_FROM_GLOBAL):
+    for flags in (B.PIVOT_PLAN_GATHER_FROM_LDS_COPY, B.PIVOT_PLAN_GATHER_FROM_GLOBAL):
         plan = G.dev_plan(p, flags=flags)
         try:
             outs.append(G.run_fc(plan, p))
@@ -212,7 +223,7 @@ def test_lds_copy_of_x_with_odd_row_length_and_offset_pointer():
     # K = 203 (not a multiple of 4) and an x that starts 4 bytes past a 16-byte boundary: the kernel must fall
     # back to the global gather on its own, with the same result
     p = WL.gen_fc(64, 203, 16, 16, 0.5, seed=33, batch=2, act=WL.ACT_NONE)
-    plan = G.dev_plan(p)
+    plan = G.dev_plan(p, flags=B.PIVOT_PLAN_GATHER_FROM_LDS_COPY)
     try:
         G.check_fc(p)
         ld = 208
