@@ -169,6 +169,11 @@ def main():
     dense_best_us = min(dense_us, torch_mv_us)
 
     cold_us, warm_us = cold_ms * 1e3, warm_ms * 1e3
+    # the instantiation the library launches for this plan (row slice height, tile width, batch rows, wavefronts,
+    # gather from an LDS copy of x: taken when a work item streams >= 48 KB and x fits)
+    slice_rows = p.bh // view["row_slices"]
+    lds_copy = view["chunk_tiles"] * slice_rows * p.bw * 4 >= 48 * 1024 and p.K % 4 == 0 and p.K * 4 <= 8 * view["wg_waves"] * 64 * 16
+    kernel_name = "pivot::fc_gemv_kernel<float, %d, %d, 1, %d, %s>" % (slice_rows, p.bw, view["wg_waves"], "true" if lds_copy else "false")
     kept = p.T / float(p.nbr * p.nbc)
     achieved = alg_bytes / (cold_us * 1e-6) / 1e9
     out = {
@@ -200,7 +205,7 @@ def main():
         "speedup_vs_dense": round(dense_best_us / cold_us, 3),
         "linear_speedup": round(1.0 / kept, 3),
         "algorithmic_bytes": alg_bytes,
-        "roofline": {"bound": "hbm", "kernel": "fc_gemv_kernel<float,32,32,1,*>", "achieved": round(achieved, 1),
+        "roofline": {"bound": "hbm", "kernel": kernel_name, "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": parse_traffic(),
                      "warm_effective": round(alg_bytes / (warm_us * 1e-6) / 1e9, 1)},
