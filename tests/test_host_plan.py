@@ -126,8 +126,36 @@ def test_host_only_plan_cannot_run_and_workspace_sizes():
         with pytest.raises(B.PivotError) as e:
             B.pivot_fc_run(plan, 16, 32, 16, 32, 1, 16, 1 << 20)
         assert e.value.code == B.PIVOT_E_NO_DEVICE
+        # the recurrent entry points refuse a host-only plan too, and check their pointers first
+        with pytest.raises(B.PivotError) as e:
+            B.pivot_lstm_run(plan, 8, 24, 16, 16, 16, None, 2, 1, 16, 1 << 20)
+        assert e.value.code == B.PIVOT_E_NO_DEVICE
+        with pytest.raises(B.PivotError) as e:
+            B.pivot_lstm_run(plan, 8, 24, None, 16, 16, None, 2, 1, 16, 1 << 20)
+        assert e.value.code == B.PIVOT_E_NULL
+        with pytest.raises(B.PivotError) as e:
+            B.pivot_lstm_status(plan, 2, 1, 16)
+        assert e.value.code == B.PIVOT_E_NO_DEVICE
+        with pytest.raises(B.PivotError) as e:
+            B.pivot_lstm_status(plan, 2, 1, None)
+        assert e.value.code == B.PIVOT_E_NULL
     finally:
         B.pivot_fc_plan_destroy(plan)
+
+
+def test_measurement_aids_check_their_arguments_without_a_device():
+    with pytest.raises(B.PivotError) as e:
+        B.pivot_stream_read_run(None, 4096, 16)
+    assert e.value.code == B.PIVOT_E_NULL
+    with pytest.raises(B.PivotError) as e:
+        B.pivot_stream_read_run(4096, 100, 16)          # fewer than 1024 bytes
+    assert e.value.code == B.PIVOT_E_SHAPE
+    with pytest.raises(B.PivotError) as e:
+        B.pivot_stream_read_run(4100, 4096, 16)         # not 16-byte aligned
+    assert e.value.code == B.PIVOT_E_SHAPE
+    with pytest.raises(B.PivotError) as e:
+        B.pivot_dense_run(None, B.PIVOT_F32, 4, 4, 16, 4, None, 16, 4, 1, 0)
+    assert e.value.code == B.PIVOT_E_NULL
 
 
 @pytest.mark.parametrize("eliminated", [False, True])
