@@ -41,18 +41,27 @@ struct Piece { const void* src; size_t bytes; void** dst; };
 int upload(pivot_fc_plan_t* p) {
     HostPlan& h = p->host;
     DevPlan& d = p->dev;
-    std::vector<int32_t> xblk;
+    // device-only arrays: the gather index for an x already in block order, the identity scatter of chain
+    // intermediates, and the schedule with each block row's piece range folded in (one load instead of two)
+    std::vector<int32_t> xblk, rowid, chunks8;
     try {
         xblk.resize(h.xidx.size());
+        rowid.assign(h.M_pad, -1);
+        chunks8.assign((size_t)h.nchunks * 8, 0);
     } catch (const std::bad_alloc&) { set_error("out of host memory"); return PIVOT_E_ALLOC; }
     for (int t = 0; t < h.T; ++t)
         for (int c = 0; c < h.d.bw; ++c) xblk[(size_t)t * h.d.bw + c] = h.col_idx[t] * h.d.bw + c;
-    std::vector<int32_t> rowid(h.M_pad, -1);
     for (int r = 0; r < h.d.M; ++r) rowid[r] = r;
+    for (int j = 0; j < h.nchunks; ++j) {
+        for (int q = 0; q < 4; ++q) chunks8[(size_t)8 * j + q] = h.chunks[(size_t)4 * j + q];
+        const int br = h.chunks[(size_t)4 * j];
+        chunks8[(size_t)8 * j + 4] = h.part_base[br];
+        chunks8[(size_t)8 * j + 5] = h.part_base[br + 1] - h.part_base[br];
+    }
     Piece pieces[] = {
         {h.vals.data(),      h.vals.size(),                 (void**)&d.vals},
         {h.col_idx.data(),   h.col_idx.size() * 4,          (void**)&d.col_idx},
-        {h.chunks.data(),    h.chunks.size() * 4,           (void**)&d.chunks},
+        {chunks8.data(),     chunks8.size() * 4,            (void**)&d.chunks},
         {h.part_base.data(), h.part_base.size() * 4,        (void**)&d.part_base},
         {h.bias_p.data(),    h.bias_p.size() * 4,           (void**)&d.bias_p},
         {h.prow_pad.data(),  h.prow_pad.size() * 4,         (void**)&d.prow_pad},

@@ -261,10 +261,14 @@ __device__ __forceinline__ Chunk load_chunk(int uniform_ct, int uniform_parts, c
         c.first = c.br * uniform_parts;
         c.nparts = uniform_parts;
     } else {
-        const int4 cd = chunks[blockIdx.x];
+        // device copy of the schedule: eight ints per chunk (block_row, tile_begin, tile_end, slot, first slot of
+        // the block row, its number of pieces, 0, 0), so that the descriptor is ONE dependent load
+        const int4 cd = chunks[2 * blockIdx.x];
+        const int4 ce = chunks[2 * blockIdx.x + 1];
         c.br = cd.x; c.tile_begin = cd.y; c.ntiles = cd.z - cd.y; c.slot = cd.w;
-        c.first = part_base[c.br];
-        c.nparts = part_base[c.br + 1] - c.first;
+        c.first = ce.x;
+        c.nparts = ce.y;
+        (void)part_base;
     }
     return c;
 }

@@ -73,7 +73,7 @@ struct FcLaunch {
     // plan
     const void*    vals;
     const int32_t* col_idx;
-    const int32_t* chunks;      // int4 per chunk
+    const int32_t* chunks;      // eight ints per chunk: (block_row, tile_begin, tile_end, slot, first slot of the row, pieces, 0, 0)
     const int32_t* part_base;
     const float*   bias_p;
     const int32_t* xidx;        // [T*bw]: index into x of column c of tile t (-1 = padding): through pcol for
