@@ -173,7 +173,7 @@ def main():
     # gather from an LDS copy of x: taken when a work item streams >= 48 KB and x fits)
     slice_rows = p.bh // view["row_slices"]
     lds_copy = view["chunk_tiles"] * slice_rows * p.bw * 4 >= 48 * 1024 and p.K % 4 == 0 and p.K * 4 <= 8 * view["wg_waves"] * 64 * 16
-    kernel_name = "pivot::fc_gemv_kernel<float, %d, %d, 1, %d, %s>" % (slice_rows, p.bw, view["wg_waves"], "true" if lds_copy else "false")
+    kernel_name = "pivot::fc_gemv_kernel<float, %d, %d, 1, %d, %d>" % (slice_rows, p.bw, view["wg_waves"], 1 if lds_copy else 0)
     kept = p.T / float(p.nbr * p.nbc)
     achieved = alg_bytes / (cold_us * 1e-6) / 1e9
     out = {

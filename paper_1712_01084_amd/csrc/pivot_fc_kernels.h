@@ -333,7 +333,9 @@ __device__ __forceinline__ void finish_rows(const FcArgs& a, const float* red, i
 // stream, i.e. VEC columns of one tile row; LPR lanes cover a row, a wave
 // covers RPW rows per load.
 // ---------------------------------------------------------------------------
-template <typename WT, int BH, int BW, int NB, int NW, bool XR>
+// XR: 0 = gather from global x; 1 = gather from an LDS copy of x; 2 = the same for irregular schedules, with
+// the copy requested before the work item's descriptor has arrived (it depends on nothing).
+template <typename WT, int BH, int BW, int NB, int NW, int XR>
 __global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(PIVOT_GEMV_PARAMS, FcArgs a) {
     using V = typename Elem<WT>::vec;
     constexpr int VEC = Elem<WT>::VEC;
@@ -361,6 +363,9 @@ __global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(PIVOT_GEMV_PARAMS, FcA
     const int q_bh_full = q_misc & 0x7F, q_batch = (q_misc >> 7) & 0x7F, q_xn_vecs = (int)((unsigned)q_misc >> 14);
     const int q_xs_stride = (q_ct_parts & 0xFFFF) * BW + VEC;
     const long long q_ldx = (NB == 1) ? 0 : a.ldx;     // one batch row: row 0 only
+    // order of issue = order of arrival: (x,) gather indices, then the weights, then the epilogue operands
+    XRes<WT, NB, NT> xres;
+    if constexpr (XR == 2) xres.load(q_batch, q_ldx, q_xn_vecs, p_x, b0, tid);
     const Chunk ck = load_chunk(q_uniform_ct, q_uniform_parts, p_chunks, a.part_base);
     const int br = ck.br, tile_begin = ck.tile_begin, ntiles = ck.ntiles, slot = ck.slot;
     const int first = ck.first, nparts = ck.nparts;
@@ -368,9 +373,7 @@ __global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(PIVOT_GEMV_PARAMS, FcA
     const int row0 = br * q_bh_full + slice * BH;
     const int tile_elems = q_bh_full * BW;
 
-    // order of issue = order of arrival: (x,) gather indices, then the weights, then the epilogue operands
-    XRes<WT, NB, NT> xres;
-    if constexpr (XR) xres.load(q_batch, q_ldx, q_xn_vecs, p_x, b0, tid);
+    if constexpr (XR == 1) xres.load(q_batch, q_ldx, q_xn_vecs, p_x, b0, tid);
     XStage<WT, BW, NB, NT> xst;
     xst.load_idx(p_idx, tile_begin, ntiles * BW, tid);
 
@@ -401,7 +404,7 @@ __global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(PIVOT_GEMV_PARAMS, FcA
     rp.load(p_bias, p_scatter, row0, tid);
     // every load above is issued before anything below waits for one of them
     __builtin_amdgcn_sched_barrier(0);
-    if constexpr (XR) {
+    if constexpr (XR != 0) {
         xres.store(q_batch, q_xn_vecs, xn, b0, tid);
         lds_barrier();
         xst.template gather<true>(q_batch, q_ldx, q_xn_vecs * VEC, q_xs_stride, p_idx, xn, xs, tile_begin, ntiles * BW, b0, tid);

@@ -3,7 +3,7 @@
 
 namespace pivot {
 
-template <int BH, int BW, int NB, bool XR>
+template <int BH, int BW, int NB, int XR>
 static int launch_t(const FcArgs& a, int nw, dim3 grid, size_t smem, hipStream_t st) {
     if (nw == 16)     hipLaunchKernelGGL((fc_gemv_kernel<float, BH, BW, NB, 16, XR>), grid, dim3(16 * 64), smem, st, PIVOT_GEMV_ARGS(a), a);
     else if (nw == 8) hipLaunchKernelGGL((fc_gemv_kernel<float, BH, BW, NB, 8, XR>), grid, dim3(8 * 64), smem, st, PIVOT_GEMV_ARGS(a), a);
@@ -15,9 +15,9 @@ static int launch_t(const FcArgs& a, int nw, dim3 grid, size_t smem, hipStream_t
 template <int BH, int BW>
 static int launch_nb(const FcArgs& a, int nb, int nw, int xres, dim3 grid, size_t smem, hipStream_t st) {
     switch (nb) {
-        case 1: return xres ? launch_t<BH, BW, 1, true>(a, nw, grid, smem, st) : launch_t<BH, BW, 1, false>(a, nw, grid, smem, st);
-        case 2: return xres ? launch_t<BH, BW, 2, true>(a, nw, grid, smem, st) : launch_t<BH, BW, 2, false>(a, nw, grid, smem, st);
-        default: return xres ? launch_t<BH, BW, 4, true>(a, nw, grid, smem, st) : launch_t<BH, BW, 4, false>(a, nw, grid, smem, st);
+        case 1: return xres == 2 ? launch_t<BH, BW, 1, 2>(a, nw, grid, smem, st) : (xres ? launch_t<BH, BW, 1, 1>(a, nw, grid, smem, st) : launch_t<BH, BW, 1, 0>(a, nw, grid, smem, st));
+        case 2: return xres == 2 ? launch_t<BH, BW, 2, 2>(a, nw, grid, smem, st) : (xres ? launch_t<BH, BW, 2, 1>(a, nw, grid, smem, st) : launch_t<BH, BW, 2, 0>(a, nw, grid, smem, st));
+        default: return xres == 2 ? launch_t<BH, BW, 4, 2>(a, nw, grid, smem, st) : (xres ? launch_t<BH, BW, 4, 1>(a, nw, grid, smem, st) : launch_t<BH, BW, 4, 0>(a, nw, grid, smem, st));
     }
 }
 

@@ -117,7 +117,7 @@ int launch_fc(const FcLaunch& L) {
     if (L.layout == PIVOT_BRC && L.x_resident != 0 && (L.x_resident == 2 || item_bytes >= 48 * 1024) && xlen % vec == 0 && L.ldx % vec == 0 &&
         (reinterpret_cast<uintptr_t>(L.x) & 15) == 0 && (size_t)nbt * (xlen / vec) <= (size_t)8 * nw * 64) {
         xn_bytes = (size_t)nbt * xlen * es + 16;
-        if (xn_bytes + xs_bytes <= 64 * 1024 && red_bytes <= 64 * 1024) xres = 1;
+        if (xn_bytes + xs_bytes <= 64 * 1024 && red_bytes <= 64 * 1024) xres = a.uniform_ct > 0 ? 1 : 2;
     }
     a.xn_vecs = xres ? xlen / vec : 0; a.xn_stride = xlen;
     size_t smem = xres ? xn_bytes + xs_bytes : xs_bytes;
