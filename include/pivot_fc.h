@@ -239,14 +239,16 @@ int    pivot_mlp_run(const pivot_mlp_plan_t* plan, const void* x_dev, int64_t ld
  *   z_dbg    device, optional [batch][4H] fp32: gate pre-activations of the
  *            last step in natural order (NULL to skip)
  *
- * Two forms.  Plans with fp16 16x32 BRC tiles, batch <= 16, batch*K_pad <= 131072
- * and at most 16 kept tiles per wavefront of a full-device grid run the whole
- * sequence in ONE launch: the kept tiles stay in registers for all steps, the
- * steps are separated by grid-wide barriers (a counter in the workspace), and
- * per step only h, x_t and the gate sums move.  Its workgroups wait for each
- * other, so nothing else should occupy the device while it runs; a wait that
- * does not end within about a second gives up, every workgroup leaves, h/c
- * are left unwritten and the status word reads 1.  Every other plan (or
+ * Two forms.  Plans with fp16 16x32 BRC tiles, batch <= 8, at most 16 kept
+ * tiles per wavefront of a full-device grid (one workgroup per compute unit,
+ * all co-resident) and K_pad/32 <= that grid run the whole sequence in ONE
+ * launch: the kept tiles stay in registers for all steps and per step only h,
+ * x_t and the gate sums move.  There are no grid barriers: the exchanged data
+ * carries the step it belongs to and a consumer re-reads until it sees its
+ * step.  Its workgroups wait for each other, so nothing else should occupy
+ * the device while it runs; a wait that does not end within 2^18 polls gives
+ * up, every workgroup leaves, h/c are left unwritten and the status word
+ * reads 1.  Every other plan (or
  * PIVOT_PLAN_LSTM_LAUNCH_PER_STEP) runs one layer launch and one cell launch
  * per step.  pivot_lstm_status synchronises the stream and returns the status
  * word of the last pivot_lstm_run on this workspace (0 = completed).
