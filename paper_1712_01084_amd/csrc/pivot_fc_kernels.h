@@ -143,55 +143,107 @@ struct RowPre {
 // P_col): xs[b][t*BW + c] = x[b][xidx[(tile_begin + t)*BW + c]].  xidx is the
 // column index array already composed with the tile list, so one index load
 // feeds the gather.  Index -1 (padding column) and batch rows past `batch`
-// read as zero.  NB consecutive threads share one column and take one batch
-// row each.  The first XP indices per thread are fetched before the weight
-// stream is issued (loads return in order: an index fetched after the weights
-// would only arrive after them).  All of these loads and LDS writes are
-// unconditional: out-of-range elements use a clamped index and land in a dump
-// slot at the end of the LDS row.
+// read as zero.  A thread takes elements tid, tid + NT, ... and moves all NB
+// batch rows of each: the index does not depend on the batch row, so the
+// number of dependent index rounds is that of a single row.  The first XP
+// indices per thread are fetched before the weight stream is issued (loads
+// return in order: an index fetched after the weights would only arrive after
+// them).  All of these loads and LDS writes are unconditional: out-of-range
+// elements use a clamped index and land in a dump slot at the end of the LDS row.
 template <typename WT, int BW, int NB, int NT>
 struct XStage {
     static constexpr int XP = 4;
-    static constexpr int STEP = NT / NB;
     int src[XP];
     __device__ __forceinline__ void load_idx(const int32_t* xidx, int tile_begin, int ne, int tid) {
         const int32_t* xi = xidx + (size_t)tile_begin * BW;
         const int emax = ne > 0 ? ne - 1 : 0;       // index arrays carry 16 bytes of padding: xi[0] is readable
         #pragma unroll
         for (int k = 0; k < XP; ++k) {
-            const int e = tid / NB + k * STEP;
+            const int e = tid + k * NT;
             src[k] = xi[e < emax ? e : emax];
         }
     }
     // SRC_LDS = false: `x` is the global x (one dependent global load per element).
     // SRC_LDS = true:  `x` is the whole of x already copied into LDS (row b at
-    // b * a.xn_stride), so the gather costs no second trip to memory.
+    // b * xn_stride), so the gather costs no second trip to memory.
     template <bool SRC_LDS>
     __device__ __forceinline__ void gather(int batch, long long ldx, int xn_stride, int xs_stride,
                                            const int32_t* xidx, const WT* x, WT* xs,
                                            int tile_begin, int ne, int b0, int tid) {
-        const int b = tid % NB;
-        const bool row_ok = (b0 + b) < batch;
-        const WT* xrow = SRC_LDS ? x + b * xn_stride
-                                 : x + (long long)(row_ok ? b0 + b : 0) * ldx;
-        WT* xsrow = xs + b * xs_stride;
+        const WT* xrow[NB];
+        bool row_ok[NB];
+        #pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            row_ok[b] = (b0 + b) < batch;
+            xrow[b] = SRC_LDS ? x + b * xn_stride : x + (long long)(row_ok[b] ? b0 + b : 0) * ldx;
+        }
+        const int dump = xs_stride - 1;
+        auto move = [&](const int (&sr)[XP], int e0) {
+            WT v[XP][NB];
+            #pragma unroll
+            for (int k = 0; k < XP; ++k)
+                #pragma unroll
+                for (int b = 0; b < NB; ++b) v[k][b] = xrow[b][sr[k] > 0 ? sr[k] : 0];
+            #pragma unroll
+            for (int k = 0; k < XP; ++k) {
+                const int e = e0 + k * NT;
+                #pragma unroll
+                for (int b = 0; b < NB; ++b)
+                    xs[b * xs_stride + (e < ne ? e : dump)] = (sr[k] >= 0 && row_ok[b]) ? v[k][b] : WT(0);
+            }
+        };
+        move(src, tid);
+        // longer chunks: further rounds of XP elements per thread, each round's loads issued together
+        const int32_t* xi = xidx + (size_t)tile_begin * BW;
+        const int emax = ne > 0 ? ne - 1 : 0;
+        for (int e0 = tid + XP * NT; e0 < ne; e0 += XP * NT) {
+            int s2[XP];
+            #pragma unroll
+            for (int k = 0; k < XP; ++k) {
+                const int e = e0 + k * NT;
+                s2[k] = xi[e < emax ? e : emax];
+            }
+            move(s2, e0);
+        }
+    }
+};
+
+// One batch row: the same staging with the batch loop folded away.
+template <typename WT, int BW, int NT>
+struct XStage<WT, BW, 1, NT> {
+    static constexpr int XP = 4;
+    int src[XP];
+    __device__ __forceinline__ void load_idx(const int32_t* xidx, int tile_begin, int ne, int tid) {
+        const int32_t* xi = xidx + (size_t)tile_begin * BW;
+        const int emax = ne > 0 ? ne - 1 : 0;
+        #pragma unroll
+        for (int k = 0; k < XP; ++k) {
+            const int e = tid + k * NT;
+            src[k] = xi[e < emax ? e : emax];
+        }
+    }
+    template <bool SRC_LDS>
+    __device__ __forceinline__ void gather(int batch, long long ldx, int xn_stride, int xs_stride,
+                                           const int32_t* xidx, const WT* x, WT* xs,
+                                           int tile_begin, int ne, int b0, int tid) {
+        const bool row_ok = b0 < batch;
+        const WT* xrow = SRC_LDS ? x : x + (long long)(row_ok ? b0 : 0) * ldx;
         const int dump = xs_stride - 1;
         WT v[XP];
         #pragma unroll
         for (int k = 0; k < XP; ++k) v[k] = xrow[src[k] > 0 ? src[k] : 0];
         #pragma unroll
         for (int k = 0; k < XP; ++k) {
-            const int e = tid / NB + k * STEP;
-            xsrow[e < ne ? e : dump] = (src[k] >= 0 && row_ok) ? v[k] : WT(0);
+            const int e = tid + k * NT;
+            xs[e < ne ? e : dump] = (src[k] >= 0 && row_ok) ? v[k] : WT(0);
         }
-        // longer chunks: further rounds of XP elements per thread, each round's loads issued together
         const int32_t* xi = xidx + (size_t)tile_begin * BW;
         const int emax = ne > 0 ? ne - 1 : 0;
-        for (int e0 = tid / NB + XP * STEP; e0 < ne; e0 += XP * STEP) {
+        for (int e0 = tid + XP * NT; e0 < ne; e0 += XP * NT) {
             int s2[XP];
             #pragma unroll
             for (int k = 0; k < XP; ++k) {
-                const int e = e0 + k * STEP;
+                const int e = e0 + k * NT;
                 s2[k] = xi[e < emax ? e : emax];
             }
             WT v2[XP];
@@ -199,8 +251,8 @@ struct XStage {
             for (int k = 0; k < XP; ++k) v2[k] = xrow[s2[k] > 0 ? s2[k] : 0];
             #pragma unroll
             for (int k = 0; k < XP; ++k) {
-                const int e = e0 + k * STEP;
-                xsrow[e < ne ? e : dump] = (s2[k] >= 0 && row_ok) ? v2[k] : WT(0);
+                const int e = e0 + k * NT;
+                xs[e < ne ? e : dump] = (s2[k] >= 0 && row_ok) ? v2[k] : WT(0);
             }
         }
     }
@@ -362,7 +414,9 @@ __global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(PIVOT_GEMV_PARAMS, FcA
     const int q_uniform_parts = q_ct_parts >> 16, q_uniform_ct = q_uniform_parts > 0 ? (q_ct_parts & 0xFFFF) : 0;
     const int q_bh_full = q_misc & 0x7F, q_batch = (q_misc >> 7) & 0x7F, q_xn_vecs = (int)((unsigned)q_misc >> 14);
     const int q_xs_stride = (q_ct_parts & 0xFFFF) * BW + VEC;
-    const long long q_ldx = (NB == 1) ? 0 : a.ldx;     // one batch row: row 0 only
+    // one batch row: row 0 only; the LDS-copy forms are only launched on densely packed rows of x (row stride =
+    // row length), so that the copy can be requested without waiting for the rest of the argument block
+    const long long q_ldx = (NB == 1) ? 0 : (XR != 0) ? (long long)q_xn_vecs * VEC : a.ldx;
     // order of issue = order of arrival: (x,) gather indices, then the weights, then the epilogue operands
     XRes<WT, NB, NT> xres;
     if constexpr (XR == 2) xres.load(q_batch, q_ldx, q_xn_vecs, p_x, b0, tid);

@@ -104,7 +104,8 @@ int launch_fc(const FcLaunch& L) {
     size_t xs_bytes = (size_t)nbt * a.xs_stride * es;
     size_t red_bytes = (size_t)nw * bhs * nbt * 4;
     // x-resident variant: every work item first copies the whole of x (nbt rows) into LDS with independent
-    // coalesced loads and gathers from there.  Taken when the rows are 16-byte vectors, a thread has to hold at
+    // coalesced loads and gathers from there.  Taken when the rows are 16-byte vectors (densely packed if there
+    // is more than one: the kernel then derives the row stride from its preloaded arguments), a thread has to hold at
     // most 8 of them, everything fits in 64 KB of LDS, and the work item streams at least 48 KB of weights
     // (measured: below that the extra LDS pass and barrier cost 0.3 us warm and gain under 0.1 us cold;
     // above it they gain 0.2-0.4 us cold).
@@ -114,7 +115,7 @@ int launch_fc(const FcLaunch& L) {
     int xres = 0;
     size_t xn_bytes = 0;
     const size_t item_bytes = (size_t)(a.uniform_ct > 0 ? a.uniform_ct : L.chunk_tiles) * bhs * L.bw * es;
-    if (L.layout == PIVOT_BRC && L.x_resident != 0 && (L.x_resident == 2 || item_bytes >= 48 * 1024) && xlen % vec == 0 && L.ldx % vec == 0 &&
+    if (L.layout == PIVOT_BRC && L.x_resident != 0 && (L.x_resident == 2 || item_bytes >= 48 * 1024) && xlen % vec == 0 && (nbt == 1 || L.ldx == xlen) &&
         (reinterpret_cast<uintptr_t>(L.x) & 15) == 0 && (size_t)nbt * (xlen / vec) <= (size_t)8 * nw * 64) {
         xn_bytes = (size_t)nbt * xlen * es + 16;
         if (xn_bytes + xs_bytes <= 64 * 1024 && red_bytes <= 64 * 1024) xres = a.uniform_ct > 0 ? 1 : 2;
