@@ -209,7 +209,7 @@ int prepare(const pivot_fc_plan_t* plan, int batch, void* ws, size_t ws_bytes, F
     L.row_slices = h.row_slices;
     L.uniform_ct = h.uniform_ct; L.uniform_parts = h.uniform_parts;
     L.batch = batch;
-    int nbt = fc_batch_tile(h.d.layout, h.d.wdtype, h.d.bh, h.d.bw, batch);
+    int nbt = fc_batch_tile(h.d.layout, h.d.wdtype, h.d.bh, h.d.bw, h.chunk_tiles, batch);
     int ngy = (batch + nbt - 1) / nbt;
     L.tickets = reinterpret_cast<uint32_t*>(ws);
     L.partials = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + fc_ticket_bytes(h.nbr, ngy, h.row_slices));
@@ -222,7 +222,7 @@ int prepare(const pivot_fc_plan_t* plan, int batch, void* ws, size_t ws_bytes, F
 int natural_input(const pivot_fc_plan_t* plan, const void* x_dev, int64_t ldx, int batch, void* xg, void* stream,
                   FcLaunch& L) {
     const HostPlan& h = plan->host;
-    if (fc_uses_matrix_cores(h.d.layout, h.d.wdtype, h.d.bh, h.d.bw, batch)) {
+    if (fc_uses_matrix_cores(h.d.layout, h.d.wdtype, h.d.bh, h.d.bw, h.chunk_tiles, batch)) {
         int rc = launch_gather_x(x_dev, ldx, plan->dev.pcol_pad, xg, h.K_pad, batch, h.d.wdtype, stream);
         if (rc != PIVOT_OK) return rc;
         L.x = xg; L.ldx = h.K_pad; L.xidx = plan->dev.xidx_blk; L.x_block_order = 1;

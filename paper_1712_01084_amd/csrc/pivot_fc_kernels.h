@@ -85,6 +85,7 @@ struct FcArgs {
 int launch_gemv_f32(const FcArgs& a, int bhs, int bw, int nb, int nw, int xres, dim3 grid, size_t smem, hipStream_t st);
 int launch_gemv_f16(const FcArgs& a, int bhs, int bw, int nb, int nw, int xres, dim3 grid, size_t smem, hipStream_t st);
 int launch_mfma_f16(const FcArgs& a, int kind, int bhs, int bw, int nw, dim3 grid, size_t smem, hipStream_t st);
+int launch_mfma_lds_f16(const FcArgs& a, int kind, int bhs, int bw, int nbs, int nw, int xres, dim3 grid, size_t smem, hipStream_t st);
 int launch_colmajor(const FcArgs& a, int layout, int wdtype, int bh, int bw, int nw, dim3 grid, size_t smem, hipStream_t st);
 
 #define PIVOT_SHAPES(X) \
@@ -682,6 +683,123 @@ __global__ void __launch_bounds__(NW * 64) fc_mfma_kernel(PIVOT_LEAD_PARAMS, FcA
     if (wave < RW) put(wave);
     __syncthreads();
     finish_rows<BH, NBT, NT>(a, red, RW, br, slot, first, nparts, rp, b0, tid, &s_flag);
+}
+
+// ---------------------------------------------------------------------------
+// batch 3..16, fp16 weights: matrix cores fed from LDS.  With several batch
+// rows the vector kernel is bound by LDS (every 16-byte weight load needs one
+// 16-byte LDS read per batch row); here a tile slice is the MFMA A operand and
+// ONE 16-byte LDS read per lane supplies the B fragment for all batch rows.
+// Prologue and epilogue are the vector kernel's (preloaded arguments only, the
+// whole of x copied first where it fits, gather into LDS xs[b][tile*BW + c]
+// for b < NBS); lane l reads B[k 8(l/MR)..+7][column l%MR] = xs[l%MR][...].
+// Lanes whose column is past NBS read row 0; their accumulator columns are
+// never stored.
+// ---------------------------------------------------------------------------
+template <int KIND, int BH, int BW, int NBS, int NW, int XR>
+__global__ void __launch_bounds__(NW * 64) fc_mfma_lds_kernel(PIVOT_GEMV_PARAMS, FcArgs a) {
+    using MF = Mfma<KIND>;
+    using acc_t = typename MF::acc_t;
+    using WT = _Float16;
+    constexpr int VEC = 8;
+    constexpr int MR = MF::MR, MK = MF::MK, CV = MF::CV;
+    constexpr int NT = NW * 64;
+    constexpr int RB = BH / MR;                         // row blocks per tile slice
+    constexpr int KS = BW / MK;                         // k steps per tile
+    constexpr int LT = RB * KS;                         // 16-byte weight loads per lane per tile
+    constexpr int U  = (LT >= 8) ? 1 : 8 / LT;          // tiles in flight per wave
+    constexpr int N  = BH * NBS;
+    static_assert(BH % MR == 0 && BW % MK == 0, "tile shape does not fit this MFMA");
+    static_assert(NBS <= MR, "more staged batch rows than MFMA columns");
+
+    extern __shared__ __align__(16) char smem[];
+    __shared__ int s_flag;
+    const int q_uniform_parts = q_ct_parts >> 16, q_uniform_ct = q_uniform_parts > 0 ? (q_ct_parts & 0xFFFF) : 0;
+    const int q_bh_full = q_misc & 0x7F, q_batch = (q_misc >> 7) & 0x7F, q_xn_vecs = (int)((unsigned)q_misc >> 14);
+    const int q_xs_stride = (q_ct_parts & 0xFFFF) * BW + VEC;
+    WT* xn = reinterpret_cast<WT*>(smem);
+    WT* xs = XR ? xn + NBS * q_xn_vecs * VEC + VEC : xn;
+    float* red = reinterpret_cast<float*>(smem);        // reused after the stream phase: NW * N floats
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int b0 = blockIdx.y * NBS, slice = blockIdx.z;
+    const long long q_ldx = (XR != 0) ? (long long)q_xn_vecs * VEC : a.ldx;
+    XRes<WT, NBS, NT> xres;
+    if constexpr (XR != 0) xres.load(q_batch, q_ldx, q_xn_vecs, p_x, b0, tid);
+    const Chunk ck = load_chunk(q_uniform_ct, q_uniform_parts, p_chunks, a.part_base);
+    const int br = ck.br, tile_begin = ck.tile_begin, ntiles = ck.ntiles, slot = ck.slot;
+    const int first = ck.first, nparts = ck.nparts;
+    const int row0 = br * q_bh_full + slice * BH;
+    const int tile_elems = q_bh_full * BW;
+
+    XStage<WT, BW, NBS, NT> xst;
+    xst.load_idx(p_idx, tile_begin, ntiles * BW, tid);
+
+    const int li = lane % MR;                           // A row / B column of this lane
+    const int lg = lane / MR;                           // k group of 8
+    const _Float16* vbase = reinterpret_cast<const _Float16*>(p_vals) + (size_t)tile_begin * tile_elems
+                            + (size_t)slice * BH * BW + li * BW + lg * 8;
+    const int tmax = ntiles > 0 ? ntiles - 1 : 0;       // clamped, unconditional loads (see fc_gemv_kernel)
+    f16x8 w[U][LT];
+    auto fill = [&](int u, int t) {
+        const int tc = t < tmax ? t : tmax;
+        #pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+            #pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+                w[u][rb * KS + ks] = load16<f16x8>(vbase + (size_t)tc * tile_elems + rb * MR * BW + ks * MK);
+    };
+    #pragma unroll
+    for (int u = 0; u < U; ++u) fill(u, wave + u * NW);
+
+    RowPre<BH, N, NT> rp;
+    rp.load(p_bias, p_scatter, row0, tid);
+    __builtin_amdgcn_sched_barrier(0);                  // every load above is issued before anything below waits
+    if constexpr (XR != 0) {
+        xres.store(q_batch, q_xn_vecs, xn, b0, tid);
+        lds_barrier();
+        xst.template gather<true>(q_batch, q_ldx, q_xn_vecs * VEC, q_xs_stride, p_idx, xn, xs, tile_begin, ntiles * BW, b0, tid);
+    } else {
+        xst.template gather<false>(q_batch, q_ldx, 0, q_xs_stride, p_idx, reinterpret_cast<const WT*>(p_x), xs, tile_begin, ntiles * BW, b0, tid);
+    }
+    lds_barrier();
+
+    acc_t acc[RB];
+    #pragma unroll
+    for (int rb = 0; rb < RB; ++rb) acc[rb] = acc_t(0);
+    const WT* xrow = xs + (li < NBS ? li : 0) * q_xs_stride + lg * 8;
+    auto consume = [&](int u, int t) {
+        #pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const f16x8 xv = *reinterpret_cast<const f16x8*>(xrow + t * BW + ks * MK);
+            #pragma unroll
+            for (int rb = 0; rb < RB; ++rb) acc[rb] = MF::run(w[u][rb * KS + ks], xv, acc[rb]);
+        }
+    };
+    int t0 = wave;
+    for (; t0 + NW * U < ntiles; t0 += NW * U) {
+        #pragma unroll
+        for (int u = 0; u < U; ++u) {
+            consume(u, t0 + u * NW);
+            fill(u, t0 + u * NW + NW * U);
+        }
+    }
+    #pragma unroll
+    for (int u = 0; u < U; ++u)
+        if (t0 + u * NW < ntiles) consume(u, t0 + u * NW);
+
+    // every wave's sums for the staged batch columns go to LDS; the epilogue adds the NW copies
+    __syncthreads();                                    // xs no longer needed; red aliases it
+    if (li < NBS) {
+        #pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+            #pragma unroll
+            for (int v = 0; v < CV; ++v)
+                red[wave * N + li * BH + rb * MR + MF::row_of(lane, v)] = acc[rb][v];
+    }
+    __syncthreads();
+    finish_rows<BH, NBS, NT>(a, red, NW, br, slot, first, nparts, rp, b0, tid, &s_flag);
 }
 
 }  // namespace pivot

@@ -95,9 +95,11 @@ struct FcLaunch {
 };
 
 // Batch rows one launch of the layer kernel covers (grid.y repeats it).
-int    fc_batch_tile(int layout, int wdtype, int bh, int bw, int batch);
-bool   fc_uses_matrix_cores(int layout, int wdtype, int bh, int bw, int batch);
-int    fc_row_slices(int layout, int wdtype, int bh, int bw, int batch, int want);
+enum { kPathVector = 0, kPathMfmaLds = 1, kPathMfmaGather = 2 };
+int    fc_path(int layout, int wdtype, int bh, int bw, int chunk_tiles, int batch);
+int    fc_batch_tile(int layout, int wdtype, int bh, int bw, int chunk_tiles, int batch);
+bool   fc_uses_matrix_cores(int layout, int wdtype, int bh, int bw, int chunk_tiles, int batch);   // the form that needs x in block order
+int    fc_row_slices(int layout, int wdtype, int bh, int bw, int chunk_tiles, int batch, int want);
 // Workspace of one layer application: [arrival counters][partials of split rows][x in block order (matrix path)]
 size_t fc_ticket_bytes(int nbr, int ngy, int slices);
 size_t fc_partial_bytes(const HostPlan& hp, int batch);

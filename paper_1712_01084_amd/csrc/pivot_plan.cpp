@@ -53,9 +53,9 @@ void choose_schedule(HostPlan& hp) {
     int sl = d.row_slices;
     if (sl == 0) {
         sl = 1;
-        while (sl < 8 && hp.nbr * sl < 256 && fc_row_slices(d.layout, d.wdtype, d.bh, d.bw, 1, sl * 2) == sl * 2) sl *= 2;
+        while (sl < 8 && hp.nbr * sl < 256 && fc_row_slices(d.layout, d.wdtype, d.bh, d.bw, 0, 1, sl * 2) == sl * 2) sl *= 2;
     }
-    if (d.device >= 0) sl = fc_row_slices(d.layout, d.wdtype, d.bh, d.bw, 1, sl);
+    if (d.device >= 0) sl = fc_row_slices(d.layout, d.wdtype, d.bh, d.bw, 0, 1, sl);
     hp.row_slices = sl;
 
     const size_t slice_bytes = std::max<size_t>(1, tile_bytes / sl);

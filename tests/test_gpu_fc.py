@@ -83,6 +83,18 @@ def test_batches_fp16_including_matrix_core_path(bh, bw, batch):
     G.check_fc(p, chunk_tiles=3)
 
 
+@pytest.mark.parametrize("batch", [3, 5, 6, 9, 13, 16])
+@pytest.mark.parametrize("bh,bw", [(64, 16), (16, 32), (32, 64)])
+def test_fp16_small_batches_matrix_cores_fed_from_lds(bh, bw, batch):
+    # batch 3..16 with few staged elements: the tile is the MFMA A operand, the B fragments come from the
+    # x-segments staged in LDS (4, 8 or 16 rows; rows past the batch are zero and never stored); whole block
+    # rows per work item, ragged M and K, one empty block row
+    p = WL.gen_fc(3 * bh + 7, 6 * bw - 5, bh, bw, 0.6, seed=40 + batch, wdtype=WL.F16, batch=batch, act=WL.ACT_RELU)
+    p.tile_mask[2, :] = 0
+    G.check_fc(p)
+    G.check_fc(p, wg_waves=8, row_slices=2)
+
+
 def test_degenerate_masks_and_natural_weights():
     p = WL.gen_fc(64, 96, 16, 16, 0.5, seed=9, act=WL.ACT_RELU)
     p.tile_mask[:] = 0                                   # no tile kept: y = relu(b)
@@ -202,7 +214,8 @@ def test_stream_read_aid_sums_what_it_reads():
 
 
 @pytest.mark.parametrize("wdtype,bh,bw,batch,K", [(WL.F32, 32, 32, 1, 320), (WL.F32, 16, 16, 3, 200), (WL.F16, 64, 16, 4, 264),
-                                                 (WL.F16, 16, 32, 2, 96), (WL.F32, 8, 8, 1, 1024)])
+                                                 (WL.F16, 16, 32, 2, 96), (WL.F32, 8, 8, 1, 1024),
+                                                 (WL.F16, 16, 32, 8, 96), (WL.F16, 32, 32, 13, 128)])
 def test_gather_through_lds_copy_of_x_equals_gather_from_global(wdtype, bh, bw, batch, K):
     # the two forms of the column gather feed the same arithmetic in the same order: identical bits;
     # an x whose rows are not whole 16-byte vectors (or misaligned) silently takes the global form
