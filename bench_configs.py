@@ -123,14 +123,14 @@ def time_fc(p, iters, name, dense=True):
     torch.cuda.empty_cache()
 
 
-def time_chain(probs, iters, name):
+def time_chain(probs, iters, name, per_layer=False):
     st = torch.cuda.current_stream().cuda_stream
     alg = sum(p.algorithmic_bytes(1) for p in probs)
     ncopies = int(max(2, -(-COLD_FOOTPRINT // alg)))
     sets = []
     for _ in range(ncopies):
         plans = [dev_plan(p) for p in probs] if not sets else [B.pivot_fc_plan_clone(h) for h in sets[0][0]]
-        sets.append((plans, B.pivot_mlp_plan(plans, 0)))
+        sets.append((plans, B.pivot_mlp_plan(plans, B.PIVOT_MLP_LAUNCH_PER_LAYER if per_layer else 0)))
     xs = [torch.from_numpy(probs[0].x.copy()).cuda() for _ in range(ncopies)]
     M = probs[-1].M
     yd = torch.empty((1, M), dtype=torch.float32, device="cuda")
@@ -144,7 +144,10 @@ def time_chain(probs, iters, name):
 
     cold = gt(go(True), ncopies * max(1, 24 // ncopies))
     warm = gt(go(False), 40)
-    emit(name, cold, warm, alg, None, {"launches": len(probs)})
+    torch.cuda.synchronize()
+    for plans, mlp in sets:
+        assert B.pivot_mlp_status(mlp, st) == 0
+    emit(name, cold, warm, alg, None, {"launches": len(probs) if per_layer else 1})
     for plans, mlp in sets:
         B.pivot_mlp_plan_destroy(mlp)
         for h in plans:
@@ -202,8 +205,11 @@ def main():
                         "cfg3 4096x4096 f16 64x16 %g%% b%d" % (frac * 100, batch))
     if "4" in which:
         for elim in (False, True):
-            time_chain(WL.config4(seed=args.seed, eliminated=elim), args.iters,
-                       "cfg4 MLP 25088-4096-4096-1000 f32 %s" % ("eliminated" if elim else "composed"))
+            for per_layer in (False, True):
+                time_chain(WL.config4(seed=args.seed, eliminated=elim), args.iters,
+                           "cfg4 MLP 25088-4096-4096-1000 f32 %s, %s" % ("eliminated" if elim else "composed",
+                                                                       "launch per layer" if per_layer else "one launch"),
+                           per_layer=per_layer)
     if "5" in which:
         time_lstm(WL.config5(seed=args.seed), "cfg5 LSTM gates 8192x3072 f16 16x32 zipf b8, 256 steps, one launch")
         time_lstm(WL.config5(seed=args.seed), "cfg5 LSTM gates 8192x3072 f16 16x32 zipf b8, 256 steps, launch per step",

@@ -203,8 +203,24 @@ int  pivot_fc_run(const pivot_fc_plan_t* plan, const void* x_dev, int64_t ldx,
  * Intermediates have the plans' wdtype (F16 chains round once per boundary).
  * All layers must share wdtype and device.  Layer plans are borrowed and must
  * outlive the chain plan.
+ *
+ * Two forms.  A chain of fp32 BRC plans of one tile width whose work items
+ * are whole block rows, at most 1024 per layer and all resident on the device
+ * at once, runs at batch 1 in ONE launch (view.one_launch = 1): workgroup g
+ * takes work item g of every layer in turn, an intermediate activation is
+ * stored as a (value, launch tag) pair, and the next layer's gather re-reads
+ * the pairs it needs until they carry this launch's tag.  The pairs and the
+ * launch counters live in device memory owned by the chain plan, so launches
+ * of one chain plan must not overlap (one stream, or ordered by events), and
+ * nothing else should occupy the device while it runs: its workgroups wait
+ * for each other.  A wait that does not end within 2^18 polls gives up, the
+ * status word reads 1 and y_dev is undefined; pivot_mlp_status synchronises
+ * the stream, returns the status of the launches since its last call and
+ * clears it.  Every other chain and batch (or PIVOT_MLP_LAUNCH_PER_LAYER)
+ * runs one launch per layer.
  */
 #define PIVOT_MLP_KEEP_FINAL_BLOCK_ORDER 1
+#define PIVOT_MLP_LAUNCH_PER_LAYER       2
 
 typedef struct pivot_mlp_view {
     int32_t L;
@@ -213,6 +229,7 @@ typedef struct pivot_mlp_view {
     const int32_t* const* dst;   /* [L-1] arrays, dst[l] has M_pad_l entries:
                                     dst[l][r] = invpcol_{l+1}[prow_l[r]], -1 in padding        */
     const int32_t* identity;     /* [L-1] flags: 1 if q[l] is the identity                    */
+    int32_t one_launch;          /* 1 if batch-1 runs of this chain take the one-launch form  */
 } pivot_mlp_view;
 
 int    pivot_mlp_plan(pivot_fc_plan_t* const* layers, int L, int flags, pivot_mlp_plan_t** out);
@@ -224,6 +241,8 @@ size_t pivot_mlp_workspace_bytes(const pivot_mlp_plan_t* plan, int batch);
 int    pivot_mlp_run(const pivot_mlp_plan_t* plan, const void* x_dev, int64_t ldx,
                      void* y_dev, int64_t ldy, int batch,
                      void* ws_dev, size_t ws_bytes, void* stream);
+/* *status = 0 if every one-launch run of this chain since the last call completed, 1 if a wait gave up. */
+int    pivot_mlp_status(const pivot_mlp_plan_t* plan, void* stream, int* status);
 
 /*
  * Recurrent use: an LSTM whose gate matrix (4H x (H+I), gate order i,f,g,o,

@@ -20,6 +20,7 @@ PIVOT_PLAN_GATHER_FROM_LDS_COPY = 4
 PIVOT_ACT_NONE, PIVOT_ACT_RELU = 0, 1
 PIVOT_W_NATURAL, PIVOT_W_PIVOTED = 0, 1
 PIVOT_MLP_KEEP_FINAL_BLOCK_ORDER = 1
+PIVOT_MLP_LAUNCH_PER_LAYER = 2
 
 PIVOT_OK = 0
 PIVOT_E_NULL, PIVOT_E_SHAPE, PIVOT_E_NOT_PERMUTATION, PIVOT_E_UNSUPPORTED = -1, -2, -3, -4
@@ -30,7 +31,7 @@ EXPORTS = [
     "pivot_fc_plan", "pivot_fc_plan_host_view", "pivot_fc_plan_clone", "pivot_fc_plan_destroy",
     "pivot_fc_workspace_bytes", "pivot_workspace_init", "pivot_fc_run",
     "pivot_mlp_plan", "pivot_mlp_plan_host_view", "pivot_mlp_plan_destroy",
-    "pivot_mlp_workspace_bytes", "pivot_mlp_run",
+    "pivot_mlp_workspace_bytes", "pivot_mlp_run", "pivot_mlp_status",
     "pivot_lstm_workspace_bytes", "pivot_lstm_run", "pivot_lstm_status",
     "pivot_dense_run", "pivot_csr_run", "pivot_null_run", "pivot_stream_read_run", "pivot_feedback_search",
 ]
@@ -62,7 +63,7 @@ class pivot_plan_view(C.Structure):
 class pivot_mlp_view(C.Structure):
     _fields_ = [("L", C.c_int32), ("flags", C.c_int32),
                 ("q", C.POINTER(C.POINTER(C.c_int32))), ("dst", C.POINTER(C.POINTER(C.c_int32))),
-                ("identity", C.POINTER(C.c_int32))]
+                ("identity", C.POINTER(C.c_int32)), ("one_launch", C.c_int32)]
 
 
 _lib = None
@@ -104,6 +105,7 @@ def lib():
     L.pivot_mlp_workspace_bytes.argtypes = [vp, i32]
     L.pivot_mlp_workspace_bytes.restype = sz
     L.pivot_mlp_run.argtypes = [vp, vp, i64, vp, i64, i32, vp, sz, vp]
+    L.pivot_mlp_status.argtypes = [vp, vp, C.POINTER(C.c_int)]
     L.pivot_lstm_workspace_bytes.argtypes = [vp, i32, i32, i32, i32]
     L.pivot_lstm_workspace_bytes.restype = sz
     L.pivot_lstm_run.argtypes = [vp, i32, i32, vp, vp, vp, vp, i32, i32, vp, sz, vp]
@@ -217,7 +219,7 @@ def pivot_mlp_plan_host_view(mlp, layer_views):
         qs.append(np.ctypeslib.as_array(v.q[l], shape=(nq,)).copy())
         dsts.append(np.ctypeslib.as_array(v.dst[l], shape=(nd,)).copy())
         ident.append(int(v.identity[l]))
-    return dict(L=v.L, flags=v.flags, q=qs, dst=dsts, identity=ident)
+    return dict(L=v.L, flags=v.flags, q=qs, dst=dsts, identity=ident, one_launch=int(v.one_launch))
 
 
 def pivot_mlp_plan_destroy(mlp):
@@ -230,6 +232,13 @@ def pivot_mlp_workspace_bytes(mlp, batch):
 
 def pivot_mlp_run(mlp, x_ptr, ldx, y_ptr, ldy, batch, ws_ptr, ws_bytes, stream=None):
     _check(lib().pivot_mlp_run(mlp, x_ptr, ldx, y_ptr, ldy, batch, ws_ptr, ws_bytes, stream))
+
+
+def pivot_mlp_status(mlp, stream=None):
+    """0 if every one-launch run of the chain since the last call completed (synchronises the stream)."""
+    st = C.c_int(0)
+    _check(lib().pivot_mlp_status(mlp, stream, C.byref(st)))
+    return int(st.value)
 
 
 def pivot_lstm_workspace_bytes(plan, H, I, steps, batch):

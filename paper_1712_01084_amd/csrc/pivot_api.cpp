@@ -258,7 +258,7 @@ int pivot_mlp_plan(pivot_fc_plan_t* const* layers, int Lcount, int flags, pivot_
     if (out) *out = nullptr;
     if (!layers || !out) { set_error("layers and out are required"); return PIVOT_E_NULL; }
     if (Lcount < 1) { set_error("a chain needs at least one layer"); return PIVOT_E_SHAPE; }
-    if (flags & ~PIVOT_MLP_KEEP_FINAL_BLOCK_ORDER) { set_error("unknown flags"); return PIVOT_E_UNSUPPORTED; }
+    if (flags & ~(PIVOT_MLP_KEEP_FINAL_BLOCK_ORDER | PIVOT_MLP_LAUNCH_PER_LAYER)) { set_error("unknown flags"); return PIVOT_E_UNSUPPORTED; }
     for (int l = 0; l < Lcount; ++l) {
         if (!layers[l]) { set_error("layer %d is NULL", l); return PIVOT_E_NULL; }
         if (layers[l]->host.d.wdtype != layers[0]->host.d.wdtype || layers[l]->device != layers[0]->device) {
@@ -301,6 +301,16 @@ int pivot_mlp_plan(pivot_fc_plan_t* const* layers, int Lcount, int flags, pivot_
         size_t total = 0;
         for (auto& v : mp->dst) total += align_up(v.size() * 4, 256);
         DeviceGuard g(mp->device);
+        // one-launch form: control words and a buffer of (value, tag) pairs per boundary, zeroed once
+        std::vector<const HostPlan*> hps;
+        for (int l = 0; l < Lcount; ++l) hps.push_back(&layers[l]->host);
+        mp->persist_ok = !(flags & PIVOT_MLP_LAUNCH_PER_LAYER) &&
+                         chain_persist_supported(hps, mp->device, &mp->persist_grid, &mp->persist_smem, nullptr);
+        const size_t persist_off = total;
+        if (mp->persist_ok) {
+            total += align_up(chain_persist_ctl_bytes(), 256);
+            for (int l = 0; l + 1 < Lcount; ++l) total += align_up((size_t)layers[l + 1]->host.K_pad * 8, 256);
+        }
         void* base = nullptr;
         hipError_t e = hipMalloc(&base, total);
         if (e != hipSuccess) { set_error("hipMalloc(%zu) failed: %s", total, hipGetErrorString(e)); delete mp; return PIVOT_E_ALLOC; }
@@ -311,6 +321,17 @@ int pivot_mlp_plan(pivot_fc_plan_t* const* layers, int Lcount, int flags, pivot_
             if (e != hipSuccess) { set_error("hipMemcpy failed: %s", hipGetErrorString(e)); (void)hipFree(base); delete mp; return PIVOT_E_HIP; }
             mp->dst_dev.push_back(reinterpret_cast<int32_t*>(mp->dev_base + off));
             off += align_up(v.size() * 4, 256);
+        }
+        if (mp->persist_ok) {
+            e = hipMemset(mp->dev_base + persist_off, 0, total - persist_off);
+            if (e != hipSuccess) { set_error("hipMemset failed: %s", hipGetErrorString(e)); (void)hipFree(base); delete mp; return PIVOT_E_HIP; }
+            off = persist_off;
+            mp->persist_ctl = reinterpret_cast<uint32_t*>(mp->dev_base + off);
+            off += align_up(chain_persist_ctl_bytes(), 256);
+            for (int l = 0; l + 1 < Lcount; ++l) {
+                mp->persist_pairs.push_back(reinterpret_cast<unsigned long long*>(mp->dev_base + off));
+                off += align_up((size_t)layers[l + 1]->host.K_pad * 8, 256);
+            }
         }
     }
     *out = mp;
@@ -324,6 +345,7 @@ int pivot_mlp_plan_host_view(const pivot_mlp_plan_t* plan, pivot_mlp_view* v) {
     v->q = plan->q_ptrs.data();
     v->dst = plan->dst_ptrs.data();
     v->identity = plan->identity.data();
+    v->one_launch = plan->persist_ok ? 1 : 0;
     return PIVOT_OK;
 }
 
@@ -340,15 +362,21 @@ void pivot_mlp_plan_destroy(pivot_mlp_plan_t* plan) {
 
 namespace {
 
-// Workspace of a chain: [layer scratch (largest)] [block-order copy of x (matrix path)] [intermediate 0] ...
+// Workspace of a chain: [scratch of layer 0] [scratch of layer 1] ... [block-order copy of x (matrix path)]
+// [intermediate 0] ...  Every layer has its own scratch: the arrival counters of split block rows rely on being
+// zero between launches, so no other layer's partial sums may land on them.
 // Intermediate l holds batch rows of K_pad_{l+1} elements of wdtype in the
 // consumer's block order; its padding columns stay zero from pivot_workspace_init.
-struct MlpLayout { size_t scratch, gather_off, total; std::vector<size_t> inter_off; };
+struct MlpLayout { size_t scratch, gather_off, total; std::vector<size_t> inter_off, scratch_off, scratch_len; };
 
 MlpLayout mlp_layout(const pivot_mlp_plan_t* mp, int batch) {
-    MlpLayout m{0, 0, 0, {}};
-    for (auto* l : mp->layers) m.scratch = std::max(m.scratch, fc_workspace_bytes(l->host, batch));
-    m.scratch = align_up(m.scratch, 256);
+    MlpLayout m{0, 0, 0, {}, {}, {}};
+    for (auto* l : mp->layers) {
+        const size_t len = align_up(fc_workspace_bytes(l->host, batch), 256);
+        m.scratch_off.push_back(m.scratch);
+        m.scratch_len.push_back(len);
+        m.scratch += len;
+    }
     m.gather_off = m.scratch;
     m.scratch += fc_gather_bytes(mp->layers[0]->host, batch);
     size_t off = m.scratch;
@@ -382,10 +410,32 @@ int pivot_mlp_run(const pivot_mlp_plan_t* plan, const void* x_dev, int64_t ldx, 
     const pivot_fc_plan_t* last = plan->layers[Lc - 1];
     if (ldx < plan->layers[0]->host.d.K || ldy < (keep ? last->host.M_pad : last->host.d.M)) { set_error("ldx/ldy too small"); return PIVOT_E_SHAPE; }
     char* ws = reinterpret_cast<char*>(ws_dev);
+    if (batch == 1 && plan->persist_ok) {
+        // the whole chain in one launch; intermediates are the plan's own (value, tag) pairs
+        ChainPersistLaunch C;
+        C.ctl = plan->persist_ctl; C.grid = plan->persist_grid; C.smem = plan->persist_smem;
+        C.bw = plan->layers[0]->host.d.bw; C.stream = stream;
+        for (int l = 0; l < Lc; ++l) {
+            const pivot_fc_plan_t* p = plan->layers[l];
+            ChainPersistLayer s{};
+            s.hp = &p->host; s.vals = p->dev.vals; s.chunks = p->dev.chunks; s.bias_p = p->dev.bias_p;
+            s.xidx = l == 0 ? p->dev.xidx : p->dev.xidx_blk;
+            s.in = l == 0 ? x_dev : static_cast<const void*>(plan->persist_pairs[l - 1]);
+            if (l + 1 < Lc) {
+                s.dst = plan->identity[l] ? p->dev.rowid_pad : plan->dst_dev[l];
+                s.out = plan->persist_pairs[l];
+            } else {
+                s.dst = keep ? p->dev.rowid_pad : p->dev.prow_pad;
+                s.out = y_dev;
+            }
+            C.layers.push_back(s);
+        }
+        return launch_chain_persist(C);
+    }
     for (int l = 0; l < Lc; ++l) {
         const pivot_fc_plan_t* p = plan->layers[l];
         FcLaunch L{};
-        int rc = prepare(p, batch, ws, m.gather_off, L);
+        int rc = prepare(p, batch, ws + m.scratch_off[l], m.scratch_len[l], L);
         if (rc != PIVOT_OK) return rc;
         L.stream = stream;
         if (l == 0) {
@@ -407,6 +457,20 @@ int pivot_mlp_run(const pivot_mlp_plan_t* plan, const void* x_dev, int64_t ldx, 
         rc = launch_fc(L);
         if (rc != PIVOT_OK) return rc;
     }
+    return PIVOT_OK;
+}
+
+int pivot_mlp_status(const pivot_mlp_plan_t* plan, void* stream, int* status) {
+    if (!plan || !status) { set_error("plan and status are required"); return PIVOT_E_NULL; }
+    *status = 0;
+    if (!plan->persist_ok) return PIVOT_OK;
+    DeviceGuard g(plan->device);
+    API_HIP(hipStreamSynchronize(reinterpret_cast<hipStream_t>(stream)), (void)0);
+    char* word = reinterpret_cast<char*>(plan->persist_ctl) + chain_persist_status_offset();
+    uint32_t st = 0;
+    API_HIP(hipMemcpy(&st, word, 4, hipMemcpyDeviceToHost), (void)0);
+    if (st != 0) API_HIP(hipMemset(word, 0, 4), (void)0);
+    *status = (int)st;
     return PIVOT_OK;
 }
 

@@ -267,11 +267,10 @@ struct XStage<WT, BW, 1, NT> {
 // A thread holds up to XN vectors; the launcher only picks this variant when
 // NB rows of x fit (NB * xn_vecs <= XN * NT) and rows are 16-byte aligned.
 // Slots past the end load vector 0 again and are written to a dump vector.
-template <typename WT, int NB, int NT>
+template <typename WT, int NB, int NT, int XN = 8>
 struct XRes {
     using V = typename Elem<WT>::vec;
     static constexpr int VEC = Elem<WT>::VEC;
-    static constexpr int XN = 8;
     V v[XN];
     __device__ __forceinline__ void load(int batch, long long ldx, int xn_vecs, const void* x, int b0, int tid) {
         const int total = NB * xn_vecs;
@@ -387,7 +386,9 @@ __device__ __forceinline__ void finish_rows(const FcArgs& a, const float* red, i
 // covers RPW rows per load.
 // ---------------------------------------------------------------------------
 // XR: 0 = gather from global x; 1 = gather from an LDS copy of x; 2 = the same for irregular schedules, with
-// the copy requested before the work item's descriptor has arrived (it depends on nothing).
+// the copy requested before the work item's descriptor has arrived (it depends on nothing); 3 = as 2 with up
+// to 16 vectors of x per thread (long inputs, LDS beyond 64 KB: a gather of single elements from a long x
+// moves a whole cache line per element, the copy moves every line once).
 template <typename WT, int BH, int BW, int NB, int NW, int XR>
 __global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(PIVOT_GEMV_PARAMS, FcArgs a) {
     using V = typename Elem<WT>::vec;
@@ -419,8 +420,8 @@ __global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(PIVOT_GEMV_PARAMS, FcA
     // row length), so that the copy can be requested without waiting for the rest of the argument block
     const long long q_ldx = (NB == 1) ? 0 : (XR != 0) ? (long long)q_xn_vecs * VEC : a.ldx;
     // order of issue = order of arrival: (x,) gather indices, then the weights, then the epilogue operands
-    XRes<WT, NB, NT> xres;
-    if constexpr (XR == 2) xres.load(q_batch, q_ldx, q_xn_vecs, p_x, b0, tid);
+    XRes<WT, NB, NT, (XR == 3) ? 16 : 8> xres;
+    if constexpr (XR >= 2) xres.load(q_batch, q_ldx, q_xn_vecs, p_x, b0, tid);
     const Chunk ck = load_chunk(q_uniform_ct, q_uniform_parts, p_chunks, a.part_base);
     const int br = ck.br, tile_begin = ck.tile_begin, ntiles = ck.ntiles, slot = ck.slot;
     const int first = ck.first, nparts = ck.nparts;

@@ -5,9 +5,19 @@ namespace pivot {
 
 template <int BH, int BW, int NB, int XR>
 static int launch_t(const FcArgs& a, int nw, dim3 grid, size_t smem, hipStream_t st) {
-    if (nw == 16)     hipLaunchKernelGGL((fc_gemv_kernel<float, BH, BW, NB, 16, XR>), grid, dim3(16 * 64), smem, st, PIVOT_GEMV_ARGS(a), a);
-    else if (nw == 8) hipLaunchKernelGGL((fc_gemv_kernel<float, BH, BW, NB, 8, XR>), grid, dim3(8 * 64), smem, st, PIVOT_GEMV_ARGS(a), a);
-    else              hipLaunchKernelGGL((fc_gemv_kernel<float, BH, BW, NB, 4, XR>), grid, dim3(4 * 64), smem, st, PIVOT_GEMV_ARGS(a), a);
+    if constexpr (XR == 3) {
+        // more than 64 KB of dynamic LDS per workgroup has to be allowed per kernel
+        static size_t allowed = 64 * 1024;
+        if (smem > allowed) {
+            HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&fc_gemv_kernel<float, BH, BW, NB, 8, XR>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+            allowed = smem;
+        }
+        hipLaunchKernelGGL((fc_gemv_kernel<float, BH, BW, NB, 8, XR>), grid, dim3(8 * 64), smem, st, PIVOT_GEMV_ARGS(a), a);
+    }
+    else if (nw == 16) hipLaunchKernelGGL((fc_gemv_kernel<float, BH, BW, NB, 16, XR>), grid, dim3(16 * 64), smem, st, PIVOT_GEMV_ARGS(a), a);
+    else if (nw == 8)  hipLaunchKernelGGL((fc_gemv_kernel<float, BH, BW, NB, 8, XR>), grid, dim3(8 * 64), smem, st, PIVOT_GEMV_ARGS(a), a);
+    else               hipLaunchKernelGGL((fc_gemv_kernel<float, BH, BW, NB, 4, XR>), grid, dim3(4 * 64), smem, st, PIVOT_GEMV_ARGS(a), a);
     HIP_TRY(hipGetLastError());
     return PIVOT_OK;
 }
@@ -15,7 +25,7 @@ static int launch_t(const FcArgs& a, int nw, dim3 grid, size_t smem, hipStream_t
 template <int BH, int BW>
 static int launch_nb(const FcArgs& a, int nb, int nw, int xres, dim3 grid, size_t smem, hipStream_t st) {
     switch (nb) {
-        case 1: return xres == 2 ? launch_t<BH, BW, 1, 2>(a, nw, grid, smem, st) : (xres ? launch_t<BH, BW, 1, 1>(a, nw, grid, smem, st) : launch_t<BH, BW, 1, 0>(a, nw, grid, smem, st));
+        case 1: return xres == 3 ? launch_t<BH, BW, 1, 3>(a, nw, grid, smem, st) : xres == 2 ? launch_t<BH, BW, 1, 2>(a, nw, grid, smem, st) : (xres ? launch_t<BH, BW, 1, 1>(a, nw, grid, smem, st) : launch_t<BH, BW, 1, 0>(a, nw, grid, smem, st));
         case 2: return xres == 2 ? launch_t<BH, BW, 2, 2>(a, nw, grid, smem, st) : (xres ? launch_t<BH, BW, 2, 1>(a, nw, grid, smem, st) : launch_t<BH, BW, 2, 0>(a, nw, grid, smem, st));
         default: return xres == 2 ? launch_t<BH, BW, 4, 2>(a, nw, grid, smem, st) : (xres ? launch_t<BH, BW, 4, 1>(a, nw, grid, smem, st) : launch_t<BH, BW, 4, 0>(a, nw, grid, smem, st));
     }

@@ -152,6 +152,24 @@ size_t lstm_persist_partial_bytes(const HostPlan& hp, int batch);
 constexpr size_t kLstmCtlBytes = 2048;
 int    launch_lstm_persist(const LstmPersistLaunch& P);
 
+// A chain of layers in one launch (fp32 BRC plans with whole block rows per work item, batch 1).
+struct ChainPersistLayer {
+    const HostPlan* hp;
+    const void* vals; const int32_t* chunks; const int32_t* xidx; const float* bias_p; const int32_t* dst;
+    const void* in; void* out;
+};
+struct ChainPersistLaunch {
+    std::vector<ChainPersistLayer> layers;
+    uint32_t* ctl;                     // chain_persist_ctl_bytes, zeroed once when the chain plan is made
+    int grid, bw; size_t smem;
+    void* stream;
+};
+bool   chain_persist_supported(const std::vector<const HostPlan*>& layers, int device, int* grid_out, size_t* smem_out,
+                               std::string* why);
+size_t chain_persist_ctl_bytes();
+int    chain_persist_status_offset();  // byte offset of the status word inside the control block
+int    launch_chain_persist(const ChainPersistLaunch& C);
+
 }  // namespace pivot
 
 struct pivot_fc_plan {
@@ -170,4 +188,10 @@ struct pivot_mlp_plan {
     char* dev_base = nullptr;
     std::vector<int32_t*> dst_dev;
     int device = -1;
+    // one-launch form: control words and one buffer of (value, tag) pairs per boundary, in dev_base
+    bool persist_ok = false;
+    int persist_grid = 0;
+    size_t persist_smem = 0;
+    uint32_t* persist_ctl = nullptr;
+    std::vector<unsigned long long*> persist_pairs;
 };

@@ -4,6 +4,17 @@
 
 namespace pivot {
 
+// Compute units of the current device (asked once).
+static int device_cus() {
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) cus = n;
+        else { (void)hipGetLastError(); cus = 1; }
+    }
+    return cus;
+}
+
 static int mfma_kind(int wdtype, int bh, int bw) {
     if (wdtype != PIVOT_F16) return -1;
     if (bw % 32 == 0 && bh % 16 == 0) return 0;
@@ -144,14 +155,27 @@ int launch_fc(const FcLaunch& L) {
     size_t xn_bytes = 0;
     const size_t item_bytes = (size_t)(a.uniform_ct > 0 ? a.uniform_ct : L.chunk_tiles) * bhs * L.bw * es;
     if (L.layout == PIVOT_BRC && L.x_resident != 0 && (L.x_resident == 2 || item_bytes >= 48 * 1024) && xlen % vec == 0 && (nbt == 1 || L.ldx == xlen) &&
-        (reinterpret_cast<uintptr_t>(L.x) & 15) == 0 && (size_t)nbt * (xlen / vec) <= (size_t)8 * nw * 64) {
+        (reinterpret_cast<uintptr_t>(L.x) & 15) == 0) {
+        const size_t vectors = (size_t)nbt * (xlen / vec);
         xn_bytes = (size_t)nbt * xlen * es + 16;
-        if (xn_bytes + xs_bytes <= 64 * 1024 && red_bytes <= 64 * 1024) xres = a.uniform_ct > 0 ? 1 : 2;
+        if (vectors <= (size_t)8 * nw * 64 && xn_bytes + xs_bytes <= 64 * 1024 && red_bytes <= 64 * 1024) {
+            xres = a.uniform_ct > 0 ? 1 : 2;
+        } else if (!ml && nbt == 1 && vectors <= (size_t)16 * 8 * 64 && xn_bytes + xs_bytes <= 144 * 1024 &&
+                   (size_t)L.nchunks * sl <= (size_t)device_cus()) {
+            // Long x (beyond 64 KB of LDS or 8 vectors per thread): 8 wavefronts hold up to 16 vectors each and
+            // the workgroup takes most of the 160 KB of a compute unit, so this form is only used when every
+            // work item still gets a compute unit of its own.  It replaces a gather that moves a whole cache
+            // line per element by a copy that moves every line once (25088 inputs, 78 tiles per work item:
+            // 320 KB of lines per work item against 100 KB).
+            xres = 3;
+            nw = 8;
+            red_bytes = (size_t)nw * bhs * nbt * 4;
+        }
     }
     a.xn_vecs = xres ? xlen / vec : 0; a.xn_stride = xlen;
     size_t smem = xres ? xn_bytes + xs_bytes : xs_bytes;
     smem = align_up(smem > red_bytes ? smem : red_bytes, 16);
-    if (smem > 64 * 1024) { set_error("chunk does not fit in LDS (%zu bytes)", smem); return PIVOT_E_UNSUPPORTED; }
+    if (smem > (size_t)(xres == 3 ? 150 : 64) * 1024) { set_error("chunk does not fit in LDS (%zu bytes)", smem); return PIVOT_E_UNSUPPORTED; }
     if (L.layout != PIVOT_BRC) return launch_colmajor(a, L.layout, L.wdtype, L.bh, L.bw, nw, grid, smem, st);
     if (ml) return launch_mfma_lds_f16(a, mfma_kind(L.wdtype, L.bh, L.bw), bhs, L.bw, nbt, nw, xres, grid, smem, st);
     if (L.wdtype == PIVOT_F32) return launch_gemv_f32(a, bhs, L.bw, nbt, nw, xres, grid, smem, st);

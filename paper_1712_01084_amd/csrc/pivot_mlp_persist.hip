@@ -1,0 +1,381 @@
+// A chain of pruned layers in ONE launch (Section 4.2: consecutive PBP layers
+// whose boundary permutations are composed or eliminated).  With a launch per
+// layer every boundary costs an empty-kernel turnaround plus a cold first trip
+// to memory for the next layer's indices and weights.  Here workgroup g runs
+// work item g of layer 0, then work item g of layer 1, and so on; the layers
+// are ordered by the data itself: an intermediate activation is stored as the
+// 8-byte pair (value, tag) with one device-coherent store, and the gather of
+// the next layer re-reads the pairs it needs until all carry this launch's
+// tag.  A workgroup requests the next layer's gather indices and weights
+// before it starts waiting, so they arrive while the boundary is in flight.
+//
+// The tag is a launch counter kept per workgroup in device memory owned by
+// the chain plan (word g is read and bumped by workgroup g alone, so every
+// launch, also a replayed graph node, sees a value no earlier launch used);
+// the pair buffers are owned by the plan too, hence launches of one chain plan
+// must not overlap.  No fences, no atomics on floats, fixed summation order:
+// results are bit-identical from run to run.  All workgroups must be resident
+// at once (checked at plan time); every wait is bounded: after kSpinLimit
+// polls it raises the status word, the wait ends, and the results of that
+// launch are undefined.
+//
+// The per-layer body is the batch-1 vector kernel: 16-byte coalesced stream of
+// BRC tile rows, x-segments staged in LDS, DPP lane reduction, LDS wave
+// reduction, bias, activation, store through the composed boundary array.
+// Restricted to fp32 BRC plans with whole block rows per work item.
+#include "pivot_fc_kernels.h"
+
+namespace pivot {
+
+namespace {
+
+constexpr int kMaxChainLayers = 8;
+constexpr int kChainNW = 8;                     // wavefronts per workgroup
+constexpr int kChainMaxGrid = 1024;             // launch-counter words
+constexpr int kChainStatus = 1024;              // index of the status word
+constexpr uint32_t kChainSpinLimit = 1u << 18;
+
+struct ChainLayer {
+    const int4*    chunks;      // eight ints per chunk (irregular schedules)
+    const int32_t* xidx;        // gather index of every kept tile's columns
+    const float*   vals;
+    const float*   bias_p;
+    const int32_t* dst;         // block-space row -> position in `out`, -1 = not stored
+    const void*    in;          // layer 0: float x in natural order; later layers: pairs in this layer's block order
+    void*          out;         // pairs in the next layer's block order; last layer: float y
+    int nitems, slices, bhs, bh_full, uniform_ct, uniform_parts, chunk_tiles, act, k_valid;
+};
+
+struct ChainArgs {
+    ChainLayer L[kMaxChainLayers];
+    uint32_t*  ctl;             // [0, kChainMaxGrid): launch counter of every workgroup; [kChainStatus]: status
+    int        nlayers;
+};
+
+__device__ __forceinline__ unsigned long long cld64(const unsigned long long* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void cst64(unsigned long long* p, unsigned long long v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint32_t cld32(const uint32_t* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void cst32(uint32_t* p, uint32_t v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// A poll that did not succeed: pause; every 64th time look at the status word,
+// and give up (raising it) at the limit.  Returns false when the wait must end.
+__device__ __forceinline__ bool chain_keep_waiting(uint32_t* ctl, uint32_t& spins) {
+    __builtin_amdgcn_s_sleep(4);
+    if ((++spins & 63u) != 0u) return true;
+    if (cld32(ctl + kChainStatus) != 0u) return false;
+    if (spins >= kChainSpinLimit) { cst32(ctl + kChainStatus, 1u); return false; }
+    return true;
+}
+
+// One work item of one layer (see fc_gemv_kernel for the streaming scheme).
+// No thread leaves early: every barrier is reached by the whole workgroup.
+// IN_TAGGED is a compile-time switch: a run-time branch around the gather loads would make the compiler wait for
+// every outstanding weight load before it issues them.  The first layer (plain x, usually the long one) fetches
+// eight gather indices per thread up front, so that up to 4096 staged elements need one round of dependent loads.
+template <int BH, int BW, int NW, bool IN_TAGGED>
+__device__ __forceinline__ void chain_item(const ChainLayer& P, int item, bool out_tagged,
+                                           uint32_t tag, uint32_t counter, uint32_t* s_tag, uint32_t* ctl, char* smem) {
+    using V = f32x4;
+    constexpr int VEC = 4;
+    constexpr int NT  = NW * 64;
+    constexpr int LPR = BW / VEC;
+    constexpr int RPW = 64 / LPR;
+    constexpr int NL  = (BH >= RPW) ? BH / RPW : 1;
+    constexpr int TPL = (BH >= RPW) ? 1 : RPW / BH;
+    constexpr int U   = (NL >= 8) ? 1 : 8 / NL;
+    constexpr int XP  = IN_TAGGED ? 4 : 8;
+    static_assert(BH <= NT, "one thread per output row");
+
+    float* xs  = reinterpret_cast<float*>(smem);
+    float* red = reinterpret_cast<float*>(smem);        // reused after the stream phase
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int chunk = item / P.slices, slice = item - chunk * P.slices;
+    int br, tile_begin, ntiles;
+    if (P.uniform_ct > 0) {
+        br = chunk / P.uniform_parts; tile_begin = chunk * P.uniform_ct; ntiles = P.uniform_ct;
+    } else {
+        const int4 cd = P.chunks[2 * chunk];
+        br = cd.x; tile_begin = cd.y; ntiles = cd.z - cd.y;
+    }
+    const int ne = ntiles * BW, emax = ne > 0 ? ne - 1 : 0;
+    const int dump = P.chunk_tiles * BW + VEC - 1;      // LDS row: chunk_tiles*BW staged elements + 16 bytes
+    const int32_t* xi = P.xidx + (size_t)tile_begin * BW;
+    int src[XP];
+    #pragma unroll
+    for (int k = 0; k < XP; ++k) {
+        const int e = tid + k * NT;
+        src[k] = xi[e < emax ? e : emax];
+    }
+
+    const int ngroups = (ntiles + TPL - 1) / TPL;
+    const int gmax = ngroups > 0 ? ngroups - 1 : 0;
+    const int tile_elems = P.bh_full * BW;
+    const int s  = lane / LPR, cg = lane % LPR;
+    const int ts = (TPL > 1) ? s / BH : 0;
+    const size_t gstride = (size_t)TPL * tile_elems;
+    const float* vbase = P.vals + (size_t)tile_begin * tile_elems + (size_t)slice * BH * BW + lane * VEC;
+    V w[U][NL];
+    #pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int g = wave + u * NW;
+        const int gc = g < gmax ? g : gmax;
+        #pragma unroll
+        for (int j = 0; j < NL; ++j) w[u][j] = load16<V>(vbase + gc * gstride + j * 64 * VEC);
+    }
+    const int orow = br * P.bh_full + slice * BH + tid % BH;
+    const float bias = P.bias_p[orow];
+    const int   dst  = P.dst[orow];
+    __builtin_amdgcn_sched_barrier(0);                  // every load above is issued before anything below waits
+
+    // stage the x-segments: plain loads from the caller's x, or pairs re-read until they carry this launch's tag.
+    // The first round stands outside the loop so that no loop header sits between its loads and the ones above.
+    auto stage = [&](int e0) {
+        if constexpr (!IN_TAGGED) {
+            const float* x = reinterpret_cast<const float*>(P.in);
+            float v[XP];
+            #pragma unroll
+            for (int k = 0; k < XP; ++k) v[k] = x[src[k] > 0 ? src[k] : 0];
+            #pragma unroll
+            for (int k = 0; k < XP; ++k) {
+                const int e = e0 + k * NT;
+                xs[e < ne ? e : dump] = (src[k] >= 0) ? v[k] : 0.f;
+            }
+        } else {
+            const unsigned long long* xp = reinterpret_cast<const unsigned long long*>(P.in);
+            unsigned long long pv[XP];
+            uint32_t spins = 0;
+            for (;;) {
+                #pragma unroll
+                for (int k = 0; k < XP; ++k) pv[k] = cld64(xp + ((src[k] > 0 && src[k] < P.k_valid) ? src[k] : 0));
+                bool ok = true;
+                #pragma unroll
+                for (int k = 0; k < XP; ++k) {
+                    const int e = e0 + k * NT;
+                    const bool needed = e < ne && src[k] >= 0 && src[k] < P.k_valid;
+                    ok = ok && (!needed || (uint32_t)(pv[k] >> 32) == tag);
+                }
+                if (ok) break;
+                if (!chain_keep_waiting(ctl, spins)) break;
+            }
+            #pragma unroll
+            for (int k = 0; k < XP; ++k) {
+                const int e = e0 + k * NT;
+                const bool real = src[k] >= 0 && src[k] < P.k_valid;    // padding columns read as zero
+                xs[e < ne ? e : dump] = real ? __uint_as_float((uint32_t)pv[k]) : 0.f;
+            }
+        }
+    };
+    stage(tid);
+    for (int r = XP * NT; r < ne; r += XP * NT) {       // longer work items: further rounds (uniform trip count)
+        #pragma unroll
+        for (int k = 0; k < XP; ++k) {
+            const int e = tid + r + k * NT;
+            src[k] = xi[e < emax ? e : emax];
+        }
+        stage(tid + r);
+    }
+    lds_barrier();
+
+    float acc[NL];
+    #pragma unroll
+    for (int j = 0; j < NL; ++j) acc[j] = 0.f;
+    auto consume = [&](int u, int g) {
+        const int tl = g * TPL + ts;
+        const V xv = *reinterpret_cast<const V*>(xs + tl * BW + cg * VEC);
+        #pragma unroll
+        for (int j = 0; j < NL; ++j) acc[j] = dot_vec(w[u][j], xv, acc[j]);
+    };
+    int g0 = wave;
+    for (; g0 + NW * U < ngroups; g0 += NW * U) {
+        #pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int g = g0 + u * NW;
+            consume(u, g);
+            const int gn = g + NW * U;
+            const int gc = gn < gmax ? gn : gmax;
+            #pragma unroll
+            for (int j = 0; j < NL; ++j) w[u][j] = load16<V>(vbase + gc * gstride + j * 64 * VEC);
+        }
+    }
+    #pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int g = g0 + u * NW;
+        if (g < ngroups && g * TPL + ts < ntiles) consume(u, g);
+    }
+    #pragma unroll
+    for (int j = 0; j < NL; ++j) {
+        float v = group_sum<LPR>(acc[j]);
+        if constexpr (TPL > 1) v = stride_sum<BH * LPR>(v);
+        acc[j] = v;
+    }
+    __syncthreads();                                    // xs no longer needed; red aliases it
+    if (cg == 0 && (TPL == 1 || s < BH)) {
+        #pragma unroll
+        for (int j = 0; j < NL; ++j) {
+            const int r = (TPL > 1) ? s : j * RPW + s;
+            red[wave * BH + r] = acc[j];
+        }
+    }
+    // a workgroup whose first layer is layer 0 learns its tag here: thread 0's load of the launch counter,
+    // requested at kernel start, has long arrived and rides on this barrier to the other threads
+    if (s_tag && tid == 0) *s_tag = counter + 1u;
+    __syncthreads();
+    if (s_tag) tag = *s_tag;
+    if (tid < BH) {
+        float sum = 0.f;
+        #pragma unroll
+        for (int wv = 0; wv < NW; ++wv) sum += red[wv * BH + tid];
+        const float v = apply_act(sum + bias, P.act);
+        if (dst >= 0) {
+            if (out_tagged)
+                cst64(reinterpret_cast<unsigned long long*>(P.out) + dst,
+                      ((unsigned long long)tag << 32) | (unsigned long long)__float_as_uint(v));
+            else
+                reinterpret_cast<float*>(P.out)[dst] = v;
+        }
+    }
+    __syncthreads();                                    // the next layer's staging reuses the LDS
+}
+
+template <int BW>
+__global__ void __launch_bounds__(kChainNW * 64) mlp_persist_kernel(ChainArgs A) {
+    extern __shared__ __align__(16) char smem[];
+    __shared__ uint32_t s_tag;
+    const int wg = blockIdx.x;
+    // This launch's tag = the workgroup's own launch counter + 1.  Thread 0 requests the counter now; nothing
+    // waits for it until the workgroup first needs the tag (layer 0: at its store; a workgroup that starts with
+    // a later layer: before its first poll, where it would be waiting anyway).
+    uint32_t counter = 0;
+    if (threadIdx.x == 0) counter = cld32(A.ctl + wg);
+    uint32_t tag = 0;
+    bool have_tag = false;
+    for (int l = 0; l < A.nlayers; ++l) {
+        const ChainLayer& P = A.L[l];
+        if (wg >= P.nitems) continue;                   // uniform over the workgroup
+        const bool in_tagged = l > 0, out_tagged = l + 1 < A.nlayers;
+        if (!have_tag && in_tagged) {
+            if (threadIdx.x == 0) s_tag = counter + 1u;
+            __syncthreads();
+            tag = s_tag;
+            have_tag = true;
+            if (threadIdx.x == 0) cst32(A.ctl + wg, tag);   // bumped by its only reader: no other workgroup touches it
+        }
+        uint32_t* st = have_tag ? nullptr : &s_tag;
+        if (in_tagged) {
+            switch (P.bhs) {
+                case 8:  chain_item<8,  BW, kChainNW, true>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
+                case 16: chain_item<16, BW, kChainNW, true>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
+                case 32: chain_item<32, BW, kChainNW, true>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
+                default: chain_item<64, BW, kChainNW, true>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
+            }
+        } else {
+            switch (P.bhs) {
+                case 8:  chain_item<8,  BW, kChainNW, false>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
+                case 16: chain_item<16, BW, kChainNW, false>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
+                case 32: chain_item<32, BW, kChainNW, false>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
+                default: chain_item<64, BW, kChainNW, false>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
+            }
+        }
+        if (!have_tag) {                                // s_tag was set inside the item, before its last barriers
+            tag = s_tag;
+            have_tag = true;
+            if (threadIdx.x == 0) cst32(A.ctl + wg, tag);
+        }
+    }
+}
+
+const void* chain_kernel_for(int bw) {
+    switch (bw) {
+        case 16: return reinterpret_cast<const void*>(&mlp_persist_kernel<16>);
+        case 32: return reinterpret_cast<const void*>(&mlp_persist_kernel<32>);
+        case 64: return reinterpret_cast<const void*>(&mlp_persist_kernel<64>);
+        default: return nullptr;
+    }
+}
+
+// Row slices of a layer inside the chain kernel: the plan's own choice, lowered until a slice holds at least
+// one 1 KB wave-load and 8 rows (the same rule as the layer kernel's).
+int chain_slices(const HostPlan& hp) {
+    return fc_row_slices(hp.d.layout, hp.d.wdtype, hp.d.bh, hp.d.bw, hp.chunk_tiles, 1, hp.row_slices);
+}
+
+}  // namespace
+
+size_t chain_persist_ctl_bytes() { return (size_t)(kChainStatus + 64) * 4; }
+
+bool chain_persist_supported(const std::vector<const HostPlan*>& layers, int device, int* grid_out, size_t* smem_out,
+                             std::string* why) {
+    auto no = [&](const char* m) { if (why) *why = m; return false; };
+    const int Lc = (int)layers.size();
+    if (Lc < 2 || Lc > kMaxChainLayers) return no("2..8 layers");
+    const int bw = layers[0]->d.bw;
+    if (!chain_kernel_for(bw)) return no("tile width 16, 32 or 64");
+    int G = 0;
+    size_t smem = 0;
+    for (const HostPlan* hp : layers) {
+        if (hp->d.wdtype != PIVOT_F32 || hp->d.layout != PIVOT_BRC) return no("fp32 BRC plans only");
+        if (hp->d.bw != bw) return no("one tile width for all layers");
+        if (hp->max_parts > 1) return no("whole block rows per work item only");
+        const int sl = chain_slices(*hp);
+        const int bhs = hp->d.bh / sl;
+        if (bhs != 8 && bhs != 16 && bhs != 32 && bhs != 64) return no("row slices of 8, 16, 32 or 64 rows");
+        if (bw / 4 > 64 || hp->d.bh > 64) return no("tile shape");
+        const long long items = (long long)hp->nchunks * sl;
+        if (items > kChainMaxGrid) return no("more work items than the one-launch form takes");
+        G = std::max(G, (int)items);
+        const int ct = hp->uniform_ct > 0 ? hp->uniform_ct : hp->chunk_tiles;
+        smem = std::max(smem, ((size_t)ct * bw + 4) * 4);
+        smem = std::max(smem, (size_t)kChainNW * bhs * 4);
+    }
+    smem = align_up(smem, 16);
+    if (smem > 64 * 1024) return no("staged x does not fit in LDS");
+    if (device >= 0) {
+        int per_cu = 0, cus = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, chain_kernel_for(bw), kChainNW * 64, smem) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess) {
+            (void)hipGetLastError();
+            return no("occupancy query failed");
+        }
+        if ((long long)per_cu * cus < G) return no("the work items of a layer are not all resident at once");
+    }
+    if (grid_out) *grid_out = G;
+    if (smem_out) *smem_out = smem;
+    return true;
+}
+
+int launch_chain_persist(const ChainPersistLaunch& C) {
+    ChainArgs A{};
+    const int Lc = (int)C.layers.size();
+    A.nlayers = Lc;
+    A.ctl = C.ctl;
+    for (int l = 0; l < Lc; ++l) {
+        const ChainPersistLayer& s = C.layers[l];
+        const HostPlan& hp = *s.hp;
+        ChainLayer& P = A.L[l];
+        const int sl = chain_slices(hp);
+        P.chunks = reinterpret_cast<const int4*>(s.chunks);
+        P.xidx = s.xidx; P.vals = reinterpret_cast<const float*>(s.vals); P.bias_p = s.bias_p; P.dst = s.dst;
+        P.in = s.in; P.out = s.out;
+        P.nitems = hp.nchunks * sl; P.slices = sl; P.bhs = hp.d.bh / sl; P.bh_full = hp.d.bh;
+        P.uniform_ct = hp.uniform_ct; P.uniform_parts = hp.uniform_parts;
+        P.chunk_tiles = hp.uniform_ct > 0 ? hp.uniform_ct : hp.chunk_tiles;
+        P.act = hp.d.act; P.k_valid = hp.d.K;
+    }
+    hipStream_t st = reinterpret_cast<hipStream_t>(C.stream);
+    void* args[] = {&A};
+    HIP_TRY(hipLaunchKernel(chain_kernel_for(C.bw), dim3(C.grid), dim3(kChainNW * 64), args, C.smem, st));
+    return PIVOT_OK;
+}
+
+int chain_persist_status_offset() { return kChainStatus * 4; }
+
+}  // namespace pivot

@@ -250,7 +250,7 @@ def config3(seed=0, batch=1, frac=0.10, M=4096, K=4096):
 
 
 def config4(seed=0, batch=1, dims=(25088, 4096, 4096, 1000), eliminated=False,
-            wdtype=F32) -> List[FCProblem]:
+            wdtype=F32, bh=32, bw=32, frac=0.10) -> List[FCProblem]:
     """VGG FC shapes, 32x32 tiles, 10 % kept per layer, balanced, ReLU between
     layers and identity on the logits.  ``eliminated`` makes every layer's
     column index array equal to the previous layer's row index array, the
@@ -263,7 +263,7 @@ def config4(seed=0, batch=1, dims=(25088, 4096, 4096, 1000), eliminated=False,
     for l in range(L):
         K, M = dims[l], dims[l + 1]
         pcol = prev_prow if (eliminated and prev_prow is not None) else None
-        p = gen_fc(M, K, 32, 32, 0.10, seed, mask="balanced", wdtype=wdtype,
+        p = gen_fc(M, K, bh, bw, frac, seed, mask="balanced", wdtype=wdtype,
                    batch=batch, act=(ACT_RELU if l < L - 1 else ACT_NONE),
                    x_kind="relu_normal", pcol=pcol, rng=rng, draw_x=(l == 0),
                    name="cfg4_L%d_%dx%d" % (l + 1, M, K))

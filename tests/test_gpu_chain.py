@@ -18,10 +18,13 @@ def _layers(probs):
             for p in probs]
 
 
-def _run_chain(probs, flags=0, chunk_tiles=0, repeats=2):
+def _run_chain(probs, flags=0, chunk_tiles=0, repeats=2, want_one_launch=None):
     plans = [G.dev_plan(p, chunk_tiles=chunk_tiles) for p in probs]
     mlp = B.pivot_mlp_plan(plans, flags)
     try:
+        view = B.pivot_mlp_plan_host_view(mlp, [B.pivot_fc_plan_host_view(h) for h in plans])
+        if want_one_launch is not None:
+            assert view["one_launch"] == int(want_one_launch)
         x = probs[0].x
         batch = x.shape[0]
         xd = torch.from_numpy(x).cuda()
@@ -37,6 +40,7 @@ def _run_chain(probs, flags=0, chunk_tiles=0, repeats=2):
             torch.cuda.synchronize()
             outs.append(yd.cpu().numpy())
         assert outs[0].tobytes() == outs[-1].tobytes()
+        assert B.pivot_mlp_status(mlp, st) == 0
         y = outs[0].astype(np.float64)
         if keep:                                   # host relabels with prow of the last layer (Section 4.2.2)
             nat = np.empty((batch, last.M))
@@ -49,8 +53,8 @@ def _run_chain(probs, flags=0, chunk_tiles=0, repeats=2):
             B.pivot_fc_plan_destroy(h)
 
 
-def _check_chain(probs, flags=0, chunk_tiles=0):
-    y = _run_chain(probs, flags=flags, chunk_tiles=chunk_tiles)
+def _check_chain(probs, flags=0, chunk_tiles=0, want_one_launch=None, repeats=2):
+    y = _run_chain(probs, flags=flags, chunk_tiles=chunk_tiles, want_one_launch=want_one_launch, repeats=repeats)
     bd = np.float16 if probs[0].wdtype == WL.F16 else None
     outs, scales, chain = O.oracle_mlp(_layers(probs), probs[0].x, boundary_dtype=bd, return_all=True)
     assert not np.isnan(y).any()
@@ -81,8 +85,35 @@ def test_fp16_chain_batch16_uses_matrix_cores():
 @pytest.mark.parametrize("eliminated", [False, True])
 def test_config4_full(eliminated):
     probs = WL.config4(seed=0, eliminated=eliminated)
-    err = _check_chain(probs)
-    print("config4 eliminated=%s scaled error %.3g" % (eliminated, err))
+    err = _check_chain(probs, want_one_launch=True)
+    print("config4 eliminated=%s one launch: scaled error %.3g" % (eliminated, err))
+    err = _check_chain(probs, flags=B.PIVOT_MLP_LAUNCH_PER_LAYER, want_one_launch=False)
+    print("config4 eliminated=%s launch per layer: scaled error %.3g" % (eliminated, err))
+
+
+@pytest.mark.parametrize("eliminated", [False, True])
+@pytest.mark.parametrize("bh,bw,dims", [(32, 32, (300, 200, 136, 70)), (16, 16, (100, 90, 50)), (8, 64, (260, 72, 40, 24, 130)),
+                                        (64, 16, (150, 190, 64)), (16, 32, (96, 64, 48))])
+def test_one_launch_chain_fp32_batch1(eliminated, bh, bw, dims):
+    # fp32 chains whose work items are whole block rows run at batch 1 in ONE launch: intermediates travel as
+    # (value, launch tag) pairs.  Ragged M and K (padding rows are never stored, padding columns never waited
+    # for), several tile shapes, 2 to 5 layers, both boundary variants, five launches in a row (a tag per launch)
+    probs = WL.config4(seed=21 + bh, dims=dims, eliminated=eliminated, bh=bh, bw=bw, frac=0.4)
+    _check_chain(probs, want_one_launch=True, repeats=5)
+    _check_chain(probs, flags=B.PIVOT_MLP_KEEP_FINAL_BLOCK_ORDER, want_one_launch=True)
+    y1 = _run_chain(probs, want_one_launch=True)
+    y2 = _run_chain(probs, flags=B.PIVOT_MLP_LAUNCH_PER_LAYER, want_one_launch=False)
+    outs, scales, chain = O.oracle_mlp(_layers(probs), probs[0].x, return_all=True)
+    assert O.max_scaled_error(y1, y2, chain[-1]) <= 2 * G.TOL[WL.F32]
+
+
+def test_one_launch_chain_falls_back():
+    # split block rows, fp16 plans and batch > 1 keep one launch per layer
+    probs = WL.config4(seed=30, dims=(200, 96, 128), eliminated=False, frac=0.6)
+    _check_chain(probs, chunk_tiles=1, want_one_launch=False)
+    _check_chain(WL.config4(seed=31, dims=(200, 96, 128), wdtype=WL.F16), want_one_launch=False)
+    probs3 = WL.config4(seed=32, batch=3, dims=(200, 96, 128))
+    _check_chain(probs3)                                  # one_launch plan, batch 3: per-layer launches
 
 
 # ------------------------------------------------------------------------ LSTM
