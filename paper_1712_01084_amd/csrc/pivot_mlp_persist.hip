@@ -246,8 +246,14 @@ __device__ __forceinline__ void chain_item(const ChainLayer& P, int item, bool o
     __syncthreads();                                    // the next layer's staging reuses the LDS
 }
 
+// The first layer's pointers and shape come as separate leading arguments: those are preloaded into SGPRs with the
+// wave (14 dwords), so the first loads of the launch do not wait for a fetch of the argument block.
+// q0_ct_parts = uniform_ct | uniform_parts << 16; q0_shape = slices | bhs << 8 | bh_full << 16.
 template <int BW>
-__global__ void __launch_bounds__(kChainNW * 64) mlp_persist_kernel(ChainArgs A) {
+__global__ void __launch_bounds__(kChainNW * 64) mlp_persist_kernel(
+        const int32_t* __restrict__ p0_xidx, const float* __restrict__ p0_vals, const void* __restrict__ p0_in,
+        const float* __restrict__ p0_bias, const int32_t* __restrict__ p0_dst,
+        int q0_ct_parts, int q0_shape, int q0_chunk_tiles, int q0_nitems, ChainArgs A) {
     extern __shared__ __align__(16) char smem[];
     __shared__ uint32_t s_tag;
     const int wg = blockIdx.x;
@@ -258,9 +264,7 @@ __global__ void __launch_bounds__(kChainNW * 64) mlp_persist_kernel(ChainArgs A)
     if (threadIdx.x == 0) counter = cld32(A.ctl + wg);
     uint32_t tag = 0;
     bool have_tag = false;
-    for (int l = 0; l < A.nlayers; ++l) {
-        const ChainLayer& P = A.L[l];
-        if (wg >= P.nitems) continue;                   // uniform over the workgroup
+    auto run_layer = [&](const ChainLayer& P, int l) {
         const bool in_tagged = l > 0, out_tagged = l + 1 < A.nlayers;
         if (!have_tag && in_tagged) {
             if (threadIdx.x == 0) s_tag = counter + 1u;
@@ -290,6 +294,19 @@ __global__ void __launch_bounds__(kChainNW * 64) mlp_persist_kernel(ChainArgs A)
             have_tag = true;
             if (threadIdx.x == 0) cst32(A.ctl + wg, tag);
         }
+    };
+    if (wg < q0_nitems) {                               // uniform over the workgroup
+        ChainLayer P0;
+        P0.xidx = p0_xidx; P0.vals = p0_vals; P0.in = p0_in; P0.bias_p = p0_bias; P0.dst = p0_dst;
+        P0.uniform_ct = q0_ct_parts & 0xFFFF; P0.uniform_parts = q0_ct_parts >> 16;
+        P0.slices = q0_shape & 0xFF; P0.bhs = (q0_shape >> 8) & 0xFF; P0.bh_full = (q0_shape >> 16) & 0xFF;
+        P0.chunk_tiles = q0_chunk_tiles; P0.nitems = q0_nitems;
+        P0.chunks = A.L[0].chunks; P0.out = A.L[0].out; P0.act = A.L[0].act; P0.k_valid = A.L[0].k_valid;
+        run_layer(P0, 0);
+    }
+    for (int l = 1; l < A.nlayers; ++l) {
+        const ChainLayer& P = A.L[l];
+        if (wg < P.nitems) run_layer(P, l);             // uniform over the workgroup
     }
 }
 
@@ -371,7 +388,13 @@ int launch_chain_persist(const ChainPersistLaunch& C) {
         P.act = hp.d.act; P.k_valid = hp.d.K;
     }
     hipStream_t st = reinterpret_cast<hipStream_t>(C.stream);
-    void* args[] = {&A};
+    const ChainLayer& F = A.L[0];
+    if (F.uniform_ct > 0xFFFF || F.uniform_parts > 0x7FFF) { set_error("first layer outside the packed arguments"); return PIVOT_E_UNSUPPORTED; }
+    const int32_t* p0_xidx = F.xidx; const float* p0_vals = F.vals; const void* p0_in = F.in;
+    const float* p0_bias = F.bias_p; const int32_t* p0_dst = F.dst;
+    int q0_ct_parts = F.uniform_ct | (F.uniform_parts << 16), q0_shape = F.slices | (F.bhs << 8) | (F.bh_full << 16);
+    int q0_chunk_tiles = F.chunk_tiles, q0_nitems = F.nitems;
+    void* args[] = {&p0_xidx, &p0_vals, &p0_in, &p0_bias, &p0_dst, &q0_ct_parts, &q0_shape, &q0_chunk_tiles, &q0_nitems, &A};
     HIP_TRY(hipLaunchKernel(chain_kernel_for(C.bw), dim3(C.grid), dim3(kChainNW * 64), args, C.smem, st));
     return PIVOT_OK;
 }
