@@ -151,9 +151,8 @@ struct RowPre {
 // return in order: an index fetched after the weights would only arrive after
 // them).  All of these loads and LDS writes are unconditional: out-of-range
 // elements use a clamped index and land in a dump slot at the end of the LDS row.
-template <typename WT, int BW, int NB, int NT>
+template <typename WT, int BW, int NB, int NT, int XP = 4>
 struct XStage {
-    static constexpr int XP = 4;
     int src[XP];
     __device__ __forceinline__ void load_idx(const int32_t* xidx, int tile_begin, int ne, int tid) {
         const int32_t* xi = xidx + (size_t)tile_begin * BW;
@@ -210,9 +209,8 @@ struct XStage {
 };
 
 // One batch row: the same staging with the batch loop folded away.
-template <typename WT, int BW, int NT>
-struct XStage<WT, BW, 1, NT> {
-    static constexpr int XP = 4;
+template <typename WT, int BW, int NT, int XP>
+struct XStage<WT, BW, 1, NT, XP> {
     int src[XP];
     __device__ __forceinline__ void load_idx(const int32_t* xidx, int tile_begin, int ne, int tid) {
         const int32_t* xi = xidx + (size_t)tile_begin * BW;
@@ -430,7 +428,7 @@ __global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(PIVOT_GEMV_PARAMS, FcA
     const int tile_elems = q_bh_full * BW;
 
     if constexpr (XR == 1) xres.load(q_batch, q_ldx, q_xn_vecs, p_x, b0, tid);
-    XStage<WT, BW, NB, NT> xst;
+    XStage<WT, BW, NB, NT, (XR == 3) ? 8 : 4> xst;      // long inputs come with long work items: 8 indices up front
     xst.load_idx(p_idx, tile_begin, ntiles * BW, tid);
 
     const int s  = lane / LPR;                          // row within the wave-load
