@@ -305,7 +305,7 @@ int pivot_mlp_plan(pivot_fc_plan_t* const* layers, int Lcount, int flags, pivot_
         std::vector<const HostPlan*> hps;
         for (int l = 0; l < Lcount; ++l) hps.push_back(&layers[l]->host);
         mp->persist_ok = !(flags & PIVOT_MLP_LAUNCH_PER_LAYER) &&
-                         chain_persist_supported(hps, mp->device, &mp->persist_grid, &mp->persist_smem, nullptr);
+                         chain_persist_supported(hps, mp->device, &mp->persist_grid, &mp->persist_smem, &mp->persist_smem_copy, nullptr);
         const size_t persist_off = total;
         if (mp->persist_ok) {
             total += align_up(chain_persist_ctl_bytes(), 256);
@@ -413,7 +413,7 @@ int pivot_mlp_run(const pivot_mlp_plan_t* plan, const void* x_dev, int64_t ldx, 
     if (batch == 1 && plan->persist_ok) {
         // the whole chain in one launch; intermediates are the plan's own (value, tag) pairs
         ChainPersistLaunch C;
-        C.ctl = plan->persist_ctl; C.grid = plan->persist_grid; C.smem = plan->persist_smem;
+        C.ctl = plan->persist_ctl; C.grid = plan->persist_grid; C.smem = plan->persist_smem; C.smem_copy = plan->persist_smem_copy;
         C.bw = plan->layers[0]->host.d.bw; C.stream = stream;
         for (int l = 0; l < Lc; ++l) {
             const pivot_fc_plan_t* p = plan->layers[l];

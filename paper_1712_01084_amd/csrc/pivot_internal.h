@@ -162,10 +162,11 @@ struct ChainPersistLaunch {
     std::vector<ChainPersistLayer> layers;
     uint32_t* ctl;                     // chain_persist_ctl_bytes, zeroed once when the chain plan is made
     int grid, bw; size_t smem;
+    size_t smem_copy;                  // > 0: LDS size with the first layer's x copied into LDS whole (used if x is 16-byte aligned)
     void* stream;
 };
 bool   chain_persist_supported(const std::vector<const HostPlan*>& layers, int device, int* grid_out, size_t* smem_out,
-                               std::string* why);
+                               size_t* smem_copy_out, std::string* why);
 size_t chain_persist_ctl_bytes();
 int    chain_persist_status_offset();  // byte offset of the status word inside the control block
 int    launch_chain_persist(const ChainPersistLaunch& C);
@@ -191,7 +192,7 @@ struct pivot_mlp_plan {
     // one-launch form: control words and one buffer of (value, tag) pairs per boundary, in dev_base
     bool persist_ok = false;
     int persist_grid = 0;
-    size_t persist_smem = 0;
+    size_t persist_smem = 0, persist_smem_copy = 0;
     uint32_t* persist_ctl = nullptr;
     std::vector<unsigned long long*> persist_pairs;
 };

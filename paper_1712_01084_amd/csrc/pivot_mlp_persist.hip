@@ -44,6 +44,7 @@ struct ChainLayer {
     const void*    in;          // layer 0: float x in natural order; later layers: pairs in this layer's block order
     void*          out;         // pairs in the next layer's block order; last layer: float y
     int nitems, slices, bhs, bh_full, uniform_ct, uniform_parts, chunk_tiles, act, k_valid;
+    int xn_vecs;                // first layer, kInCopy: 16-byte vectors of x
 };
 
 struct ChainArgs {
@@ -77,10 +78,16 @@ __device__ __forceinline__ bool chain_keep_waiting(uint32_t* ctl, uint32_t& spin
 
 // One work item of one layer (see fc_gemv_kernel for the streaming scheme).
 // No thread leaves early: every barrier is reached by the whole workgroup.
-// IN_TAGGED is a compile-time switch: a run-time branch around the gather loads would make the compiler wait for
-// every outstanding weight load before it issues them.  The first layer (plain x, usually the long one) fetches
-// eight gather indices per thread up front, so that up to 4096 staged elements need one round of dependent loads.
-template <int BH, int BW, int NW, bool IN_TAGGED>
+// XIN says where the layer's input comes from, at compile time (a run-time branch around the gather loads would
+// make the compiler wait for every outstanding weight load before it issues them):
+//   kInPlain  the caller's x, gathered element by element from global memory
+//   kInCopy   the caller's x, first copied whole into LDS with coalesced 16-byte loads (up to 16 per thread) and
+//             gathered from there: for a long x the element gather moves a whole cache line per element
+//   kInTagged (value, tag) pairs of the previous layer, re-read until they carry this launch's tag
+// The first layer (usually the long one) fetches eight gather indices per thread up front, so that up to 4096
+// staged elements need one round of dependent loads.
+enum { kInPlain = 0, kInTagged = 1, kInCopy = 2 };
+template <int BH, int BW, int NW, int XIN>
 __device__ __forceinline__ void chain_item(const ChainLayer& P, int item, bool out_tagged,
                                            uint32_t tag, uint32_t counter, uint32_t* s_tag, uint32_t* ctl, char* smem) {
     using V = f32x4;
@@ -91,13 +98,18 @@ __device__ __forceinline__ void chain_item(const ChainLayer& P, int item, bool o
     constexpr int NL  = (BH >= RPW) ? BH / RPW : 1;
     constexpr int TPL = (BH >= RPW) ? 1 : RPW / BH;
     constexpr int U   = (NL >= 8) ? 1 : 8 / NL;
+    constexpr bool IN_TAGGED = (XIN == kInTagged);
     constexpr int XP  = IN_TAGGED ? 4 : 8;
     static_assert(BH <= NT, "one thread per output row");
 
-    float* xs  = reinterpret_cast<float*>(smem);
+    // LDS: [copy of x + a dump vector (kInCopy)][staged x-segments]; the sums reuse it afterwards
+    float* xn  = reinterpret_cast<float*>(smem);
+    float* xs  = (XIN == kInCopy) ? xn + (size_t)P.xn_vecs * VEC + VEC : xn;
     float* red = reinterpret_cast<float*>(smem);        // reused after the stream phase
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    XRes<float, 1, NT, 16> xres;
+    if constexpr (XIN == kInCopy) xres.load(1, 0, P.xn_vecs, P.in, 0, tid);
     const int chunk = item / P.slices, slice = item - chunk * P.slices;
     int br, tile_begin, ntiles;
     if (P.uniform_ct > 0) {
@@ -138,9 +150,13 @@ __device__ __forceinline__ void chain_item(const ChainLayer& P, int item, bool o
 
     // stage the x-segments: plain loads from the caller's x, or pairs re-read until they carry this launch's tag.
     // The first round stands outside the loop so that no loop header sits between its loads and the ones above.
+    if constexpr (XIN == kInCopy) {
+        xres.store(1, P.xn_vecs, xn, 0, tid);
+        lds_barrier();
+    }
     auto stage = [&](int e0) {
         if constexpr (!IN_TAGGED) {
-            const float* x = reinterpret_cast<const float*>(P.in);
+            const float* x = (XIN == kInCopy) ? xn : reinterpret_cast<const float*>(P.in);
             float v[XP];
             #pragma unroll
             for (int k = 0; k < XP; ++k) v[k] = x[src[k] > 0 ? src[k] : 0];
@@ -248,7 +264,8 @@ __device__ __forceinline__ void chain_item(const ChainLayer& P, int item, bool o
 
 // The first layer's pointers and shape come as separate leading arguments: those are preloaded into SGPRs with the
 // wave (14 dwords), so the first loads of the launch do not wait for a fetch of the argument block.
-// q0_ct_parts = uniform_ct | uniform_parts << 16; q0_shape = slices | bhs << 8 | bh_full << 16.
+// q0_ct_parts = uniform_ct | uniform_parts << 16; q0_shape = slices | bhs << 8 | bh_full << 16;
+// q0_chunk_tiles = chunk_tiles | xn_vecs << 16 (xn_vecs > 0: copy x into LDS first).
 template <int BW>
 __global__ void __launch_bounds__(kChainNW * 64) mlp_persist_kernel(
         const int32_t* __restrict__ p0_xidx, const float* __restrict__ p0_vals, const void* __restrict__ p0_in,
@@ -276,17 +293,24 @@ __global__ void __launch_bounds__(kChainNW * 64) mlp_persist_kernel(
         uint32_t* st = have_tag ? nullptr : &s_tag;
         if (in_tagged) {
             switch (P.bhs) {
-                case 8:  chain_item<8,  BW, kChainNW, true>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
-                case 16: chain_item<16, BW, kChainNW, true>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
-                case 32: chain_item<32, BW, kChainNW, true>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
-                default: chain_item<64, BW, kChainNW, true>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
+                case 8:  chain_item<8,  BW, kChainNW, kInTagged>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
+                case 16: chain_item<16, BW, kChainNW, kInTagged>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
+                case 32: chain_item<32, BW, kChainNW, kInTagged>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
+                default: chain_item<64, BW, kChainNW, kInTagged>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
+            }
+        } else if (P.xn_vecs > 0) {
+            switch (P.bhs) {
+                case 8:  chain_item<8,  BW, kChainNW, kInCopy>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
+                case 16: chain_item<16, BW, kChainNW, kInCopy>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
+                case 32: chain_item<32, BW, kChainNW, kInCopy>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
+                default: chain_item<64, BW, kChainNW, kInCopy>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
             }
         } else {
             switch (P.bhs) {
-                case 8:  chain_item<8,  BW, kChainNW, false>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
-                case 16: chain_item<16, BW, kChainNW, false>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
-                case 32: chain_item<32, BW, kChainNW, false>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
-                default: chain_item<64, BW, kChainNW, false>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
+                case 8:  chain_item<8,  BW, kChainNW, kInPlain>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
+                case 16: chain_item<16, BW, kChainNW, kInPlain>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
+                case 32: chain_item<32, BW, kChainNW, kInPlain>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
+                default: chain_item<64, BW, kChainNW, kInPlain>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
             }
         }
         if (!have_tag) {                                // s_tag was set inside the item, before its last barriers
@@ -300,7 +324,7 @@ __global__ void __launch_bounds__(kChainNW * 64) mlp_persist_kernel(
         P0.xidx = p0_xidx; P0.vals = p0_vals; P0.in = p0_in; P0.bias_p = p0_bias; P0.dst = p0_dst;
         P0.uniform_ct = q0_ct_parts & 0xFFFF; P0.uniform_parts = q0_ct_parts >> 16;
         P0.slices = q0_shape & 0xFF; P0.bhs = (q0_shape >> 8) & 0xFF; P0.bh_full = (q0_shape >> 16) & 0xFF;
-        P0.chunk_tiles = q0_chunk_tiles; P0.nitems = q0_nitems;
+        P0.chunk_tiles = q0_chunk_tiles & 0xFFFF; P0.xn_vecs = q0_chunk_tiles >> 16; P0.nitems = q0_nitems;
         P0.chunks = A.L[0].chunks; P0.out = A.L[0].out; P0.act = A.L[0].act; P0.k_valid = A.L[0].k_valid;
         run_layer(P0, 0);
     }
@@ -330,7 +354,7 @@ int chain_slices(const HostPlan& hp) {
 size_t chain_persist_ctl_bytes() { return (size_t)(kChainStatus + 64) * 4; }
 
 bool chain_persist_supported(const std::vector<const HostPlan*>& layers, int device, int* grid_out, size_t* smem_out,
-                             std::string* why) {
+                             size_t* smem_copy_out, std::string* why) {
     auto no = [&](const char* m) { if (why) *why = m; return false; };
     const int Lc = (int)layers.size();
     if (Lc < 2 || Lc > kMaxChainLayers) return no("2..8 layers");
@@ -355,6 +379,16 @@ bool chain_persist_supported(const std::vector<const HostPlan*>& layers, int dev
     }
     smem = align_up(smem, 16);
     if (smem > 64 * 1024) return no("staged x does not fit in LDS");
+    // with the first layer's x copied into LDS whole (chosen at launch if x is 16-byte aligned): 0 = not possible
+    size_t smem_copy = 0;
+    {
+        const HostPlan& f = *layers[0];
+        const int ct = f.uniform_ct > 0 ? f.uniform_ct : f.chunk_tiles;
+        const size_t need = ((size_t)f.d.K + 4) * 4 + ((size_t)ct * bw + 4) * 4;
+        const size_t item_bytes = (size_t)ct * (f.d.bh / chain_slices(f)) * bw * 4;   // same threshold as the layer kernel
+        if (item_bytes >= 48 * 1024 && f.d.K % 4 == 0 && f.d.K / 4 <= 16 * kChainNW * 64 && need <= 150 * 1024)
+            smem_copy = align_up(std::max(need, smem), 16);
+    }
     if (device >= 0) {
         int per_cu = 0, cus = 0;
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, chain_kernel_for(bw), kChainNW * 64, smem) != hipSuccess ||
@@ -363,9 +397,15 @@ bool chain_persist_supported(const std::vector<const HostPlan*>& layers, int dev
             return no("occupancy query failed");
         }
         if ((long long)per_cu * cus < G) return no("the work items of a layer are not all resident at once");
+        // the copy takes most of a compute unit's LDS: one workgroup per compute unit
+        if (smem_copy > 80 * 1024 && G > cus) smem_copy = 0;
+        if (smem_copy > 0 && smem_copy <= 80 * 1024 && (long long)(160 * 1024 / smem_copy) * cus < G) smem_copy = 0;
+    } else {
+        smem_copy = 0;
     }
     if (grid_out) *grid_out = G;
     if (smem_out) *smem_out = smem;
+    if (smem_copy_out) *smem_copy_out = smem_copy;
     return true;
 }
 
@@ -385,17 +425,30 @@ int launch_chain_persist(const ChainPersistLaunch& C) {
         P.nitems = hp.nchunks * sl; P.slices = sl; P.bhs = hp.d.bh / sl; P.bh_full = hp.d.bh;
         P.uniform_ct = hp.uniform_ct; P.uniform_parts = hp.uniform_parts;
         P.chunk_tiles = hp.uniform_ct > 0 ? hp.uniform_ct : hp.chunk_tiles;
-        P.act = hp.d.act; P.k_valid = hp.d.K;
+        P.act = hp.d.act; P.k_valid = hp.d.K; P.xn_vecs = 0;
+    }
+    size_t smem = C.smem;
+    if (C.smem_copy > 0 && (reinterpret_cast<uintptr_t>(A.L[0].in) & 15) == 0) {
+        A.L[0].xn_vecs = C.layers[0].hp->d.K / 4;
+        smem = C.smem_copy;
+        if (smem > 64 * 1024) {                         // more than 64 KB of dynamic LDS has to be allowed per kernel
+            static size_t allowed[3] = {64 * 1024, 64 * 1024, 64 * 1024};
+            size_t& a = allowed[C.bw == 16 ? 0 : (C.bw == 32 ? 1 : 2)];
+            if (smem > a) {
+                HIP_TRY(hipFuncSetAttribute(chain_kernel_for(C.bw), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+                a = smem;
+            }
+        }
     }
     hipStream_t st = reinterpret_cast<hipStream_t>(C.stream);
     const ChainLayer& F = A.L[0];
-    if (F.uniform_ct > 0xFFFF || F.uniform_parts > 0x7FFF) { set_error("first layer outside the packed arguments"); return PIVOT_E_UNSUPPORTED; }
+    if (F.uniform_ct > 0xFFFF || F.uniform_parts > 0x7FFF || F.chunk_tiles > 0xFFFF || F.xn_vecs > 0x7FFF) { set_error("first layer outside the packed arguments"); return PIVOT_E_UNSUPPORTED; }
     const int32_t* p0_xidx = F.xidx; const float* p0_vals = F.vals; const void* p0_in = F.in;
     const float* p0_bias = F.bias_p; const int32_t* p0_dst = F.dst;
     int q0_ct_parts = F.uniform_ct | (F.uniform_parts << 16), q0_shape = F.slices | (F.bhs << 8) | (F.bh_full << 16);
-    int q0_chunk_tiles = F.chunk_tiles, q0_nitems = F.nitems;
+    int q0_chunk_tiles = F.chunk_tiles | (F.xn_vecs << 16), q0_nitems = F.nitems;
     void* args[] = {&p0_xidx, &p0_vals, &p0_in, &p0_bias, &p0_dst, &q0_ct_parts, &q0_shape, &q0_chunk_tiles, &q0_nitems, &A};
-    HIP_TRY(hipLaunchKernel(chain_kernel_for(C.bw), dim3(C.grid), dim3(kChainNW * 64), args, C.smem, st));
+    HIP_TRY(hipLaunchKernel(chain_kernel_for(C.bw), dim3(C.grid), dim3(kChainNW * 64), args, smem, st));
     return PIVOT_OK;
 }
 

@@ -107,6 +107,32 @@ def test_one_launch_chain_fp32_batch1(eliminated, bh, bw, dims):
     assert O.max_scaled_error(y1, y2, chain[-1]) <= 2 * G.TOL[WL.F32]
 
 
+def test_one_launch_chain_long_first_input_copied_into_lds():
+    # a first layer whose work items stream more than 48 KB copies x into LDS whole and gathers from there;
+    # an x that is not 16-byte aligned takes the element gather instead, with the same result
+    probs = WL.config4(seed=33, dims=(4096, 64, 48), frac=0.5)
+    _check_chain(probs, want_one_launch=True, repeats=3)
+    plans = [G.dev_plan(p) for p in probs]
+    mlp = B.pivot_mlp_plan(plans, 0)
+    try:
+        st = torch.cuda.current_stream().cuda_stream
+        ws = G.workspace(B.pivot_mlp_workspace_bytes(mlp, 1))
+        outs = []
+        for off in (0, 1):
+            buf = torch.zeros(probs[0].K + 4, dtype=torch.float32, device="cuda")
+            buf[off:off + probs[0].K] = torch.from_numpy(probs[0].x[0]).cuda()
+            yd = torch.full((1, probs[-1].M), float("nan"), dtype=torch.float32, device="cuda")
+            B.pivot_mlp_run(mlp, buf.data_ptr() + 4 * off, probs[0].K, yd.data_ptr(), probs[-1].M, 1, ws.data_ptr(), ws.numel(), st)
+            torch.cuda.synchronize()
+            outs.append(yd.cpu().numpy())
+        assert B.pivot_mlp_status(mlp, st) == 0
+        assert outs[0].tobytes() == outs[1].tobytes()      # same arithmetic in the same order
+    finally:
+        B.pivot_mlp_plan_destroy(mlp)
+        for h in plans:
+            B.pivot_fc_plan_destroy(h)
+
+
 def test_one_launch_chain_falls_back():
     # split block rows, fp16 plans and batch > 1 keep one launch per layer
     probs = WL.config4(seed=30, dims=(200, 96, 128), eliminated=False, frac=0.6)
