@@ -133,6 +133,43 @@ def test_one_launch_chain_long_first_input_copied_into_lds():
             B.pivot_fc_plan_destroy(h)
 
 
+def test_one_launch_chain_in_a_replayed_graph():
+    # the launch tag comes from a counter in device memory, so a captured launch gets a fresh tag on every
+    # replay with no host work: several replays, eager work in between, every result equal to the eager one
+    import bench_util as BU
+    probs = WL.config4(seed=34, dims=(520, 256, 96, 40), frac=0.4)
+    plans = [G.dev_plan(p) for p in probs]
+    mlp = B.pivot_mlp_plan(plans, 0)
+    try:
+        xd = torch.from_numpy(probs[0].x).cuda()
+        ws = G.workspace(B.pivot_mlp_workspace_bytes(mlp, 1))
+        yd = torch.full((1, probs[-1].M), float("nan"), dtype=torch.float32, device="cuda")
+
+        def enqueue(i, s):
+            B.pivot_mlp_run(mlp, xd.data_ptr(), probs[0].K, yd.data_ptr(), probs[-1].M, 1, ws.data_ptr(), ws.numel(), s)
+
+        st = torch.cuda.current_stream().cuda_stream
+        enqueue(0, st)
+        torch.cuda.synchronize()
+        eager = yd.cpu().numpy().copy()
+        g = BU.capture(enqueue, 3)
+        for _ in range(4):
+            yd.fill_(float("nan"))
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            assert yd.cpu().numpy().tobytes() == eager.tobytes()
+            enqueue(0, st)                                  # an eager launch between replays
+            torch.cuda.synchronize()
+        assert B.pivot_mlp_status(mlp, st) == 0
+        outs, scales, chain = O.oracle_mlp(_layers(probs), probs[0].x, return_all=True)
+        assert O.max_scaled_error(eager.astype(np.float64), outs[-1], chain[-1]) <= G.TOL[WL.F32]
+    finally:
+        B.pivot_mlp_plan_destroy(mlp)
+        for h in plans:
+            B.pivot_fc_plan_destroy(h)
+
+
 def test_one_launch_chain_falls_back():
     # split block rows, fp16 plans and batch > 1 keep one launch per layer
     probs = WL.config4(seed=30, dims=(200, 96, 128), eliminated=False, frac=0.6)
