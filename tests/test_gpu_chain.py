@@ -170,6 +170,16 @@ def test_one_launch_chain_in_a_replayed_graph():
             B.pivot_fc_plan_destroy(h)
 
 
+def test_one_launch_chain_degenerate_layers():
+    # a middle layer without any kept tile (its outputs are relu(b), still tagged and waited for), an output
+    # layer narrower than one tile, and a block row without tiles in the first layer
+    probs = WL.config4(seed=35, dims=(200, 96, 130, 5), frac=0.4)
+    probs[1].tile_mask[:] = 0
+    probs[0].tile_mask[1, :] = 0
+    _check_chain(probs, want_one_launch=True, repeats=3)
+    _check_chain(probs, flags=B.PIVOT_MLP_LAUNCH_PER_LAYER, want_one_launch=False)
+
+
 def test_one_launch_chain_falls_back():
     # split block rows, fp16 plans and batch > 1 keep one launch per layer
     probs = WL.config4(seed=30, dims=(200, 96, 128), eliminated=False, frac=0.6)
@@ -177,6 +187,8 @@ def test_one_launch_chain_falls_back():
     _check_chain(WL.config4(seed=31, dims=(200, 96, 128), wdtype=WL.F16), want_one_launch=False)
     probs3 = WL.config4(seed=32, batch=3, dims=(200, 96, 128))
     _check_chain(probs3)                                  # one_launch plan, batch 3: per-layer launches
+    wide = WL.config4(seed=36, dims=(64, 40000, 32), frac=0.5)
+    _check_chain(wide, want_one_launch=False)             # 1250 block rows: more work items than the form takes
 
 
 # ------------------------------------------------------------------------ LSTM
