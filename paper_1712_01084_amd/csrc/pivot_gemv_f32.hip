@@ -6,12 +6,15 @@ namespace pivot {
 template <int BH, int BW, int NB, int XR>
 static int launch_t(const FcArgs& a, int nw, dim3 grid, size_t smem, hipStream_t st) {
     if constexpr (XR == 3) {
-        // more than 64 KB of dynamic LDS per workgroup has to be allowed per kernel
-        static size_t allowed = 64 * 1024;
-        if (smem > allowed) {
+        // more than 64 KB of dynamic LDS per workgroup has to be allowed per kernel and device
+        static size_t allowed[16] = {};
+        int dev = 0;
+        HIP_TRY(hipGetDevice(&dev));
+        size_t& have = allowed[dev & 15];
+        if (smem > 64 * 1024 && smem > have) {
             HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&fc_gemv_kernel<float, BH, BW, NB, 8, XR>),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-            allowed = smem;
+            have = smem;
         }
         hipLaunchKernelGGL((fc_gemv_kernel<float, BH, BW, NB, 8, XR>), grid, dim3(8 * 64), smem, st, PIVOT_GEMV_ARGS(a), a);
     }

@@ -4,15 +4,18 @@
 
 namespace pivot {
 
-// Compute units of the current device (asked once).
+// Compute units of the current device (asked once per device).
 static int device_cus() {
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) cus = n;
-        else { (void)hipGetLastError(); cus = 1; }
+    static int cus[16] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return 1; }
+    int& c = cus[dev & 15];
+    if (c == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) c = n;
+        else { (void)hipGetLastError(); c = 1; }
     }
-    return cus;
+    return c;
 }
 
 static int mfma_kind(int wdtype, int bh, int bw) {

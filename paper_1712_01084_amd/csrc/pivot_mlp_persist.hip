@@ -431,9 +431,11 @@ int launch_chain_persist(const ChainPersistLaunch& C) {
     if (C.smem_copy > 0 && (reinterpret_cast<uintptr_t>(A.L[0].in) & 15) == 0) {
         A.L[0].xn_vecs = C.layers[0].hp->d.K / 4;
         smem = C.smem_copy;
-        if (smem > 64 * 1024) {                         // more than 64 KB of dynamic LDS has to be allowed per kernel
-            static size_t allowed[3] = {64 * 1024, 64 * 1024, 64 * 1024};
-            size_t& a = allowed[C.bw == 16 ? 0 : (C.bw == 32 ? 1 : 2)];
+        if (smem > 64 * 1024) {                         // more than 64 KB of dynamic LDS has to be allowed per kernel and device
+            static size_t allowed[16][3] = {};
+            int dev = 0;
+            HIP_TRY(hipGetDevice(&dev));
+            size_t& a = allowed[dev & 15][C.bw == 16 ? 0 : (C.bw == 32 ? 1 : 2)];
             if (smem > a) {
                 HIP_TRY(hipFuncSetAttribute(chain_kernel_for(C.bw), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
                 a = smem;
