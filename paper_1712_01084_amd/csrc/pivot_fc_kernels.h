@@ -395,7 +395,8 @@ __global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(PIVOT_GEMV_PARAMS, FcA
     constexpr int LPR = BW / VEC;                       // lanes per tile row
     constexpr int RPW = 64 / LPR;                       // tile rows per wave-load
     constexpr int NL  = (BH >= RPW) ? BH / RPW : 1;     // wave-loads per tile
-    constexpr int TPL = (BH >= RPW) ? 1 : RPW / BH;     // tiles per wave-load (only with a single slice)
+    constexpr int TPL = (BH >= RPW) ? 1 : RPW / BH;     // tiles per wave-load: a slice shorter than a wave-load takes
+                                                        // the same rows of TPL consecutive tiles (BH*BW*es contiguous bytes each)
     constexpr int U   = (NL >= 8) ? 1 : 8 / NL;         // groups in flight per wave
     constexpr int N   = BH * NB;
     static_assert(BW >= VEC && LPR <= 64, "tile width not supported");
@@ -435,8 +436,9 @@ __global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(PIVOT_GEMV_PARAMS, FcA
     const int cg = lane % LPR;                          // column group
     const int ts = (TPL > 1) ? s / BH : 0;              // tile within the group
     const size_t gstride = (size_t)TPL * tile_elems;    // elements between groups of tiles
+    const int lane_off = (TPL > 1) ? ts * tile_elems + (s % BH) * BW + cg * VEC : lane * VEC;
     const WT* vbase = reinterpret_cast<const WT*>(p_vals) + (size_t)tile_begin * tile_elems
-                      + (size_t)slice * BH * BW + lane * VEC;
+                      + (size_t)slice * BH * BW + lane_off;
 
     // Loads are unconditional (group index clamped; the value array is padded by
     // one group of zeros, so even an empty chunk reads valid memory): no branch

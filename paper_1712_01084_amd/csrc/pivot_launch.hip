@@ -63,8 +63,9 @@ int fc_batch_tile(int layout, int wdtype, int bh, int bw, int chunk_tiles, int b
 }
 
 // Largest number of row slices <= want that the chosen kernel supports: a
-// slice of the vector kernel must hold at least one 1 KB wave-load and 8 rows,
-// a slice of the matrix kernel whole MFMA row blocks.
+// slice of the vector kernel has at least 8 rows and is a whole number of 1 KB
+// wave-loads or a whole fraction of one (a wave-load then takes the same rows
+// of several consecutive tiles), a slice of the matrix kernel whole MFMA row blocks.
 int fc_row_slices(int layout, int wdtype, int bh, int bw, int chunk_tiles, int batch, int want) {
     if (layout != PIVOT_BRC) return 1;       // a row slice is contiguous only in row-major tiles
     int sl = want < 1 ? 1 : want;
@@ -78,7 +79,7 @@ int fc_row_slices(int layout, int wdtype, int bh, int bw, int chunk_tiles, int b
             } else {
                 const int vec = 16 / elem_size(wdtype);
                 const int rpw = 64 / (bw / vec > 0 ? bw / vec : 1);
-                ok = bhs >= 8 && bhs >= rpw;
+                ok = bhs >= 8 && (bhs % rpw == 0 || rpw % bhs == 0);
             }
         }
         if (ok) break;

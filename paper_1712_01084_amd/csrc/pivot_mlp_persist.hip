@@ -134,7 +134,8 @@ __device__ __forceinline__ void chain_item(const ChainLayer& P, int item, bool o
     const int s  = lane / LPR, cg = lane % LPR;
     const int ts = (TPL > 1) ? s / BH : 0;
     const size_t gstride = (size_t)TPL * tile_elems;
-    const float* vbase = P.vals + (size_t)tile_begin * tile_elems + (size_t)slice * BH * BW + lane * VEC;
+    const int lane_off = (TPL > 1) ? ts * tile_elems + (s % BH) * BW + cg * VEC : lane * VEC;
+    const float* vbase = P.vals + (size_t)tile_begin * tile_elems + (size_t)slice * BH * BW + lane_off;
     V w[U][NL];
     #pragma unroll
     for (int u = 0; u < U; ++u) {
