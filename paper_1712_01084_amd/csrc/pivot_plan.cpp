@@ -52,14 +52,19 @@ void choose_schedule(HostPlan& hp) {
     // workgroup to the bytes it streams.
     int sl = d.row_slices;
     if (sl == 0) {
-        // The library's own choice stops at slices of one whole 1 KB wave-load.  Shorter slices (a wave-load then
-        // takes the same rows of several tiles) run when asked for; measured on 4096x4096 with 64x16 fp16 tiles
-        // they help some densities and hurt others (cold 7.2 -> 6.6 us at 50 %, 5.25 -> 5.45 us at 25 %), and the
-        // chunking that goes with them suits the batch-1 kernel only.
+        // slices of whole 1 KB wave-loads first
         const int vec = 16 / elem_size(d.wdtype);
         const int rpw = 64 / std::max(1, d.bw / vec);
         sl = 1;
         while (sl < 8 && hp.nbr * sl < 256 && d.bh / (sl * 2) >= rpw &&
+               fc_row_slices(d.layout, d.wdtype, d.bh, d.bw, 0, 1, sl * 2) == sl * 2) sl *= 2;
+        // Still fewer work items than compute units, block rows that will stay whole (under 256 KB per work item)
+        // and enough left per work item (16 KB): shorter slices, where a wave-load takes the same rows of several
+        // consecutive tiles.  Measured on 4096x4096 with 64x16 fp16 tiles (64 block rows: 128 -> 256 work items):
+        // cold 4.19 -> 3.94 us at 10 % kept, 5.25 -> 4.87 at 25 %, 7.20 -> 6.60 at 50 %; with 11 KB per work item
+        // (1024x1024, 16x16 tiles) it costs 0.1 us, and where rows get cut anyway (dense) it costs 0.3 us cold.
+        const size_t row_bytes = (size_t)max_row * tile_bytes;
+        while (sl < 8 && hp.nbr * sl < 256 && row_bytes / sl < 256 * 1024 && row_bytes / (sl * 2) >= 16 * 1024 &&
                fc_row_slices(d.layout, d.wdtype, d.bh, d.bw, 0, 1, sl * 2) == sl * 2) sl *= 2;
     }
     if (d.device >= 0) sl = fc_row_slices(d.layout, d.wdtype, d.bh, d.bw, 0, 1, sl);
@@ -79,7 +84,7 @@ void choose_schedule(HostPlan& hp) {
     int nw = d.wg_waves;
     if (nw == 0) {
         const size_t big = (size_t)std::min(ct, std::max(max_row, 1)) * slice_bytes;
-        nw = big <= 48 * 1024 ? 4 : (big <= 256 * 1024 ? 8 : 16);
+        nw = big < 32 * 1024 ? 4 : (big <= 256 * 1024 ? 8 : 16);
     }
     hp.wg_waves = nw;
 }
