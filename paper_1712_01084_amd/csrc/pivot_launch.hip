@@ -165,12 +165,15 @@ int launch_fc(const FcLaunch& L) {
         if (vectors <= (size_t)8 * nw * 64 && xn_bytes + xs_bytes <= 64 * 1024 && red_bytes <= 64 * 1024) {
             xres = a.uniform_ct > 0 ? 1 : 2;
         } else if (!ml && nbt == 1 && vectors <= (size_t)16 * 8 * 64 && xn_bytes + xs_bytes <= 144 * 1024 &&
-                   (size_t)L.nchunks * sl <= (size_t)device_cus()) {
+                   (size_t)L.nchunks * sl <= (size_t)device_cus() &&
+                   (size_t)(a.uniform_ct > 0 ? a.uniform_ct : L.chunk_tiles) * L.bw * 128 >= 2 * xn_bytes) {
             // Long x (beyond 64 KB of LDS or 8 vectors per thread): 8 wavefronts hold up to 16 vectors each and
             // the workgroup takes most of the 160 KB of a compute unit, so this form is only used when every
             // work item still gets a compute unit of its own.  It replaces a gather that moves a whole cache
             // line per element by a copy that moves every line once (25088 inputs, 78 tiles per work item:
-            // 320 KB of lines per work item against 100 KB).
+            // 320 KB of lines per work item against 100 KB), so it is taken only when the gathered lines are at
+            // least twice the copy (16384 inputs, 8 tiles of 64 columns per work item: 64 KB either way, and the
+            // copy was measured 0.6 us slower).
             xres = 3;
             nw = 8;
             red_bytes = (size_t)nw * bhs * nbt * 4;

@@ -387,7 +387,9 @@ bool chain_persist_supported(const std::vector<const HostPlan*>& layers, int dev
         const int ct = f.uniform_ct > 0 ? f.uniform_ct : f.chunk_tiles;
         const size_t need = ((size_t)f.d.K + 4) * 4 + ((size_t)ct * bw + 4) * 4;
         const size_t item_bytes = (size_t)ct * (f.d.bh / chain_slices(f)) * bw * 4;   // same threshold as the layer kernel
-        if (item_bytes >= 48 * 1024 && f.d.K % 4 == 0 && f.d.K / 4 <= 16 * kChainNW * 64 && need <= 150 * 1024)
+        // worth it when the element gather would move at least twice the bytes of the copy (a cache line per element)
+        if (item_bytes >= 48 * 1024 && (size_t)ct * bw * 128 >= 2 * (size_t)f.d.K * 4 && f.d.K % 4 == 0 &&
+            f.d.K / 4 <= 16 * kChainNW * 64 && need <= 150 * 1024)
             smem_copy = align_up(std::max(need, smem), 16);
     }
     if (device >= 0) {

@@ -84,7 +84,7 @@ void choose_schedule(HostPlan& hp) {
     int nw = d.wg_waves;
     if (nw == 0) {
         const size_t big = (size_t)std::min(ct, std::max(max_row, 1)) * slice_bytes;
-        nw = big < 32 * 1024 ? 4 : (big <= 256 * 1024 ? 8 : 16);
+        nw = big <= 32 * 1024 ? 4 : (big <= 256 * 1024 ? 8 : 16);
     }
     hp.wg_waves = nw;
 }
