@@ -82,6 +82,25 @@ def test_null_bias_is_zero_and_default_chunking_is_valid():
     assert np.array_equal(chunks, v["chunks"]) and np.array_equal(part_base, v["part_base"])
 
 
+def test_schedule_policy_on_the_workload_shapes():
+    # the library's own choice of row slices, chunk size and wavefronts (chunk_tiles = row_slices = wg_waves = 0)
+    # on the full workload shapes: about one work item per compute unit, block rows whole unless a work item
+    # would stream 256 KB, slices below one wave-load only while a work item keeps 16 KB
+    def policy(p):
+        plan = _host_plan(p, chunk_tiles=0)
+        v = B.pivot_fc_plan_host_view(plan)
+        B.pivot_fc_plan_destroy(plan)
+        return v["row_slices"], v["chunk_tiles"], v["wg_waves"], v["nchunks"]
+    assert policy(WL.config2(seed=0)) == (2, 29, 8, 128)                       # 256 work items of 58 KB
+    sl, ct, nw, nch = policy(WL.config1(seed=0))
+    assert (sl, nw, nch) == (1, 4, 64)                                         # 11 KB halves would be too small
+    for frac, want_sl, want_nw in ((0.05, 2, 4), (0.10, 4, 4), (0.25, 4, 8), (0.50, 4, 8)):
+        sl, ct, nw, nch = policy(WL.config3(seed=0, frac=frac))
+        assert (sl, nw, nch) == (want_sl, want_nw, 64), (frac, sl, ct, nw, nch) # whole block rows
+    assert policy(WL.config3(seed=0, frac=1.0)) == (2, 128, 8, 128)            # 256 KB rows are cut in two
+    assert policy(WL.paper_grid_case(8192, 0.03125, seed=0, wdtype=WL.F32, perms="random"))[2] == 4   # 32 KB items
+
+
 def test_error_paths_return_codes():
     p = WL.gen_fc(16, 16, 4, 4, 0.5, seed=4)
     args = dict(M=16, K=16, bh=4, bw=4, wdtype=B.PIVOT_F32, W=p.Wp, w_space=B.PIVOT_W_PIVOTED,
