@@ -414,10 +414,17 @@ static int persist_grid(int device) {
 bool lstm_persist_supported(const HostPlan& hp, int H, int batch, int device, int* grid_out, int* L_out) {
     if (hp.d.wdtype != PIVOT_F16 || hp.d.layout != PIVOT_BRC || hp.d.bh != kBH || hp.d.bw != kBW) return false;
     if (batch < 1 || batch > kCellB || hp.T < 1) return false;
-    int G = persist_grid(device);
-    if (G < 1) return false;
-    if (G > 256) G = 256;
-    if (hp.K_pad / kBW > G) return false;                                  // one workgroup per 32 input columns
+    int cus = persist_grid(device);
+    if (cus < 1) return false;
+    if (cus > 256) cus = 256;
+    if (hp.K_pad / kBW > cus) return false;                                // one workgroup per 32 input columns
+    // Workgroups: as few as fill the eight tile slots of every wavefront (every workgroup adds uncached requests
+    // to both exchanges of a step), but at least half the compute units and one per 32 input columns.  Measured
+    // on 6144 tiles: 256 workgroups (6 tiles per wavefront) 2195 us for 256 steps, 224 (7) 2220 us, 192 (8)
+    // 2065 us, 160 (10, the 16-slot kernel) 2660 us.
+    int G = (hp.T + 4 * 8 - 1) / (4 * 8);
+    G = std::max(G, std::max(hp.K_pad / kBW, cus / 2));
+    G = std::min(G, cus);
     const int L = (hp.T + 4 * G - 1) / (4 * G);
     if (L > 16) return false;                                             // tiles stay in registers
     if (grid_out) *grid_out = G;
