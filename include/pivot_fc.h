@@ -204,7 +204,7 @@ int  pivot_fc_run(const pivot_fc_plan_t* plan, const void* x_dev, int64_t ldx,
  * All layers must share wdtype and device.  Layer plans are borrowed and must
  * outlive the chain plan.
  *
- * Two forms.  A chain of fp32 BRC plans of one tile width whose work items
+ * Two forms.  A chain of BRC plans of one tile width whose work items
  * are whole block rows, at most 1024 per layer and all resident on the device
  * at once, runs at batch 1 in ONE launch (view.one_launch = 1): workgroup g
  * takes work item g of every layer in turn, an intermediate activation is

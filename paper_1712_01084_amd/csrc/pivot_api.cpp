@@ -414,7 +414,7 @@ int pivot_mlp_run(const pivot_mlp_plan_t* plan, const void* x_dev, int64_t ldx, 
         // the whole chain in one launch; intermediates are the plan's own (value, tag) pairs
         ChainPersistLaunch C;
         C.ctl = plan->persist_ctl; C.grid = plan->persist_grid; C.smem = plan->persist_smem; C.smem_copy = plan->persist_smem_copy;
-        C.bw = plan->layers[0]->host.d.bw; C.stream = stream;
+        C.bw = plan->layers[0]->host.d.bw; C.wdtype = plan->layers[0]->host.d.wdtype; C.stream = stream;
         for (int l = 0; l < Lc; ++l) {
             const pivot_fc_plan_t* p = plan->layers[l];
             ChainPersistLayer s{};

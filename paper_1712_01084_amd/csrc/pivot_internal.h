@@ -152,7 +152,7 @@ size_t lstm_persist_partial_bytes(const HostPlan& hp, int batch);
 constexpr size_t kLstmCtlBytes = 2048;
 int    launch_lstm_persist(const LstmPersistLaunch& P);
 
-// A chain of layers in one launch (fp32 BRC plans with whole block rows per work item, batch 1).
+// A chain of layers in one launch (BRC plans of one weight type with whole block rows per work item, batch 1).
 struct ChainPersistLayer {
     const HostPlan* hp;
     const void* vals; const int32_t* chunks; const int32_t* xidx; const float* bias_p; const int32_t* dst;
@@ -161,7 +161,7 @@ struct ChainPersistLayer {
 struct ChainPersistLaunch {
     std::vector<ChainPersistLayer> layers;
     uint32_t* ctl;                     // chain_persist_ctl_bytes, zeroed once when the chain plan is made
-    int grid, bw; size_t smem;
+    int grid, bw, wdtype; size_t smem;
     size_t smem_copy;                  // > 0: LDS size with the first layer's x copied into LDS whole (used if x is 16-byte aligned)
     void* stream;
 };

@@ -22,7 +22,9 @@
 // The per-layer body is the batch-1 vector kernel: 16-byte coalesced stream of
 // BRC tile rows, x-segments staged in LDS, DPP lane reduction, LDS wave
 // reduction, bias, activation, store through the composed boundary array.
-// Restricted to fp32 BRC plans with whole block rows per work item.
+// Restricted to BRC plans of one weight type with whole block rows per work
+// item, batch 1; an fp16 chain rounds an intermediate to fp16 once, at the
+// producer's store, as the launch-per-layer form does.
 #include "pivot_fc_kernels.h"
 
 namespace pivot {
@@ -38,10 +40,10 @@ constexpr uint32_t kChainSpinLimit = 1u << 18;
 struct ChainLayer {
     const int4*    chunks;      // eight ints per chunk (irregular schedules)
     const int32_t* xidx;        // gather index of every kept tile's columns
-    const float*   vals;
+    const void*    vals;        // tile values of the plans' weight type
     const float*   bias_p;
     const int32_t* dst;         // block-space row -> position in `out`, -1 = not stored
-    const void*    in;          // layer 0: float x in natural order; later layers: pairs in this layer's block order
+    const void*    in;          // layer 0: x (weight type) in natural order; later layers: pairs in this layer's block order
     void*          out;         // pairs in the next layer's block order; last layer: float y
     int nitems, slices, bhs, bh_full, uniform_ct, uniform_parts, chunk_tiles, act, k_valid;
     int xn_vecs;                // first layer, kInCopy: 16-byte vectors of x
@@ -87,11 +89,11 @@ __device__ __forceinline__ bool chain_keep_waiting(uint32_t* ctl, uint32_t& spin
 // The first layer (usually the long one) fetches eight gather indices per thread up front, so that up to 4096
 // staged elements need one round of dependent loads.
 enum { kInPlain = 0, kInTagged = 1, kInCopy = 2 };
-template <int BH, int BW, int NW, int XIN>
+template <typename WT, int BH, int BW, int NW, int XIN>
 __device__ __forceinline__ void chain_item(const ChainLayer& P, int item, bool out_tagged,
                                            uint32_t tag, uint32_t counter, uint32_t* s_tag, uint32_t* ctl, char* smem) {
-    using V = f32x4;
-    constexpr int VEC = 4;
+    using V = typename Elem<WT>::vec;
+    constexpr int VEC = Elem<WT>::VEC;
     constexpr int NT  = NW * 64;
     constexpr int LPR = BW / VEC;
     constexpr int RPW = 64 / LPR;
@@ -103,12 +105,12 @@ __device__ __forceinline__ void chain_item(const ChainLayer& P, int item, bool o
     static_assert(BH <= NT, "one thread per output row");
 
     // LDS: [copy of x + a dump vector (kInCopy)][staged x-segments]; the sums reuse it afterwards
-    float* xn  = reinterpret_cast<float*>(smem);
-    float* xs  = (XIN == kInCopy) ? xn + (size_t)P.xn_vecs * VEC + VEC : xn;
+    WT* xn  = reinterpret_cast<WT*>(smem);
+    WT* xs  = (XIN == kInCopy) ? xn + (size_t)P.xn_vecs * VEC + VEC : xn;
     float* red = reinterpret_cast<float*>(smem);        // reused after the stream phase
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    XRes<float, 1, NT, 16> xres;
+    XRes<WT, 1, NT, 16> xres;
     if constexpr (XIN == kInCopy) xres.load(1, 0, P.xn_vecs, P.in, 0, tid);
     const int chunk = item / P.slices, slice = item - chunk * P.slices;
     int br, tile_begin, ntiles;
@@ -135,7 +137,7 @@ __device__ __forceinline__ void chain_item(const ChainLayer& P, int item, bool o
     const int ts = (TPL > 1) ? s / BH : 0;
     const size_t gstride = (size_t)TPL * tile_elems;
     const int lane_off = (TPL > 1) ? ts * tile_elems + (s % BH) * BW + cg * VEC : lane * VEC;
-    const float* vbase = P.vals + (size_t)tile_begin * tile_elems + (size_t)slice * BH * BW + lane_off;
+    const WT* vbase = reinterpret_cast<const WT*>(P.vals) + (size_t)tile_begin * tile_elems + (size_t)slice * BH * BW + lane_off;
     V w[U][NL];
     #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -157,14 +159,14 @@ __device__ __forceinline__ void chain_item(const ChainLayer& P, int item, bool o
     }
     auto stage = [&](int e0) {
         if constexpr (!IN_TAGGED) {
-            const float* x = (XIN == kInCopy) ? xn : reinterpret_cast<const float*>(P.in);
-            float v[XP];
+            const WT* x = (XIN == kInCopy) ? xn : reinterpret_cast<const WT*>(P.in);
+            WT v[XP];
             #pragma unroll
             for (int k = 0; k < XP; ++k) v[k] = x[src[k] > 0 ? src[k] : 0];
             #pragma unroll
             for (int k = 0; k < XP; ++k) {
                 const int e = e0 + k * NT;
-                xs[e < ne ? e : dump] = (src[k] >= 0) ? v[k] : 0.f;
+                xs[e < ne ? e : dump] = (src[k] >= 0) ? v[k] : WT(0);
             }
         } else {
             const unsigned long long* xp = reinterpret_cast<const unsigned long long*>(P.in);
@@ -187,7 +189,7 @@ __device__ __forceinline__ void chain_item(const ChainLayer& P, int item, bool o
             for (int k = 0; k < XP; ++k) {
                 const int e = e0 + k * NT;
                 const bool real = src[k] >= 0 && src[k] < P.k_valid;    // padding columns read as zero
-                xs[e < ne ? e : dump] = real ? __uint_as_float((uint32_t)pv[k]) : 0.f;
+                xs[e < ne ? e : dump] = real ? WT(__uint_as_float((uint32_t)pv[k])) : WT(0);
             }
         }
     };
@@ -251,8 +253,10 @@ __device__ __forceinline__ void chain_item(const ChainLayer& P, int item, bool o
         float sum = 0.f;
         #pragma unroll
         for (int wv = 0; wv < NW; ++wv) sum += red[wv * BH + tid];
-        const float v = apply_act(sum + bias, P.act);
+        float v = apply_act(sum + bias, P.act);
         if (dst >= 0) {
+            // an intermediate of an fp16 chain is rounded to fp16 once, here (the pair carries it as a float)
+            if (out_tagged && sizeof(WT) == 2) v = (float)(_Float16)v;
             if (out_tagged)
                 cst64(reinterpret_cast<unsigned long long*>(P.out) + dst,
                       ((unsigned long long)tag << 32) | (unsigned long long)__float_as_uint(v));
@@ -267,9 +271,9 @@ __device__ __forceinline__ void chain_item(const ChainLayer& P, int item, bool o
 // wave (14 dwords), so the first loads of the launch do not wait for a fetch of the argument block.
 // q0_ct_parts = uniform_ct | uniform_parts << 16; q0_shape = slices | bhs << 8 | bh_full << 16;
 // q0_chunk_tiles = chunk_tiles | xn_vecs << 16 (xn_vecs > 0: copy x into LDS first).
-template <int BW>
+template <typename WT, int BW>
 __global__ void __launch_bounds__(kChainNW * 64) mlp_persist_kernel(
-        const int32_t* __restrict__ p0_xidx, const float* __restrict__ p0_vals, const void* __restrict__ p0_in,
+        const int32_t* __restrict__ p0_xidx, const void* __restrict__ p0_vals, const void* __restrict__ p0_in,
         const float* __restrict__ p0_bias, const int32_t* __restrict__ p0_dst,
         int q0_ct_parts, int q0_shape, int q0_chunk_tiles, int q0_nitems, ChainArgs A) {
     extern __shared__ __align__(16) char smem[];
@@ -294,24 +298,24 @@ __global__ void __launch_bounds__(kChainNW * 64) mlp_persist_kernel(
         uint32_t* st = have_tag ? nullptr : &s_tag;
         if (in_tagged) {
             switch (P.bhs) {
-                case 8:  chain_item<8,  BW, kChainNW, kInTagged>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
-                case 16: chain_item<16, BW, kChainNW, kInTagged>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
-                case 32: chain_item<32, BW, kChainNW, kInTagged>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
-                default: chain_item<64, BW, kChainNW, kInTagged>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
+                case 8:  chain_item<WT, 8,  BW, kChainNW, kInTagged>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
+                case 16: chain_item<WT, 16, BW, kChainNW, kInTagged>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
+                case 32: chain_item<WT, 32, BW, kChainNW, kInTagged>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
+                default: chain_item<WT, 64, BW, kChainNW, kInTagged>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
             }
         } else if (P.xn_vecs > 0) {
             switch (P.bhs) {
-                case 8:  chain_item<8,  BW, kChainNW, kInCopy>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
-                case 16: chain_item<16, BW, kChainNW, kInCopy>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
-                case 32: chain_item<32, BW, kChainNW, kInCopy>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
-                default: chain_item<64, BW, kChainNW, kInCopy>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
+                case 8:  chain_item<WT, 8,  BW, kChainNW, kInCopy>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
+                case 16: chain_item<WT, 16, BW, kChainNW, kInCopy>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
+                case 32: chain_item<WT, 32, BW, kChainNW, kInCopy>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
+                default: chain_item<WT, 64, BW, kChainNW, kInCopy>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
             }
         } else {
             switch (P.bhs) {
-                case 8:  chain_item<8,  BW, kChainNW, kInPlain>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
-                case 16: chain_item<16, BW, kChainNW, kInPlain>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
-                case 32: chain_item<32, BW, kChainNW, kInPlain>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
-                default: chain_item<64, BW, kChainNW, kInPlain>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
+                case 8:  chain_item<WT, 8,  BW, kChainNW, kInPlain>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
+                case 16: chain_item<WT, 16, BW, kChainNW, kInPlain>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
+                case 32: chain_item<WT, 32, BW, kChainNW, kInPlain>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
+                default: chain_item<WT, 64, BW, kChainNW, kInPlain>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
             }
         }
         if (!have_tag) {                                // s_tag was set inside the item, before its last barriers
@@ -335,11 +339,19 @@ __global__ void __launch_bounds__(kChainNW * 64) mlp_persist_kernel(
     }
 }
 
-const void* chain_kernel_for(int bw) {
+const void* chain_kernel_for(int wdtype, int bw) {
+    if (wdtype == PIVOT_F32) {
+        switch (bw) {
+            case 16: return reinterpret_cast<const void*>(&mlp_persist_kernel<float, 16>);
+            case 32: return reinterpret_cast<const void*>(&mlp_persist_kernel<float, 32>);
+            case 64: return reinterpret_cast<const void*>(&mlp_persist_kernel<float, 64>);
+            default: return nullptr;
+        }
+    }
     switch (bw) {
-        case 16: return reinterpret_cast<const void*>(&mlp_persist_kernel<16>);
-        case 32: return reinterpret_cast<const void*>(&mlp_persist_kernel<32>);
-        case 64: return reinterpret_cast<const void*>(&mlp_persist_kernel<64>);
+        case 16: return reinterpret_cast<const void*>(&mlp_persist_kernel<_Float16, 16>);
+        case 32: return reinterpret_cast<const void*>(&mlp_persist_kernel<_Float16, 32>);
+        case 64: return reinterpret_cast<const void*>(&mlp_persist_kernel<_Float16, 64>);
         default: return nullptr;
     }
 }
@@ -359,23 +371,24 @@ bool chain_persist_supported(const std::vector<const HostPlan*>& layers, int dev
     auto no = [&](const char* m) { if (why) *why = m; return false; };
     const int Lc = (int)layers.size();
     if (Lc < 2 || Lc > kMaxChainLayers) return no("2..8 layers");
-    const int bw = layers[0]->d.bw;
-    if (!chain_kernel_for(bw)) return no("tile width 16, 32 or 64");
+    const int bw = layers[0]->d.bw, wdtype = layers[0]->d.wdtype;
+    const int es = elem_size(wdtype), vec = 16 / es;
+    if (!chain_kernel_for(wdtype, bw)) return no("tile width 16, 32 or 64");
     int G = 0;
     size_t smem = 0;
     for (const HostPlan* hp : layers) {
-        if (hp->d.wdtype != PIVOT_F32 || hp->d.layout != PIVOT_BRC) return no("fp32 BRC plans only");
+        if (hp->d.wdtype != wdtype || hp->d.layout != PIVOT_BRC) return no("BRC plans of one weight type only");
         if (hp->d.bw != bw) return no("one tile width for all layers");
         if (hp->max_parts > 1) return no("whole block rows per work item only");
         const int sl = chain_slices(*hp);
         const int bhs = hp->d.bh / sl;
         if (bhs != 8 && bhs != 16 && bhs != 32 && bhs != 64) return no("row slices of 8, 16, 32 or 64 rows");
-        if (bw / 4 > 64 || hp->d.bh > 64) return no("tile shape");
+        if (bw < vec || bw / vec > 64 || hp->d.bh > 64) return no("tile shape");
         const long long items = (long long)hp->nchunks * sl;
         if (items > kChainMaxGrid) return no("more work items than the one-launch form takes");
         G = std::max(G, (int)items);
         const int ct = hp->uniform_ct > 0 ? hp->uniform_ct : hp->chunk_tiles;
-        smem = std::max(smem, ((size_t)ct * bw + 4) * 4);
+        smem = std::max(smem, ((size_t)ct * bw + vec) * es);
         smem = std::max(smem, (size_t)kChainNW * bhs * 4);
     }
     smem = align_up(smem, 16);
@@ -385,16 +398,16 @@ bool chain_persist_supported(const std::vector<const HostPlan*>& layers, int dev
     {
         const HostPlan& f = *layers[0];
         const int ct = f.uniform_ct > 0 ? f.uniform_ct : f.chunk_tiles;
-        const size_t need = ((size_t)f.d.K + 4) * 4 + ((size_t)ct * bw + 4) * 4;
-        const size_t item_bytes = (size_t)ct * (f.d.bh / chain_slices(f)) * bw * 4;   // same threshold as the layer kernel
+        const size_t need = ((size_t)f.d.K + vec) * es + ((size_t)ct * bw + vec) * es;
+        const size_t item_bytes = (size_t)ct * (f.d.bh / chain_slices(f)) * bw * es;  // same threshold as the layer kernel
         // worth it when the element gather would move at least twice the bytes of the copy (a cache line per element)
-        if (item_bytes >= 48 * 1024 && (size_t)ct * bw * 128 >= 2 * (size_t)f.d.K * 4 && f.d.K % 4 == 0 &&
-            f.d.K / 4 <= 16 * kChainNW * 64 && need <= 150 * 1024)
+        if (item_bytes >= 48 * 1024 && (size_t)ct * bw * 128 >= 2 * (size_t)f.d.K * es && f.d.K % vec == 0 &&
+            f.d.K / vec <= 16 * kChainNW * 64 && need <= 150 * 1024)
             smem_copy = align_up(std::max(need, smem), 16);
     }
     if (device >= 0) {
         int per_cu = 0, cus = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, chain_kernel_for(bw), kChainNW * 64, smem) != hipSuccess ||
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, chain_kernel_for(wdtype, bw), kChainNW * 64, smem) != hipSuccess ||
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess) {
             (void)hipGetLastError();
             return no("occupancy query failed");
@@ -423,7 +436,7 @@ int launch_chain_persist(const ChainPersistLaunch& C) {
         ChainLayer& P = A.L[l];
         const int sl = chain_slices(hp);
         P.chunks = reinterpret_cast<const int4*>(s.chunks);
-        P.xidx = s.xidx; P.vals = reinterpret_cast<const float*>(s.vals); P.bias_p = s.bias_p; P.dst = s.dst;
+        P.xidx = s.xidx; P.vals = s.vals; P.bias_p = s.bias_p; P.dst = s.dst;
         P.in = s.in; P.out = s.out;
         P.nitems = hp.nchunks * sl; P.slices = sl; P.bhs = hp.d.bh / sl; P.bh_full = hp.d.bh;
         P.uniform_ct = hp.uniform_ct; P.uniform_parts = hp.uniform_parts;
@@ -432,15 +445,15 @@ int launch_chain_persist(const ChainPersistLaunch& C) {
     }
     size_t smem = C.smem;
     if (C.smem_copy > 0 && (reinterpret_cast<uintptr_t>(A.L[0].in) & 15) == 0) {
-        A.L[0].xn_vecs = C.layers[0].hp->d.K / 4;
+        A.L[0].xn_vecs = C.layers[0].hp->d.K / (16 / elem_size(C.wdtype));
         smem = C.smem_copy;
         if (smem > 64 * 1024) {                         // more than 64 KB of dynamic LDS has to be allowed per kernel and device
-            static size_t allowed[16][3] = {};
+            static size_t allowed[16][6] = {};
             int dev = 0;
             HIP_TRY(hipGetDevice(&dev));
-            size_t& a = allowed[dev & 15][C.bw == 16 ? 0 : (C.bw == 32 ? 1 : 2)];
+            size_t& a = allowed[dev & 15][(C.wdtype == PIVOT_F32 ? 0 : 3) + (C.bw == 16 ? 0 : (C.bw == 32 ? 1 : 2))];
             if (smem > a) {
-                HIP_TRY(hipFuncSetAttribute(chain_kernel_for(C.bw), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+                HIP_TRY(hipFuncSetAttribute(chain_kernel_for(C.wdtype, C.bw), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
                 a = smem;
             }
         }
@@ -448,12 +461,12 @@ int launch_chain_persist(const ChainPersistLaunch& C) {
     hipStream_t st = reinterpret_cast<hipStream_t>(C.stream);
     const ChainLayer& F = A.L[0];
     if (F.uniform_ct > 0xFFFF || F.uniform_parts > 0x7FFF || F.chunk_tiles > 0xFFFF || F.xn_vecs > 0x7FFF) { set_error("first layer outside the packed arguments"); return PIVOT_E_UNSUPPORTED; }
-    const int32_t* p0_xidx = F.xidx; const float* p0_vals = F.vals; const void* p0_in = F.in;
+    const int32_t* p0_xidx = F.xidx; const void* p0_vals = F.vals; const void* p0_in = F.in;
     const float* p0_bias = F.bias_p; const int32_t* p0_dst = F.dst;
     int q0_ct_parts = F.uniform_ct | (F.uniform_parts << 16), q0_shape = F.slices | (F.bhs << 8) | (F.bh_full << 16);
     int q0_chunk_tiles = F.chunk_tiles | (F.xn_vecs << 16), q0_nitems = F.nitems;
     void* args[] = {&p0_xidx, &p0_vals, &p0_in, &p0_bias, &p0_dst, &q0_ct_parts, &q0_shape, &q0_chunk_tiles, &q0_nitems, &A};
-    HIP_TRY(hipLaunchKernel(chain_kernel_for(C.bw), dim3(C.grid), dim3(kChainNW * 64), args, smem, st));
+    HIP_TRY(hipLaunchKernel(chain_kernel_for(C.wdtype, C.bw), dim3(C.grid), dim3(kChainNW * 64), args, smem, st));
     return PIVOT_OK;
 }
 

@@ -94,17 +94,19 @@ def test_config4_full(eliminated):
 @pytest.mark.parametrize("eliminated", [False, True])
 @pytest.mark.parametrize("bh,bw,dims", [(32, 32, (300, 200, 136, 70)), (16, 16, (100, 90, 50)), (8, 64, (260, 72, 40, 24, 130)),
                                         (64, 16, (150, 190, 64)), (16, 32, (96, 64, 48))])
-def test_one_launch_chain_fp32_batch1(eliminated, bh, bw, dims):
-    # fp32 chains whose work items are whole block rows run at batch 1 in ONE launch: intermediates travel as
+@pytest.mark.parametrize("wdtype", [WL.F32, WL.F16])
+def test_one_launch_chain_batch1(wdtype, eliminated, bh, bw, dims):
+    # chains whose work items are whole block rows run at batch 1 in ONE launch: intermediates travel as
     # (value, launch tag) pairs.  Ragged M and K (padding rows are never stored, padding columns never waited
     # for), several tile shapes, 2 to 5 layers, both boundary variants, five launches in a row (a tag per launch)
-    probs = WL.config4(seed=21 + bh, dims=dims, eliminated=eliminated, bh=bh, bw=bw, frac=0.4)
+    probs = WL.config4(seed=21 + bh, dims=dims, eliminated=eliminated, bh=bh, bw=bw, frac=0.4, wdtype=wdtype)
     _check_chain(probs, want_one_launch=True, repeats=5)
     _check_chain(probs, flags=B.PIVOT_MLP_KEEP_FINAL_BLOCK_ORDER, want_one_launch=True)
     y1 = _run_chain(probs, want_one_launch=True)
     y2 = _run_chain(probs, flags=B.PIVOT_MLP_LAUNCH_PER_LAYER, want_one_launch=False)
-    outs, scales, chain = O.oracle_mlp(_layers(probs), probs[0].x, return_all=True)
-    assert O.max_scaled_error(y1, y2, chain[-1]) <= 2 * G.TOL[WL.F32]
+    bd = np.float16 if wdtype == WL.F16 else None
+    outs, scales, chain = O.oracle_mlp(_layers(probs), probs[0].x, boundary_dtype=bd, return_all=True)
+    assert O.max_scaled_error(y1, y2, chain[-1]) <= 2 * G.TOL[wdtype]
 
 
 def test_one_launch_chain_long_first_input_copied_into_lds():
@@ -181,10 +183,9 @@ def test_one_launch_chain_degenerate_layers():
 
 
 def test_one_launch_chain_falls_back():
-    # split block rows, fp16 plans and batch > 1 keep one launch per layer
+    # split block rows and batch > 1 keep one launch per layer
     probs = WL.config4(seed=30, dims=(200, 96, 128), eliminated=False, frac=0.6)
     _check_chain(probs, chunk_tiles=1, want_one_launch=False)
-    _check_chain(WL.config4(seed=31, dims=(200, 96, 128), wdtype=WL.F16), want_one_launch=False)
     probs3 = WL.config4(seed=32, batch=3, dims=(200, 96, 128))
     _check_chain(probs3)                                  # one_launch plan, batch 3: per-layer launches
     wide = WL.config4(seed=36, dims=(64, 40000, 32), frac=0.5)
