@@ -232,6 +232,24 @@ def test_gather_through_lds_copy_of_x_equals_gather_from_global(wdtype, bh, bw, 
     assert O.max_scaled_error(outs[0], y_ref, D) <= G.TOL[p.wdtype]
 
 
+@pytest.mark.parametrize("wdtype,K", [(WL.F32, 20000), (WL.F16, 40000), (WL.F32, 25088)])
+def test_long_input_copied_into_lds_beyond_64_kb(wdtype, K):
+    # an x of 80-100 KB: up to 16 vectors per thread, more than 64 KB of LDS per workgroup (allowed per kernel),
+    # eight gather indices per thread up front; same bits as the element gather from global memory
+    p = WL.gen_fc(96, K, 32, 32, 0.12, seed=41, wdtype=wdtype, act=WL.ACT_RELU)
+    outs = []
+    for flags in (B.PIVOT_PLAN_GATHER_FROM_LDS_COPY, B.PIVOT_PLAN_GATHER_FROM_GLOBAL):
+        plan = G.dev_plan(p, flags=flags)
+        try:
+            outs.append(G.run_fc(plan, p))
+        finally:
+            B.pivot_fc_plan_destroy(plan)
+    assert outs[0].tobytes() == outs[1].tobytes()
+    y_ref, D = G.oracle_of(p)
+    assert O.max_scaled_error(outs[0], y_ref, D) <= G.TOL[p.wdtype]
+    G.check_fc(p)
+
+
 def test_lds_copy_of_x_with_odd_row_length_and_offset_pointer():
     # K = 203 (not a multiple of 4) and an x that starts 4 bytes past a 16-byte boundary: the kernel must fall
     # back to the global gather on its own, with the same result
