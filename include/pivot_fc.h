@@ -87,13 +87,15 @@ typedef struct pivot_fc_desc {
     int32_t flags;        /* PIVOT_PLAN_* bits, 0 = defaults                             */
 } pivot_fc_desc;
 
-/* The vector kernel (batch <= 4) has two forms of the column gather: each
- * gathered element a dependent load x[index] from global memory, or the whole
- * of x first copied into LDS with loads that depend on nothing and the gather
- * run from there (possible when x is small enough: rows of 16-byte vectors, at
- * most 8 vectors per thread, 64 KB of LDS).  By default the library takes the
- * second form when it is possible and a work item streams 48 KB of weights or
- * more.  These bits force the first form, or the second whenever possible.   */
+/* The layer kernels have two forms of the column gather: each gathered
+ * element a dependent load x[index] from global memory, or the whole of x
+ * first copied into LDS with loads that depend on nothing and the gather run
+ * from there (possible when x is small enough: rows of 16-byte vectors, at
+ * most 8 vectors per thread and 64 KB of LDS; at batch 1 up to 16 vectors per
+ * thread and 150 KB when every work item has a compute unit of its own).  By
+ * default the library takes the second form when it is possible and a work
+ * item streams 48 KB of weights or more.  These bits force the first form, or
+ * the second whenever possible.                                               */
 #define PIVOT_PLAN_GATHER_FROM_GLOBAL 1
 #define PIVOT_PLAN_GATHER_FROM_LDS_COPY 4
 /* pivot_lstm_run normally runs the whole sequence in one launch when the plan
@@ -181,8 +183,10 @@ int    pivot_workspace_init(void* ws_dev, size_t ws_bytes, void* stream);
  *   x_dev  device, [batch][K] of wdtype, row stride ldx elements, natural coordinates
  *   y_dev  device, [batch][M] fp32, row stride ldy elements, natural coordinates
  *   batch  1..64.  F16 plans whose tiles fit an MFMA shape use the matrix
- *          cores from batch 8 on; that path first copies x into block order
- *          (one small extra kernel) and reads it from there.
+ *          cores from batch 3 on: fed from x-segments staged in LDS while a
+ *          work item stages at most 4096 elements of x (always at batch 3-4),
+ *          else (batch >= 8) from a copy of x in block order made by one small
+ *          extra kernel.
  */
 int  pivot_fc_run(const pivot_fc_plan_t* plan, const void* x_dev, int64_t ldx,
                   void* y_dev, int64_t ldy, int batch,
