@@ -282,3 +282,26 @@ def test_lstm_one_launch_agrees_with_launch_per_step():
 def test_lstm_config5_full(per_step):
     lp = WL.config5(seed=0)
     _check_lstm_steps(lp, record=(0, 1, 17, 255), tol=2e-3, per_step=per_step)
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_random_chains_match_the_oracle(seed):
+    # depth, widths, tile shape, weight type, batch, boundary variant, flags and chunking drawn together; whichever
+    # form the library picks (one launch or one launch per layer) has to agree with the oracle
+    rng = np.random.default_rng(seed)
+    for it in range(12):
+        depth = int(rng.integers(1, 6))
+        bh = int(rng.choice([8, 16, 32, 64]))
+        bw = int(rng.choice([8, 16, 32, 64]))
+        dims = tuple(int(rng.integers(1, 500)) for _ in range(depth + 1))
+        wdtype = WL.F32 if rng.random() < 0.5 else WL.F16
+        batch = int(rng.choice([1, 1, 1, 2, 4, 9]))
+        elim = bool(rng.random() < 0.5)
+        flags = int(rng.choice([0, 0, B.PIVOT_MLP_KEEP_FINAL_BLOCK_ORDER, B.PIVOT_MLP_LAUNCH_PER_LAYER]))
+        ct = int(rng.choice([0, 0, 1, 3]))
+        frac = float(rng.choice([0.2, 0.5, 1.0]))
+        print("chain dims %s tiles %dx%d %s batch %d eliminated=%s flags %d chunk_tiles %d kept %.1f"
+              % (dims, bh, bw, wdtype, batch, elim, flags, ct, frac), flush=True)
+        probs = WL.config4(seed=700 + 20 * seed + it, batch=batch, dims=dims, eliminated=elim, wdtype=wdtype,
+                           bh=bh, bw=bw, frac=frac)
+        _check_chain(probs, flags=flags, chunk_tiles=ct)
