@@ -254,7 +254,9 @@ def test_lstm_small(batch, per_step):
     assert dh < 0.05 and dc < 0.05
 
 
-@pytest.mark.parametrize("H,I,batch,frac", [(96, 40, 3, 0.3), (256, 128, 16, 0.2), (80, 8, 5, 1.0)])
+@pytest.mark.parametrize("H,I,batch,frac", [(96, 40, 3, 0.3), (256, 128, 16, 0.2), (80, 8, 5, 1.0),
+                                             (1024, 512, 8, 0.8),     # 10 tiles per wavefront: the 16-slot kernel
+                                             (512, 256, 4, 0.5)])     # fewer workgroups than compute units
 def test_lstm_one_launch_ragged_shapes(H, I, batch, frac):
     # K = H+I not a multiple of the tile width (padding columns), empty and split block rows, every tile kept
     lp = WL.config5(seed=5, batch=batch, H=H, I=I, steps=9, frac=frac)
