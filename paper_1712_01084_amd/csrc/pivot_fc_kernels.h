@@ -445,23 +445,35 @@ __global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(PIVOT_GEMV_PARAMS, FcA
     // sits between the loads and the compiler can wait for exactly the ones it needs.
     const int gmax = ngroups > 0 ? ngroups - 1 : 0;
     V w[U][NL];
-    auto issue = [&](int g0) {
+    auto issue = [&](int g0, int u0, int u1) {
         #pragma unroll
         for (int u = 0; u < U; ++u) {
+            if (u < u0 || u >= u1) continue;
             const int g = g0 + u * NW;
             const int gc = g < gmax ? g : gmax;
             #pragma unroll
             for (int j = 0; j < NL; ++j) w[u][j] = load16<V>(vbase + gc * gstride + j * 64 * VEC);
         }
     };
-
-    issue(wave);
+    // The forms that request the copy of x first (XR >= 2) put it into LDS after HALF of the first weight loads
+    // have been issued and issue the other half behind that: issuing a wave's loads takes over a microsecond
+    // (the memory pipeline takes 64 bytes per clock from the whole compute unit), and x, requested first, is
+    // back long before; the regular form keeps everything in one burst (measured: config 4 layer 1 10.3 ->
+    // 9.95 us, config 3 dense 9.4 -> 9.3 us cold; the regular form on config 2 would lose 0.06 us).
+    constexpr int UH = (XR >= 2 && U >= 2) ? U / 2 : U;
+    issue(wave, 0, UH);
+    if constexpr (UH < U) {
+        __builtin_amdgcn_sched_barrier(0);
+        xres.store(q_batch, q_xn_vecs, xn, b0, tid);
+        __builtin_amdgcn_sched_barrier(0);
+        issue(wave, UH, U);
+    }
     RowPre<BH, N, NT> rp;
     rp.load(p_bias, p_scatter, row0, tid);
     // every load above is issued before anything below waits for one of them
     __builtin_amdgcn_sched_barrier(0);
     if constexpr (XR != 0) {
-        xres.store(q_batch, q_xn_vecs, xn, b0, tid);
+        if constexpr (UH == U) xres.store(q_batch, q_xn_vecs, xn, b0, tid);
         lds_barrier();
         xst.template gather<true>(q_batch, q_ldx, q_xn_vecs * VEC, q_xs_stride, p_idx, xn, xs, tile_begin, ntiles * BW, b0, tid);
     } else {

@@ -139,12 +139,24 @@ __device__ __forceinline__ void chain_item(const ChainLayer& P, int item, bool o
     const int lane_off = (TPL > 1) ? ts * tile_elems + (s % BH) * BW + cg * VEC : lane * VEC;
     const WT* vbase = reinterpret_cast<const WT*>(P.vals) + (size_t)tile_begin * tile_elems + (size_t)slice * BH * BW + lane_off;
     V w[U][NL];
-    #pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const int g = wave + u * NW;
-        const int gc = g < gmax ? g : gmax;
+    auto issue = [&](int u0, int u1) {
         #pragma unroll
-        for (int j = 0; j < NL; ++j) w[u][j] = load16<V>(vbase + gc * gstride + j * 64 * VEC);
+        for (int u = 0; u < U; ++u) {
+            if (u < u0 || u >= u1) continue;
+            const int g = wave + u * NW;
+            const int gc = g < gmax ? g : gmax;
+            #pragma unroll
+            for (int j = 0; j < NL; ++j) w[u][j] = load16<V>(vbase + gc * gstride + j * 64 * VEC);
+        }
+    };
+    // with a copy of x: into LDS after half of the first weight loads, the other half behind it (see fc_gemv_kernel)
+    constexpr int UH = (XIN == kInCopy && U >= 2) ? U / 2 : U;
+    issue(0, UH);
+    if constexpr (UH < U) {
+        __builtin_amdgcn_sched_barrier(0);
+        xres.store(1, P.xn_vecs, xn, 0, tid);
+        __builtin_amdgcn_sched_barrier(0);
+        issue(UH, U);
     }
     const int orow = br * P.bh_full + slice * BH + tid % BH;
     const float bias = P.bias_p[orow];
@@ -154,7 +166,7 @@ __device__ __forceinline__ void chain_item(const ChainLayer& P, int item, bool o
     // stage the x-segments: plain loads from the caller's x, or pairs re-read until they carry this launch's tag.
     // The first round stands outside the loop so that no loop header sits between its loads and the ones above.
     if constexpr (XIN == kInCopy) {
-        xres.store(1, P.xn_vecs, xn, 0, tid);
+        if constexpr (UH == U) xres.store(1, P.xn_vecs, xn, 0, tid);
         lds_barrier();
     }
     auto stage = [&](int e0) {
