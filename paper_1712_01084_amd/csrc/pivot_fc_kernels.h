@@ -763,14 +763,23 @@ __global__ void __launch_bounds__(NW * 64) fc_mfma_lds_kernel(PIVOT_GEMV_PARAMS,
             for (int ks = 0; ks < KS; ++ks)
                 w[u][rb * KS + ks] = load16<f16x8>(vbase + (size_t)tc * tile_elems + rb * MR * BW + ks * MK);
     };
+    // with a copy of x: into LDS after half of the first weight loads, the other half behind it (see fc_gemv_kernel)
+    constexpr int UH = (XR != 0 && U >= 2) ? U / 2 : U;
     #pragma unroll
-    for (int u = 0; u < U; ++u) fill(u, wave + u * NW);
+    for (int u = 0; u < UH; ++u) fill(u, wave + u * NW);
+    if constexpr (UH < U) {
+        __builtin_amdgcn_sched_barrier(0);
+        xres.store(q_batch, q_xn_vecs, xn, b0, tid);
+        __builtin_amdgcn_sched_barrier(0);
+        #pragma unroll
+        for (int u = UH; u < U; ++u) fill(u, wave + u * NW);
+    }
 
     RowPre<BH, N, NT> rp;
     rp.load(p_bias, p_scatter, row0, tid);
     __builtin_amdgcn_sched_barrier(0);                  // every load above is issued before anything below waits
     if constexpr (XR != 0) {
-        xres.store(q_batch, q_xn_vecs, xn, b0, tid);
+        if constexpr (UH == U) xres.store(q_batch, q_xn_vecs, xn, b0, tid);
         lds_barrier();
         xst.template gather<true>(q_batch, q_ldx, q_xn_vecs * VEC, q_xs_stride, p_idx, xn, xs, tile_begin, ntiles * BW, b0, tid);
     } else {

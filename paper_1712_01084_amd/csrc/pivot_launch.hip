@@ -163,7 +163,10 @@ int launch_fc(const FcLaunch& L) {
         const size_t vectors = (size_t)nbt * (xlen / vec);
         xn_bytes = (size_t)nbt * xlen * es + 16;
         if (vectors <= (size_t)8 * nw * 64 && xn_bytes + xs_bytes <= 64 * 1024 && red_bytes <= 64 * 1024) {
-            xres = a.uniform_ct > 0 ? 1 : 2;
+            // form 1 (everything requested in one burst) for regular schedules whose work item is in flight whole
+            // with the first loads (8 KB per wavefront); form 2 (x stored to LDS between the two halves of the
+            // first weight loads) for irregular schedules and for longer work items, whose refills then start sooner
+            xres = (a.uniform_ct > 0 && item_bytes <= (size_t)nw * 8 * 1024) ? 1 : 2;
         } else if (!ml && nbt == 1 && vectors <= (size_t)16 * 8 * 64 && xn_bytes + xs_bytes <= 144 * 1024 &&
                    (size_t)L.nchunks * sl <= (size_t)device_cus() &&
                    (size_t)(a.uniform_ct > 0 ? a.uniform_ct : L.chunk_tiles) * L.bw * 128 >= 2 * xn_bytes) {
