@@ -169,7 +169,7 @@ int launch_fc(const FcLaunch& L) {
             xres = (a.uniform_ct > 0 && item_bytes <= (size_t)nw * 8 * 1024) ? 1 : 2;
         } else if (!ml && nbt == 1 && vectors <= (size_t)16 * 8 * 64 && xn_bytes + xs_bytes <= 144 * 1024 &&
                    (size_t)L.nchunks * sl <= (size_t)device_cus() &&
-                   (size_t)(a.uniform_ct > 0 ? a.uniform_ct : L.chunk_tiles) * L.bw * 128 >= 2 * xn_bytes) {
+                   (L.x_resident == 2 || (size_t)(a.uniform_ct > 0 ? a.uniform_ct : L.chunk_tiles) * L.bw * 128 >= 2 * xn_bytes)) {
             // Long x (beyond 64 KB of LDS or 8 vectors per thread): 8 wavefronts hold up to 16 vectors each and
             // the workgroup takes most of the 160 KB of a compute unit, so this form is only used when every
             // work item still gets a compute unit of its own.  It replaces a gather that moves a whole cache
