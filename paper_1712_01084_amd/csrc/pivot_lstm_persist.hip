@@ -293,9 +293,13 @@ __global__ void __launch_bounds__(kNT) lstm_persist_kernel(PersistArgs a) {
         // values of a row are contiguous
         unsigned long long* pbw = a.partials + (size_t)(t % kPBuf) * pbuf;
         {
-            const int row = tid / a.batch, n = tid - row * a.batch;
-            if (row < 16) {
-                for (int s = 0; s < nseg; ++s) {
+            // 16 * batch threads per segment; the thread groups take the segments in turn (a workgroup whose
+            // tiles are many short block rows has a dozen segments, and the slowest workgroup sets the step)
+            const int per = 16 * a.batch, ngrp = kNT / per;
+            const int grp = tid / per, rest = tid - grp * per;
+            const int row = rest / a.batch, n = rest - row * a.batch;
+            if (grp < ngrp) {
+                for (int s = grp; s < nseg; s += ngrp) {
                     const int sb = s_seg_b[s], se = s_seg_e[s];
                     float sum = 0.f;
                     #pragma unroll
