@@ -267,11 +267,24 @@ __global__ void __launch_bounds__(kNT) lstm_persist_kernel(PersistArgs a) {
                 else       xb[i] = f16x8(0);
             }
             wait_frags<LMAX>(xb);
-            bool bad = false;
+            // fragments of other producers may still be missing: only those are read again (one trip per
+            // retry instead of a probe and a full read; requesting everything before the probe, for the
+            // wavefronts that arrive late, was measured slower)
+            unsigned missing = 0;
             #pragma unroll
-            for (int i = 0; i < LMAX; ++i) bad = bad || (i < L && not_yet16(xb[i]));
-            if (!bad) break;
-            if (!keep_waiting(a.ctl, spins)) { ok = 0; break; }
+            for (int i = 0; i < LMAX; ++i) missing |= (i < L && not_yet16(xb[i]) ? 1u : 0u) << i;
+            while (__any(missing != 0)) {
+                if (!keep_waiting(a.ctl, spins)) { ok = 0; break; }
+                #pragma unroll
+                for (int i = 0; i < LMAX; ++i)
+                    if (missing & (1u << i)) frag_load(xb[i], xg + (size_t)brow * a.K_pad + ci[i] * kBW + lg * 8);
+                wait_frags<LMAX>(xb);
+                unsigned still = 0;
+                #pragma unroll
+                for (int i = 0; i < LMAX; ++i) still |= ((missing >> i) & 1u) && not_yet16(xb[i]) ? (1u << i) : 0u;
+                missing = still;
+            }
+            break;
         }
         f32x4 acc = f32x4(0);
         #pragma unroll
