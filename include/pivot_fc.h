@@ -136,6 +136,14 @@ typedef struct pivot_plan_view {
     const int32_t* part_base;  /* [nbr+1] */
     const int32_t* xidx;       /* [T*bw]   xidx[t*bw+c] = pcol_pad[col_idx[t]*bw+c]: the column gather
                                   composed with the tile list, what the device reads */
+    const int32_t* xsort;      /* [T*bw] or NULL: the same gather as one list per piece (positions
+                                  [tile_begin*bw, tile_end*bw)), ordered by ascending source index, padding
+                                  columns last; entry = source | position-in-piece << 19, source field all
+                                  ones for a padding column.  Built for fp16 BRC plans whose tiles fit an
+                                  MFMA shape, K_pad < 2^19 - 1 and at most 8192 columns per piece: what the
+                                  batch 3..16 kernel reads, so that neighbouring lanes gather neighbouring
+                                  addresses */
+    const int32_t* xsort_blk;  /* same for an input already in block order (source = col_idx[t]*bw+c) */
 } pivot_plan_view;
 
 int         pivot_version(void);
@@ -183,10 +191,10 @@ int    pivot_workspace_init(void* ws_dev, size_t ws_bytes, void* stream);
  *   x_dev  device, [batch][K] of wdtype, row stride ldx elements, natural coordinates
  *   y_dev  device, [batch][M] fp32, row stride ldy elements, natural coordinates
  *   batch  1..64.  F16 plans whose tiles fit an MFMA shape use the matrix
- *          cores from batch 3 on: fed from x-segments staged in LDS while a
- *          work item stages at most 4096 elements of x (always at batch 3-4),
- *          else (batch >= 8) from a copy of x in block order made by one small
- *          extra kernel.
+ *          cores from batch 3 on: up to batch 16 fed from x-segments staged
+ *          in LDS (gathered through the plan's source-ordered lists) while
+ *          the staged rows of a work item fit in 48 KB, else (batch >= 8)
+ *          from a copy of x in block order made by one small extra kernel.
  */
 int  pivot_fc_run(const pivot_fc_plan_t* plan, const void* x_dev, int64_t ldx,
                   void* y_dev, int64_t ldy, int batch,

@@ -57,7 +57,8 @@ class pivot_plan_view(C.Structure):
                    ("invprow", C.POINTER(C.c_int32)), ("invpcol", C.POINTER(C.c_int32)),
                    ("prow_pad", C.POINTER(C.c_int32)), ("pcol_pad", C.POINTER(C.c_int32)),
                    ("chunks", C.POINTER(C.c_int32)), ("part_base", C.POINTER(C.c_int32)),
-                   ("xidx", C.POINTER(C.c_int32))])
+                   ("xidx", C.POINTER(C.c_int32)), ("xsort", C.POINTER(C.c_int32)),
+                   ("xsort_blk", C.POINTER(C.c_int32))])
 
 
 class pivot_mlp_view(C.Structure):
@@ -175,6 +176,8 @@ def pivot_fc_plan_host_view(plan):
     out["chunks"] = arr(v.chunks, v.nchunks * 4, np.int32).reshape(-1, 4)
     out["part_base"] = arr(v.part_base, v.nbr + 1, np.int32)
     out["xidx"] = arr(v.xidx, v.T * v.bw, np.int32)
+    out["xsort"] = arr(v.xsort, v.T * v.bw, np.int32) if v.xsort else None
+    out["xsort_blk"] = arr(v.xsort_blk, v.T * v.bw, np.int32) if v.xsort_blk else None
     return out
 
 

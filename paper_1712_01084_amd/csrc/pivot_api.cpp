@@ -70,6 +70,8 @@ int upload(pivot_fc_plan_t* p) {
         {h.invpcol.data(),   h.invpcol.size() * 4,          (void**)&d.invpcol},
         {h.xidx.data(),      h.xidx.size() * 4,             (void**)&d.xidx},
         {xblk.data(),        xblk.size() * 4,               (void**)&d.xidx_blk},
+        {h.xsort.data(),     h.xsort.size() * 4,            (void**)&d.xsort},
+        {h.xsort_blk.data(), h.xsort_blk.size() * 4,        (void**)&d.xsort_blk},
         {rowid.data(),       rowid.size() * 4,              (void**)&d.rowid_pad},
         {h.row_ptr.data(),   h.row_ptr.size() * 4,          (void**)&d.row_ptr},
     };
@@ -144,6 +146,7 @@ int pivot_fc_plan_host_view(const pivot_fc_plan_t* plan, pivot_plan_view* v) {
     v->bias_p = h.bias_p.data(); v->invprow = h.invprow.data(); v->invpcol = h.invpcol.data();
     v->prow_pad = h.prow_pad.data(); v->pcol_pad = h.pcol_pad.data();
     v->chunks = h.chunks.data(); v->part_base = h.part_base.data(); v->xidx = h.xidx.data();
+    v->xsort = h.sorted_ok ? h.xsort.data() : nullptr; v->xsort_blk = h.sorted_ok ? h.xsort_blk.data() : nullptr;
     return PIVOT_OK;
 }
 
@@ -206,10 +209,11 @@ int prepare(const pivot_fc_plan_t* plan, int batch, void* ws, size_t ws_bytes, F
     L.K = h.d.K; L.x_resident = (h.d.flags & PIVOT_PLAN_GATHER_FROM_GLOBAL) ? 0 : ((h.d.flags & PIVOT_PLAN_GATHER_FROM_LDS_COPY) ? 2 : 1);
     L.M_pad = h.M_pad; L.K_pad = h.K_pad; L.bh = h.d.bh; L.bw = h.d.bw; L.wdtype = h.d.wdtype; L.layout = h.d.layout; L.T = h.T; L.act = h.d.act;
     L.nchunks = h.nchunks; L.nbr = h.nbr; L.chunk_tiles = h.chunk_tiles; L.wg_waves = h.wg_waves;
+    L.lds_tiles = h.lds_tiles();
     L.row_slices = h.row_slices;
     L.uniform_ct = h.uniform_ct; L.uniform_parts = h.uniform_parts;
     L.batch = batch;
-    int nbt = fc_batch_tile(h.d.layout, h.d.wdtype, h.d.bh, h.d.bw, h.chunk_tiles, batch);
+    int nbt = fc_batch_tile(h.d.layout, h.d.wdtype, h.d.bh, h.d.bw, h.lds_tiles(), batch);
     int ngy = (batch + nbt - 1) / nbt;
     L.tickets = reinterpret_cast<uint32_t*>(ws);
     L.partials = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + fc_ticket_bytes(h.nbr, ngy, h.row_slices));
@@ -222,12 +226,12 @@ int prepare(const pivot_fc_plan_t* plan, int batch, void* ws, size_t ws_bytes, F
 int natural_input(const pivot_fc_plan_t* plan, const void* x_dev, int64_t ldx, int batch, void* xg, void* stream,
                   FcLaunch& L) {
     const HostPlan& h = plan->host;
-    if (fc_uses_matrix_cores(h.d.layout, h.d.wdtype, h.d.bh, h.d.bw, h.chunk_tiles, batch)) {
+    if (fc_uses_matrix_cores(h.d.layout, h.d.wdtype, h.d.bh, h.d.bw, h.lds_tiles(), batch)) {
         int rc = launch_gather_x(x_dev, ldx, plan->dev.pcol_pad, xg, h.K_pad, batch, h.d.wdtype, stream);
         if (rc != PIVOT_OK) return rc;
-        L.x = xg; L.ldx = h.K_pad; L.xidx = plan->dev.xidx_blk; L.x_block_order = 1;
+        L.x = xg; L.ldx = h.K_pad; L.xidx = plan->dev.xidx_blk; L.xsort = plan->host.sorted_ok ? plan->dev.xsort_blk : nullptr; L.x_block_order = 1;
     } else {
-        L.x = x_dev; L.ldx = ldx; L.xidx = plan->dev.xidx; L.x_block_order = 0;
+        L.x = x_dev; L.ldx = ldx; L.xidx = plan->dev.xidx; L.xsort = plan->host.sorted_ok ? plan->dev.xsort : nullptr; L.x_block_order = 0;
     }
     return PIVOT_OK;
 }
@@ -442,7 +446,7 @@ int pivot_mlp_run(const pivot_mlp_plan_t* plan, const void* x_dev, int64_t ldx, 
             rc = natural_input(p, x_dev, ldx, batch, ws + m.gather_off, stream, L);
             if (rc != PIVOT_OK) return rc;
         } else {
-            L.xidx = p->dev.xidx_blk; L.x = ws + m.inter_off[l - 1]; L.ldx = p->host.K_pad; L.x_block_order = 1;
+            L.xidx = p->dev.xidx_blk; L.xsort = p->host.sorted_ok ? p->dev.xsort_blk : nullptr; L.x = ws + m.inter_off[l - 1]; L.ldx = p->host.K_pad; L.x_block_order = 1;
         }
         if (l + 1 < Lc) {
             // producer-side store through the composed boundary array; identity boundaries store contiguously
@@ -552,7 +556,7 @@ int pivot_lstm_run(const pivot_fc_plan_t* plan, int H, int I, const void* xs_dev
         FcLaunch L{};
         rc = prepare(plan, batch, ws, m.scratch, L);
         if (rc != PIVOT_OK) return rc;
-        L.xidx = plan->dev.xidx_blk; L.x_block_order = 1;
+        L.xidx = plan->dev.xidx_blk; L.xsort = plan->host.sorted_ok ? plan->dev.xsort_blk : nullptr; L.x_block_order = 1;
         L.x = xg + m.xg_step * (size_t)t; L.ldx = h.K_pad;
         L.scatter = plan->dev.prow_pad;      // gates land in natural order for the cell
         L.y = z; L.ldy = h.d.M; L.out_f16 = 0; L.stream = stream;

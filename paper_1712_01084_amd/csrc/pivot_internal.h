@@ -18,6 +18,16 @@ inline int    elem_size(int wdtype) { return wdtype == PIVOT_F32 ? 4 : 2; }
 // Zero bytes kept after the tile values on the device: kernels issue clamped,
 // unconditional loads of up to one group of tiles (at most 64x64 fp32).
 constexpr size_t kValsPadBytes = 16 * 1024;
+constexpr int kSortSrcBits = 19;               // packed gather entry: source index below, staged position above
+constexpr int kSortSrcNone = (1 << kSortSrcBits) - 1;
+
+// Which MFMA shape a row-major fp16 tile feeds: 0 = 16x16x32, 1 = 32x32x16, -1 = none.
+inline int mfma_kind(int wdtype, int bh, int bw) {
+    if (wdtype != PIVOT_F16) return -1;
+    if (bw % 32 == 0 && bh % 16 == 0) return 0;
+    if (bh % 32 == 0 && bw % 16 == 0) return 1;
+    return -1;
+}
 
 // Host-side canonical arrays of one layer (what pivot_plan_view exposes).
 struct HostPlan {
@@ -28,6 +38,15 @@ struct HostPlan {
                                        // chunk is full: chunk i = tiles [i*ct, (i+1)*ct) of block row i / parts
     std::vector<int32_t> row_ptr, col_idx, invprow, invpcol, prow_pad, pcol_pad;
     std::vector<int32_t> xidx;         // T*bw: xidx[t*bw+c] = pcol_pad[col_idx[t]*bw+c]
+    // Gather lists of the LDS-fed matrix-core kernel, one per work item (chunk), at [tile_begin*bw, tile_end*bw):
+    // the chunk's staged elements e = t*bw+c ordered by ascending source index, each packed as
+    // source | e << kSortSrcBits (padding columns last, source field all ones).  Neighbouring lanes then
+    // gather from neighbouring addresses (several elements per cache line instead of one) and scatter into
+    // LDS.  xsort: source = index into a natural-order x; xsort_blk: into an x in block order.  Empty when
+    // the plan cannot take that kernel or the fields do not fit.
+    std::vector<int32_t> xsort, xsort_blk;
+    bool sorted_ok = false;
+    int lds_tiles() const { return sorted_ok ? chunk_tiles : 0; }   // what fc_path takes
     std::vector<int32_t> chunks;       // nchunks x 4
     std::vector<int32_t> part_base;    // nbr + 1
     std::vector<float>   bias_p;
@@ -49,6 +68,8 @@ struct DevPlan {
     int32_t* invpcol = nullptr;
     int32_t* xidx = nullptr;      // gather index for natural-order x
     int32_t* xidx_blk = nullptr;  // same for x already in block order: col_idx[t]*bw+c
+    int32_t* xsort = nullptr;     // packed, source-ordered gather lists (see HostPlan), natural-order x
+    int32_t* xsort_blk = nullptr; // same for x in block order
     int32_t* rowid_pad = nullptr; // [M_pad] r for r < M, -1 in padding: stores that stay in block order
     int32_t* row_ptr = nullptr;   // [nbr+1] (persistent recurrent kernel: work split and piece lookup)
 };
@@ -67,6 +88,8 @@ int  max_chunk_tiles(const pivot_fc_desc& d);
 // The library's own choice of row slices, chunk size and wavefronts per work
 // item; values given in the descriptor (non-zero) are kept.
 void choose_schedule(HostPlan& hp);
+// Fills xsort / xsort_blk from the schedule (after choose_schedule / build_schedule).
+void build_sorted_gather(HostPlan& hp);
 
 // ---- what a kernel launch sees -------------------------------------------
 struct FcLaunch {
@@ -78,8 +101,10 @@ struct FcLaunch {
     const float*   bias_p;
     const int32_t* xidx;        // [T*bw]: index into x of column c of tile t (-1 = padding): through pcol for
                                 // natural-order x, the block-space column itself for x already in block order
+    const int32_t* xsort;       // the same gather as packed source-ordered lists (LDS-fed matrix-core kernel), or NULL
     const int32_t* scatter;     // [M_pad] block-space row -> index into y (-1 = padding row, not stored)
     int M_pad, K_pad, bh, bw, wdtype, layout, T, act, nchunks, nbr, chunk_tiles, wg_waves, row_slices;
+    int lds_tiles;              // chunk_tiles if the plan carries the packed gather lists, else 0
     int uniform_ct, uniform_parts;  // > 0: regular schedule, the kernels compute the chunk descriptor
     int x_block_order;          // 1: x is [batch][K_pad] in block order (what the matrix-core kernel needs)
     int K;                      // row length of a natural-order x
@@ -96,10 +121,11 @@ struct FcLaunch {
 
 // Batch rows one launch of the layer kernel covers (grid.y repeats it).
 enum { kPathVector = 0, kPathMfmaLds = 1, kPathMfmaGather = 2 };
-int    fc_path(int layout, int wdtype, int bh, int bw, int chunk_tiles, int batch);
-int    fc_batch_tile(int layout, int wdtype, int bh, int bw, int chunk_tiles, int batch);
-bool   fc_uses_matrix_cores(int layout, int wdtype, int bh, int bw, int chunk_tiles, int batch);   // the form that needs x in block order
-int    fc_row_slices(int layout, int wdtype, int bh, int bw, int chunk_tiles, int batch, int want);
+// `lds_tiles`: HostPlan::lds_tiles() (0 rules the LDS-fed matrix-core kernel out).
+int    fc_path(int layout, int wdtype, int bh, int bw, int lds_tiles, int batch);
+int    fc_batch_tile(int layout, int wdtype, int bh, int bw, int lds_tiles, int batch);
+bool   fc_uses_matrix_cores(int layout, int wdtype, int bh, int bw, int lds_tiles, int batch);   // the form that needs x in block order
+int    fc_row_slices(int layout, int wdtype, int bh, int bw, int lds_tiles, int batch, int want);
 // Workspace of one layer application: [arrival counters][partials of split rows][x in block order (matrix path)]
 size_t fc_ticket_bytes(int nbr, int ngy, int slices);
 size_t fc_partial_bytes(const HostPlan& hp, int batch);

@@ -18,13 +18,6 @@ static int device_cus() {
     return c;
 }
 
-static int mfma_kind(int wdtype, int bh, int bw) {
-    if (wdtype != PIVOT_F16) return -1;
-    if (bw % 32 == 0 && bh % 16 == 0) return 0;
-    if (bh % 32 == 0 && bw % 16 == 0) return 1;
-    return -1;
-}
-
 // Batch rows the LDS-fed matrix-core kernel stages (4, 8 or 16).
 static int mfma_lds_rows(int batch) { return batch <= 4 ? 4 : (batch <= 8 ? 8 : 16); }
 
@@ -34,29 +27,33 @@ static int mfma_lds_rows(int batch) { return batch <= 4 ? 4 : (batch <= 8 ? 8 : 
 //   kPathMfmaGather  fp16, batch >= 8 otherwise: MFMA with B fragments read from an x in block order
 // Every work item of the LDS-fed form gathers its own x-segments for all batch rows (rows * tiles * bw
 // elements), the block-order form gathers x once in a launch of its own.  Measured (4096x4096, 64x16 tiles):
-// at batch 3-4 the LDS-fed form beats the vector kernel at every density (LDS reads per weight load 4 -> 1);
-// from batch 8 on it wins while a work item stages a few thousand elements (5 % kept, batch 8: 6.8 -> 5.1 us)
-// and loses beyond (dense, batch 8: 14.2 -> 18.6 us), so it is taken up to 4096 staged elements.
-int fc_path(int layout, int wdtype, int bh, int bw, int chunk_tiles, int batch) {
+// at batch 3-4 the LDS-fed form beats the vector kernel at every density (LDS reads per weight load 4 -> 1).
+// From batch 8 on the gather decides: read in the order of the tile list every element costs a cache line per
+// batch row, and the form lost beyond a few thousand staged elements (dense, batch 8: 14.2 -> 18.6 us); read
+// through the plan's source-ordered lists (neighbouring lanes, neighbouring addresses) it wins wherever the
+// staged rows fit in 48 KB of LDS (batch 8: 7.6 -> 5.4 us at 10 % kept, 9.8 -> 7.4 at 25 %, 12.3 -> 10.1 at
+// 50 %, 14.2 -> 12.4 dense; batch 16: 7.3 -> 6.1 at 5 %, 11.0 -> 9.5 at 25 %).  Letting it take up to 136 KB of
+// LDS (one workgroup per compute unit) for batch 16 at 50 % and dense was measured too: 13.5 -> 13.2 us and
+// 14.5 -> 15.4 us, so longer rows stay with the block-order form.
+int fc_path(int layout, int wdtype, int bh, int bw, int lds_tiles, int batch) {
     // the matrix-core kernels read A fragments from row-major (BRC) tiles only
     if (layout != PIVOT_BRC || mfma_kind(wdtype, bh, bw) < 0 || batch < 3) return kPathVector;
-    if (batch <= 16 && chunk_tiles > 0) {
+    if (batch <= 16 && lds_tiles > 0) {
         const int rows = mfma_lds_rows(batch);
-        const size_t staged = (size_t)rows * chunk_tiles * bw;
-        const size_t xs_bytes = (size_t)rows * ((size_t)chunk_tiles * bw + 8) * 2;
-        if (xs_bytes <= 48 * 1024 && (rows <= 4 || staged <= 4096)) return kPathMfmaLds;
+        const size_t xs_bytes = (size_t)rows * ((size_t)lds_tiles * bw + 8) * 2;
+        if (xs_bytes <= 48 * 1024) return kPathMfmaLds;
     }
     return batch >= 8 ? kPathMfmaGather : kPathVector;
 }
 
-bool fc_uses_matrix_cores(int layout, int wdtype, int bh, int bw, int chunk_tiles, int batch) {
-    return fc_path(layout, wdtype, bh, bw, chunk_tiles, batch) == kPathMfmaGather;
+bool fc_uses_matrix_cores(int layout, int wdtype, int bh, int bw, int lds_tiles, int batch) {
+    return fc_path(layout, wdtype, bh, bw, lds_tiles, batch) == kPathMfmaGather;
 }
 
 // Batch rows one launch row covers in the kernel's epilogue and in the workspace (grid.y repeats it).
-int fc_batch_tile(int layout, int wdtype, int bh, int bw, int chunk_tiles, int batch) {
+int fc_batch_tile(int layout, int wdtype, int bh, int bw, int lds_tiles, int batch) {
     if (layout != PIVOT_BRC) return 1;       // the column-major kernels take one batch row per launch row
-    const int path = fc_path(layout, wdtype, bh, bw, chunk_tiles, batch);
+    const int path = fc_path(layout, wdtype, bh, bw, lds_tiles, batch);
     if (path == kPathMfmaGather) return mfma_kind(wdtype, bh, bw) == 0 ? 16 : 32;
     if (path == kPathMfmaLds) return mfma_lds_rows(batch);
     return batch >= 3 ? 4 : batch;
@@ -66,14 +63,14 @@ int fc_batch_tile(int layout, int wdtype, int bh, int bw, int chunk_tiles, int b
 // slice of the vector kernel has at least 8 rows and is a whole number of 1 KB
 // wave-loads or a whole fraction of one (a wave-load then takes the same rows
 // of several consecutive tiles), a slice of the matrix kernel whole MFMA row blocks.
-int fc_row_slices(int layout, int wdtype, int bh, int bw, int chunk_tiles, int batch, int want) {
+int fc_row_slices(int layout, int wdtype, int bh, int bw, int lds_tiles, int batch, int want) {
     if (layout != PIVOT_BRC) return 1;       // a row slice is contiguous only in row-major tiles
     int sl = want < 1 ? 1 : want;
     while (sl > 1) {
         bool ok = (bh % sl == 0);
         const int bhs = bh / sl;
         if (ok) {
-            if (fc_path(layout, wdtype, bh, bw, chunk_tiles, batch) != kPathVector) {
+            if (fc_path(layout, wdtype, bh, bw, lds_tiles, batch) != kPathVector) {
                 const int mr = mfma_kind(wdtype, bh, bw) == 0 ? 16 : 32;
                 ok = (bhs % mr == 0);
             } else {
@@ -92,30 +89,30 @@ size_t fc_ticket_bytes(int nbr, int ngy, int slices) { return (size_t)4 * kTicke
 
 size_t fc_partial_bytes(const HostPlan& hp, int batch) {
     if (hp.max_parts <= 1) return 0;
-    const int nbt = fc_batch_tile(hp.d.layout, hp.d.wdtype, hp.d.bh, hp.d.bw, hp.chunk_tiles, batch);
+    const int nbt = fc_batch_tile(hp.d.layout, hp.d.wdtype, hp.d.bh, hp.d.bw, hp.lds_tiles(), batch);
     const int ngy = (batch + nbt - 1) / nbt;
     return align_up((size_t)4 * hp.nchunks * hp.d.bh * nbt * ngy, 256);
 }
 
 size_t fc_workspace_bytes(const HostPlan& hp, int batch) {
     if (batch < 1) return 0;
-    const int nbt = fc_batch_tile(hp.d.layout, hp.d.wdtype, hp.d.bh, hp.d.bw, hp.chunk_tiles, batch);
+    const int nbt = fc_batch_tile(hp.d.layout, hp.d.wdtype, hp.d.bh, hp.d.bw, hp.lds_tiles(), batch);
     const int ngy = (batch + nbt - 1) / nbt;
     // counters are sized for the plan's slice count (a launch may use fewer)
     return fc_ticket_bytes(hp.nbr, ngy, hp.row_slices) + fc_partial_bytes(hp, batch);
 }
 
 size_t fc_gather_bytes(const HostPlan& hp, int batch) {
-    if (!fc_uses_matrix_cores(hp.d.layout, hp.d.wdtype, hp.d.bh, hp.d.bw, hp.chunk_tiles, batch)) return 0;
+    if (!fc_uses_matrix_cores(hp.d.layout, hp.d.wdtype, hp.d.bh, hp.d.bw, hp.lds_tiles(), batch)) return 0;
     return align_up((size_t)batch * hp.K_pad * elem_size(hp.d.wdtype), 256);
 }
 
 int launch_fc(const FcLaunch& L) {
-    const int path = fc_path(L.layout, L.wdtype, L.bh, L.bw, L.chunk_tiles, L.batch);
+    const int path = fc_path(L.layout, L.wdtype, L.bh, L.bw, L.lds_tiles, L.batch);
     const bool mc = path == kPathMfmaGather, ml = path == kPathMfmaLds;
-    const int nbt = fc_batch_tile(L.layout, L.wdtype, L.bh, L.bw, L.chunk_tiles, L.batch);
+    const int nbt = fc_batch_tile(L.layout, L.wdtype, L.bh, L.bw, L.lds_tiles, L.batch);
     const int ngy = (L.batch + nbt - 1) / nbt;
-    const int sl = fc_row_slices(L.layout, L.wdtype, L.bh, L.bw, L.chunk_tiles, L.batch, L.row_slices);
+    const int sl = fc_row_slices(L.layout, L.wdtype, L.bh, L.bw, L.lds_tiles, L.batch, L.row_slices);
     const int bhs = L.bh / sl;
     int nw = (L.wg_waves == 16 || L.wg_waves == 8) ? L.wg_waves : 4;
     if (ml && nw > 8) nw = 8;                // the LDS-fed matrix-core kernel comes with 4 or 8 wavefronts
@@ -187,6 +184,10 @@ int launch_fc(const FcLaunch& L) {
     smem = align_up(smem > red_bytes ? smem : red_bytes, 16);
     if (smem > (size_t)(xres == 3 ? 150 : 64) * 1024) { set_error("chunk does not fit in LDS (%zu bytes)", smem); return PIVOT_E_UNSUPPORTED; }
     if (L.layout != PIVOT_BRC) return launch_colmajor(a, L.layout, L.wdtype, L.bh, L.bw, nw, grid, smem, st);
+    if (ml) {
+        if (!L.xsort) { set_error("internal: the LDS-fed matrix-core kernel needs the packed gather lists"); return PIVOT_E_UNSUPPORTED; }
+        a.xidx = L.xsort;
+    }
     if (ml) return launch_mfma_lds_f16(a, mfma_kind(L.wdtype, L.bh, L.bw), bhs, L.bw, nbt, nw, xres, grid, smem, st);
     if (L.wdtype == PIVOT_F32) return launch_gemv_f32(a, bhs, L.bw, nbt, nw, xres, grid, smem, st);
     return launch_gemv_f16(a, bhs, L.bw, nbt, nw, xres, grid, smem, st);

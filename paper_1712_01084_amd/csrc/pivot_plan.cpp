@@ -171,6 +171,40 @@ static void pack_tiles(const HostPlan& hp, const E* W, int w_space, const int32_
     }
 }
 
+// The gather lists of the LDS-fed matrix-core kernel (see HostPlan::xsort): per
+// work item, the staged positions in ascending order of the address they read.
+// Tiles of a block row are in ascending block column, so the block-order list
+// is already sorted; the natural-order list is sorted here (stable, padding last).
+void build_sorted_gather(HostPlan& hp) {
+    const pivot_fc_desc& d = hp.d;
+    hp.xsort.clear(); hp.xsort_blk.clear(); hp.sorted_ok = false;
+    if (d.layout != PIVOT_BRC || mfma_kind(d.wdtype, d.bh, d.bw) < 0) return;
+    if (hp.K_pad >= kSortSrcNone || (long long)hp.chunk_tiles * d.bw > (1ll << (32 - kSortSrcBits))) return;
+    const size_t n = (size_t)hp.T * d.bw;
+    hp.xsort.resize(n); hp.xsort_blk.resize(n);
+    std::vector<int32_t> order;
+    for (int j = 0; j < hp.nchunks; ++j) {
+        const size_t e0 = (size_t)hp.chunks[(size_t)4 * j + 1] * d.bw, e1 = (size_t)hp.chunks[(size_t)4 * j + 2] * d.bw;
+        const int ne = (int)(e1 - e0);
+        order.resize(ne);
+        std::iota(order.begin(), order.end(), 0);
+        const int32_t* src = hp.xidx.data() + e0;
+        std::stable_sort(order.begin(), order.end(), [&](int a, int b) {
+            const unsigned ka = src[a] < 0 ? 0xFFFFFFFFu : (unsigned)src[a], kb = src[b] < 0 ? 0xFFFFFFFFu : (unsigned)src[b];
+            return ka < kb;
+        });
+        for (int i = 0; i < ne; ++i) {
+            const int e = order[i];
+            const uint32_t s = src[e] < 0 ? (uint32_t)kSortSrcNone : (uint32_t)src[e];
+            hp.xsort[e0 + i] = (int32_t)(s | ((uint32_t)e << kSortSrcBits));
+            const size_t g = e0 + i;                    // block order: position i reads column col_idx[t]*bw + c
+            const uint32_t sb = (uint32_t)hp.col_idx[g / d.bw] * d.bw + (uint32_t)(g % d.bw);
+            hp.xsort_blk[g] = (int32_t)(sb | ((uint32_t)i << kSortSrcBits));
+        }
+    }
+    hp.sorted_ok = true;
+}
+
 int build_host_plan(const pivot_fc_desc& d, const void* W, int w_space, const uint8_t* tile_mask,
                     const int32_t* prow, const int32_t* pcol, const float* bias, HostPlan& hp) {
     if (!W || !tile_mask || !prow || !pcol) { set_error("W, tile_mask, prow and pcol are required"); return PIVOT_E_NULL; }
@@ -226,6 +260,7 @@ int build_host_plan(const pivot_fc_desc& d, const void* W, int w_space, const ui
             for (int c = 0; c < d.bw; ++c) hp.xidx[(size_t)t * d.bw + c] = hp.pcol_pad[(size_t)hp.col_idx[t] * d.bw + c];
 
         choose_schedule(hp);
+        build_sorted_gather(hp);
     } catch (const std::bad_alloc&) {
         set_error("out of host memory while building the plan");
         return PIVOT_E_ALLOC;

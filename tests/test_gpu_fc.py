@@ -95,6 +95,20 @@ def test_fp16_small_batches_matrix_cores_fed_from_lds(bh, bw, batch):
     G.check_fc(p, wg_waves=8, row_slices=2)
 
 
+@pytest.mark.parametrize("batch,frac", [(8, 0.3), (8, 1.0), (12, 0.6), (16, 0.3), (16, 0.1)])
+def test_fp16_batches_gather_through_source_ordered_lists(batch, frac):
+    # batch 5..16 with long work items: every thread takes several entries of the plan's source-ordered gather
+    # list, in more than one round (2040 columns, 512 or 256 threads, 4 entries per round), with padding columns
+    # at the end of the list (K is not a multiple of the tile width), whole and split block rows
+    p = WL.gen_fc(4 * 64 + 9, 2040, 64, 16, frac, seed=70 + batch, wdtype=WL.F16, batch=batch, act=WL.ACT_RELU,
+                  mask="full" if frac == 1.0 else "uniform")
+    G.check_fc(p)
+    G.check_fc(p, chunk_tiles=100, wg_waves=4, row_slices=2)
+    p = WL.gen_fc(5 * 16 + 3, 1530, 16, 32, frac, seed=90 + batch, wdtype=WL.F16, batch=batch,
+                  mask="full" if frac == 1.0 else "uniform")
+    G.check_fc(p)
+
+
 def test_degenerate_masks_and_natural_weights():
     p = WL.gen_fc(64, 96, 16, 16, 0.5, seed=9, act=WL.ACT_RELU)
     p.tile_mask[:] = 0                                   # no tile kept: y = relu(b)

@@ -101,6 +101,37 @@ def test_schedule_policy_on_the_workload_shapes():
     assert policy(WL.paper_grid_case(8192, 0.03125, seed=0, wdtype=WL.F32, perms="random"))[2] == 4   # 32 KB items
 
 
+def test_source_ordered_gather_lists():
+    # the batch 3..16 kernel's gather lists: per piece of the schedule the same (source, staged position) pairs as
+    # xidx, ordered by source with padding columns last, packed as source | position << 19; the block-order twin
+    # reads column col_idx[t]*bw+c; plans the kernel cannot take (fp32, tiles off the MFMA shapes) carry none
+    for p, ct in ((WL.config3(seed=2, M=256, K=500, frac=0.3), 3), (WL.config3(seed=3, M=128, K=512, frac=1.0), 0),
+                  (WL.gen_fc(96, 200, 16, 32, 0.4, seed=5, wdtype=WL.F16), 2),
+                  (WL.gen_fc(64, 64, 16, 32, 0.0, seed=5, wdtype=WL.F16), 0)):
+        plan = _host_plan(p, chunk_tiles=ct)
+        v = B.pivot_fc_plan_host_view(plan)
+        B.pivot_fc_plan_destroy(plan)
+        if v["T"] == 0:
+            continue                                                   # nothing to list
+        assert v["xsort"] is not None and v["xsort"].shape == v["xidx"].shape == v["xsort_blk"].shape, p.name
+        bw, none = v["bw"], (1 << 19) - 1
+        for br, tb, te, slot in v["chunks"]:
+            for packed, blk in ((v["xsort"], False), (v["xsort_blk"], True)):
+                ent = packed[tb * bw:te * bw].astype(np.int64) & 0xFFFFFFFF
+                src, pos = ent & none, ent >> 19
+                assert sorted(pos.tolist()) == list(range((te - tb) * bw)), (p.name, br)
+                assert np.all(np.diff(src) >= 0), (p.name, br)                    # padding (all ones) sorts last
+                want = (np.repeat(v["col_idx"][tb:te], bw) * bw + np.tile(np.arange(bw), te - tb)) if blk \
+                    else v["xidx"][tb * bw:te * bw]
+                want = np.where(want < 0, none, want)[pos]
+                assert np.array_equal(src, want), (p.name, br, blk)
+    for p in (WL.gen_fc(64, 64, 16, 32, 0.5, seed=1, wdtype=WL.F32), WL.gen_fc(64, 64, 8, 8, 0.5, seed=1, wdtype=WL.F16)):
+        plan = _host_plan(p, chunk_tiles=0)
+        v = B.pivot_fc_plan_host_view(plan)
+        B.pivot_fc_plan_destroy(plan)
+        assert v["xsort"] is None and v["xsort_blk"] is None
+
+
 def test_error_paths_return_codes():
     p = WL.gen_fc(16, 16, 4, 4, 0.5, seed=4)
     args = dict(M=16, K=16, bh=4, bw=4, wdtype=B.PIVOT_F32, W=p.Wp, w_space=B.PIVOT_W_PIVOTED,
