@@ -109,6 +109,21 @@ def test_fp16_batches_gather_through_source_ordered_lists(batch, frac):
     G.check_fc(p)
 
 
+def test_fp16_batches_beyond_the_gather_lists_range():
+    # 2^19 input columns and more do not fit the packed list entries: the plan carries no lists and batch 3..16
+    # falls back to the vector kernel (batch < 8) or to the block-order copy plus the matrix-core kernel
+    p = WL.gen_fc(32, (1 << 19) + 40, 32, 16, 0.002, seed=77, wdtype=WL.F16, batch=9)
+    plan = G.dev_plan(p)
+    try:
+        assert B.pivot_fc_plan_host_view(plan)["xsort"] is None
+        for batch in (4, 9):
+            y = G.run_fc(plan, p, x=p.x[:batch])
+            y_ref, D = G.oracle_of(p, x=p.x[:batch])
+            assert O.max_scaled_error(y, y_ref, D) <= G.TOL[p.wdtype], batch
+    finally:
+        B.pivot_fc_plan_destroy(plan)
+
+
 def test_degenerate_masks_and_natural_weights():
     p = WL.gen_fc(64, 96, 16, 16, 0.5, seed=9, act=WL.ACT_RELU)
     p.tile_mask[:] = 0                                   # no tile kept: y = relu(b)
