@@ -148,14 +148,20 @@ int launch_fc(const FcLaunch& L) {
     // is more than one: the kernel then derives the row stride from its preloaded arguments), a thread has to hold at
     // most 8 of them, everything fits in 64 KB of LDS, and the work item streams at least 48 KB of weights
     // (measured: below that the extra LDS pass and barrier cost 0.3 us warm and gain under 0.1 us cold;
-    // above it they gain 0.2-0.4 us cold).
+    // above it they gain 0.2-0.4 us cold).  With several batch rows the gather issues a load per element and
+    // row, so there the copy is also taken as soon as it needs no more loads than the gather would
+    // (4096x4096 fp16 at 10 % kept: batch 2 4.16 -> 4.02 us cold, batch 4 4.75 -> 4.43; at 25 %, batch 2:
+    // 5.49 -> 4.98; at 5 %, where the gather is the shorter, the copy was 0.1 us slower; warm launches pay
+    // 0.2-0.4 us for it).
     if (L.chunk_tiles > 0xFFFF || L.bh > 64 || L.batch > 64) { set_error("shape outside the vector kernel's packed arguments"); return PIVOT_E_UNSUPPORTED; }
     const int vec = 16 / es;
     const int xlen = L.x_block_order ? L.K_pad : L.K;
     int xres = 0;
     size_t xn_bytes = 0;
     const size_t item_bytes = (size_t)(a.uniform_ct > 0 ? a.uniform_ct : L.chunk_tiles) * bhs * L.bw * es;
-    if (L.layout == PIVOT_BRC && L.x_resident != 0 && (L.x_resident == 2 || item_bytes >= 48 * 1024) && xlen % vec == 0 && (nbt == 1 || L.ldx == xlen) &&
+    const size_t staged_cols = (size_t)(a.uniform_ct > 0 ? a.uniform_ct : L.chunk_tiles) * L.bw;
+    if (L.layout == PIVOT_BRC && L.x_resident != 0 &&
+        (L.x_resident == 2 || item_bytes >= 48 * 1024 || (nbt >= 2 && staged_cols * vec >= (size_t)xlen)) && xlen % vec == 0 && (nbt == 1 || L.ldx == xlen) &&
         (reinterpret_cast<uintptr_t>(L.x) & 15) == 0) {
         const size_t vectors = (size_t)nbt * (xlen / vec);
         xn_bytes = (size_t)nbt * xlen * es + 16;
