@@ -590,6 +590,11 @@ template <> struct Mfma<1> {
     }
     __device__ static __forceinline__ int row_of(int lane, int v) { return 8 * (v / 4) + 4 * (lane / 32) + (v % 4); }
 };
+// KIND 2 (LDS-fed kernel only): v_mfma_f32_16x16x32_f16 over PAIRS of consecutive 16-column tiles of a block
+// row, so that tiles 16 columns wide can still be cut into 16-row slices: lanes with k group 0-1 supply rows of
+// the pair's first tile, groups 2-3 of its second (each tile's slice is 512 contiguous bytes); the staged
+// x-segments of consecutive tiles are adjacent in LDS, so the B fragment is the same single 16-byte read.
+template <> struct Mfma<2> : Mfma<0> {};
 
 template <int KIND, int BH, int BW, int NW>
 __global__ void __launch_bounds__(NW * 64) fc_mfma_kernel(PIVOT_LEAD_PARAMS, FcArgs a) {
@@ -735,20 +740,22 @@ __global__ void __launch_bounds__(NW * 64) fc_mfma_lds_kernel(PIVOT_GEMV_PARAMS,
     using WT = _Float16;
     constexpr int VEC = 8;
     constexpr int MR = MF::MR, MK = MF::MK, CV = MF::CV;
+    constexpr bool PAIR = (KIND == 2);                  // one MFMA step spans two consecutive tiles
     constexpr int NT = NW * 64;
     constexpr int RB = BH / MR;                         // row blocks per tile slice
-    constexpr int KS = BW / MK;                         // k steps per tile
-    constexpr int LT = RB * KS;                         // 16-byte weight loads per lane per tile
-    constexpr int U  = (LT >= 8) ? 1 : 8 / LT;          // tiles in flight per wave
+    constexpr int KS = PAIR ? 1 : BW / MK;              // k steps per tile (pair)
+    constexpr int LT = RB * KS;                         // 16-byte weight loads per lane per tile (pair)
+    constexpr int U  = (LT >= 8) ? 1 : 8 / LT;          // tiles (pairs) in flight per wave
     constexpr int N  = BH * NBS;
-    static_assert(BH % MR == 0 && BW % MK == 0, "tile shape does not fit this MFMA");
+    constexpr int XPAD = PAIR ? BW : 0;                 // zeroed columns after the last staged tile (odd tile count)
+    static_assert(BH % MR == 0 && (PAIR ? BW * 2 == MK : BW % MK == 0), "tile shape does not fit this MFMA");
     static_assert(NBS <= MR, "more staged batch rows than MFMA columns");
 
     extern __shared__ __align__(16) char smem[];
     __shared__ int s_flag;
     const int q_uniform_parts = q_ct_parts >> 16, q_uniform_ct = q_uniform_parts > 0 ? (q_ct_parts & 0xFFFF) : 0;
     const int q_bh_full = q_misc & 0x7F, q_batch = (q_misc >> 7) & 0x7F, q_xn_vecs = (int)((unsigned)q_misc >> 14);
-    const int q_xs_stride = (q_ct_parts & 0xFFFF) * BW + VEC;
+    const int q_xs_stride = (q_ct_parts & 0xFFFF) * BW + XPAD + VEC;
     WT* xn = reinterpret_cast<WT*>(smem);
     WT* xs = XR ? xn + NBS * q_xn_vecs * VEC + VEC : xn;
     float* red = reinterpret_cast<float*>(smem);        // reused after the stream phase: NW * N floats
@@ -771,16 +778,20 @@ __global__ void __launch_bounds__(NW * 64) fc_mfma_lds_kernel(PIVOT_GEMV_PARAMS,
     const int li = lane % MR;                           // A row / B column of this lane
     const int lg = lane / MR;                           // k group of 8
     const _Float16* vbase = reinterpret_cast<const _Float16*>(p_vals) + (size_t)tile_begin * tile_elems
-                            + (size_t)slice * BH * BW + li * BW + lg * 8;
+                            + (size_t)slice * BH * BW + li * BW + (PAIR ? (lg & 1) : lg) * 8;
     const int tmax = ntiles > 0 ? ntiles - 1 : 0;       // clamped, unconditional loads (see fc_gemv_kernel)
+    const int nsteps = PAIR ? (ntiles + 1) / 2 : ntiles; // MFMA steps along the block row: tiles, or pairs of tiles
     f16x8 w[U][LT];
     auto fill = [&](int u, int t) {
-        const int tc = t < tmax ? t : tmax;
+        const int tt = PAIR ? 2 * t + (lg >> 1) : t;    // this lane's tile
+        const int tc = tt < tmax ? tt : tmax;
         #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
             #pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
+            for (int ks = 0; ks < KS; ++ks) {
                 w[u][rb * KS + ks] = load16<f16x8>(vbase + (size_t)tc * tile_elems + rb * MR * BW + ks * MK);
+                if (PAIR && tt >= ntiles) w[u][rb * KS + ks] = f16x8(0);   // the missing half of the last pair
+            }
     };
     // with a copy of x: into LDS after half of the first weight loads, the other half behind it (see fc_gemv_kernel)
     constexpr int UH = (XR != 0 && U >= 2) ? U / 2 : U;
@@ -804,6 +815,10 @@ __global__ void __launch_bounds__(NW * 64) fc_mfma_lds_kernel(PIVOT_GEMV_PARAMS,
     } else {
         xst.template gather<false>(q_batch, q_ldx, 0, q_xs_stride, p_idx, reinterpret_cast<const WT*>(p_x), xs, tile_begin, ntiles * BW, b0, tid);
     }
+    if constexpr (PAIR) {
+        // the columns a last, single tile's partner would have: zero weights meet zero inputs, never stale LDS
+        if (tid < NBS * XPAD) xs[(tid / XPAD) * q_xs_stride + ntiles * BW + tid % XPAD] = WT(0);
+    }
     lds_barrier();
 
     acc_t acc[RB];
@@ -813,13 +828,13 @@ __global__ void __launch_bounds__(NW * 64) fc_mfma_lds_kernel(PIVOT_GEMV_PARAMS,
     auto consume = [&](int u, int t) {
         #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            const f16x8 xv = *reinterpret_cast<const f16x8*>(xrow + t * BW + ks * MK);
+            const f16x8 xv = *reinterpret_cast<const f16x8*>(xrow + t * (PAIR ? 2 * BW : BW) + ks * MK);
             #pragma unroll
             for (int rb = 0; rb < RB; ++rb) acc[rb] = MF::run(w[u][rb * KS + ks], xv, acc[rb]);
         }
     };
     int t0 = wave;
-    for (; t0 + NW * U < ntiles; t0 += NW * U) {
+    for (; t0 + NW * U < nsteps; t0 += NW * U) {
         #pragma unroll
         for (int u = 0; u < U; ++u) {
             consume(u, t0 + u * NW);
@@ -828,7 +843,7 @@ __global__ void __launch_bounds__(NW * 64) fc_mfma_lds_kernel(PIVOT_GEMV_PARAMS,
     }
     #pragma unroll
     for (int u = 0; u < U; ++u)
-        if (t0 + u * NW < ntiles) consume(u, t0 + u * NW);
+        if (t0 + u * NW < nsteps) consume(u, t0 + u * NW);
 
     // every wave's sums for the staged batch columns go to LDS; the epilogue adds the NW copies
     __syncthreads();                                    // xs no longer needed; red aliases it

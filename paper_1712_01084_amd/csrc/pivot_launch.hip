@@ -40,7 +40,7 @@ int fc_path(int layout, int wdtype, int bh, int bw, int lds_tiles, int batch) {
     if (layout != PIVOT_BRC || mfma_kind(wdtype, bh, bw) < 0 || batch < 3) return kPathVector;
     if (batch <= 16 && lds_tiles > 0) {
         const int rows = mfma_lds_rows(batch);
-        const size_t xs_bytes = (size_t)rows * ((size_t)lds_tiles * bw + 8) * 2;
+        const size_t xs_bytes = (size_t)rows * ((size_t)lds_tiles * bw + 8 + 16) * 2;   // + the paired form's zeroed columns
         if (xs_bytes <= 48 * 1024) return kPathMfmaLds;
     }
     return batch >= 8 ? kPathMfmaGather : kPathVector;
@@ -70,8 +70,11 @@ int fc_row_slices(int layout, int wdtype, int bh, int bw, int lds_tiles, int bat
         bool ok = (bh % sl == 0);
         const int bhs = bh / sl;
         if (ok) {
-            if (fc_path(layout, wdtype, bh, bw, lds_tiles, batch) != kPathVector) {
-                const int mr = mfma_kind(wdtype, bh, bw) == 0 ? 16 : 32;
+            const int path = fc_path(layout, wdtype, bh, bw, lds_tiles, batch);
+            if (path != kPathVector) {
+                // whole MFMA row blocks: 16 rows (32 for tiles 16 columns wide, except in the LDS-fed kernel,
+                // which pairs such tiles)
+                const int mr = (mfma_kind(wdtype, bh, bw) == 0 || (path == kPathMfmaLds && bw == 16)) ? 16 : 32;
                 ok = (bhs % mr == 0);
             } else {
                 const int vec = 16 / elem_size(wdtype);
@@ -140,7 +143,11 @@ int launch_fc(const FcLaunch& L) {
     if (L.uniform_ct > 0xFFFF || L.uniform_parts > 0x7FFF) a.uniform_ct = a.uniform_parts = 0;   // packed into 16 bits each: fall back to loaded descriptors
     // staged x: nbt rows of (tiles per chunk)*bw elements, plus 16 bytes whose last element is the dump slot
     // (the vector kernel derives the same stride from its preloaded arguments)
-    a.xs_stride = (a.uniform_ct > 0 ? a.uniform_ct : L.chunk_tiles) * L.bw + 16 / es;
+    // the LDS-fed matrix-core kernel takes slices that are not whole 32-row blocks of 16-column tiles as pairs
+    // of tiles (16x16x32 MFMA) and keeps 16 zeroed columns after the last staged tile
+    int kind = mfma_kind(L.wdtype, L.bh, L.bw);
+    if (ml && kind == 1 && L.bw == 16 && bhs % 32 != 0) kind = 2;
+    a.xs_stride = (a.uniform_ct > 0 ? a.uniform_ct : L.chunk_tiles) * L.bw + (ml && kind == 2 ? 16 : 0) + 16 / es;
     size_t xs_bytes = (size_t)nbt * a.xs_stride * es;
     size_t red_bytes = (size_t)nw * bhs * nbt * 4;
     // x-resident variant: every work item first copies the whole of x (nbt rows) into LDS with independent
@@ -194,7 +201,7 @@ int launch_fc(const FcLaunch& L) {
         if (!L.xsort) { set_error("internal: the LDS-fed matrix-core kernel needs the packed gather lists"); return PIVOT_E_UNSUPPORTED; }
         a.xidx = L.xsort;
     }
-    if (ml) return launch_mfma_lds_f16(a, mfma_kind(L.wdtype, L.bh, L.bw), bhs, L.bw, nbt, nw, xres, grid, smem, st);
+    if (ml) return launch_mfma_lds_f16(a, kind, bhs, L.bw, nbt, nw, xres, grid, smem, st);
     if (L.wdtype == PIVOT_F32) return launch_gemv_f32(a, bhs, L.bw, nbt, nw, xres, grid, smem, st);
     return launch_gemv_f16(a, bhs, L.bw, nbt, nw, xres, grid, smem, st);
 }

@@ -26,6 +26,7 @@ int launch_mfma_lds_f16(const FcArgs& a, int kind, int bhs, int bw, int nbs, int
     if (bhs == BH_ && bw == BW_) {                                                                         \
         if constexpr (BW_ % 32 == 0 && BH_ % 16 == 0) { if (kind == 0) return launch_t<0, BH_, BW_>(a, nbs, nw, xres, grid, smem, st); } \
         if constexpr (BH_ % 32 == 0 && BW_ % 16 == 0) { if (kind == 1) return launch_t<1, BH_, BW_>(a, nbs, nw, xres, grid, smem, st); } \
+        if constexpr (BH_ == 16 && BW_ == 16)          { if (kind == 2) return launch_t<2, BH_, BW_>(a, nbs, nw, xres, grid, smem, st); } \
     }
     PIVOT_SHAPES(X)
 #undef X

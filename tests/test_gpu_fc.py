@@ -109,6 +109,22 @@ def test_fp16_batches_gather_through_source_ordered_lists(batch, frac):
     G.check_fc(p)
 
 
+@pytest.mark.parametrize("batch", [3, 4, 8, 11, 16])
+@pytest.mark.parametrize("bh,sl", [(64, 4), (32, 2), (64, 2)])
+def test_fp16_16_column_tiles_in_16_row_slices_pair_their_tiles(bh, sl, batch):
+    # tiles 16 columns wide cut into 16-row slices: one 16x16x32 MFMA step spans two consecutive tiles of the
+    # block row; odd tile counts (the last pair's second half is zero weights against zeroed columns), block rows
+    # of one tile, an empty block row, split block rows; (64, 2) keeps 32-row slices (the 32x32x16 form)
+    p = WL.gen_fc(4 * bh - 5, 7 * 16 - 3, bh, 16, 1.0, seed=120 + batch, wdtype=WL.F16, batch=batch, mask="full",
+                  act=WL.ACT_RELU)
+    p.tile_mask[1, 1:] = 0                               # a block row of a single tile
+    p.tile_mask[2, :] = 0                                # an empty one
+    G.check_fc(p, row_slices=sl)
+    G.check_fc(p, row_slices=sl, chunk_tiles=3, wg_waves=8)
+    p = WL.gen_fc(3 * bh, 41 * 16, bh, 16, 0.5, seed=140 + batch, wdtype=WL.F16, batch=batch)
+    G.check_fc(p, row_slices=sl)
+
+
 def test_fp16_batches_beyond_the_gather_lists_range():
     # 2^19 input columns and more do not fit the packed list entries: the plan carries no lists and batch 3..16
     # falls back to the vector kernel (batch < 8) or to the block-order copy plus the matrix-core kernel
