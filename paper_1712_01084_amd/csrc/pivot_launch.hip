@@ -18,8 +18,11 @@ static int device_cus() {
     return c;
 }
 
-// Batch rows the LDS-fed matrix-core kernel stages (4, 8 or 16).
-static int mfma_lds_rows(int batch) { return batch <= 4 ? 4 : (batch <= 8 ? 8 : 16); }
+// Batch rows the LDS-fed matrix-core kernel stages: 4, or 8 (batch 9..16 then runs as two launch rows of 8, each
+// workgroup gathering half the rows: staging all 16 in one workgroup was measured slower at every density, 6.0 ->
+// 4.7 us at 5 % kept and 13.4 -> 12.3 at 50 % on 4096x4096, where 16 rows no longer fit; four launch rows of 4
+// were slower again from 10 % kept on: the weights are then streamed four times).
+static int mfma_lds_rows(int batch) { return batch <= 4 ? 4 : 8; }
 
 // Which kernel applies the layer:
 //   kPathVector      batch 1-2 (and whatever the matrix cores cannot take): FMA / dot2 against x staged in LDS
@@ -33,7 +36,7 @@ static int mfma_lds_rows(int batch) { return batch <= 4 ? 4 : (batch <= 8 ? 8 : 
 // through the plan's source-ordered lists (neighbouring lanes, neighbouring addresses) it wins wherever the
 // staged rows fit in 48 KB of LDS (batch 8: 7.6 -> 5.4 us at 10 % kept, 9.8 -> 7.4 at 25 %, 12.3 -> 10.1 at
 // 50 %, 14.2 -> 12.4 dense; batch 16: 7.3 -> 6.1 at 5 %, 11.0 -> 9.5 at 25 %).  Letting it take up to 136 KB of
-// LDS (one workgroup per compute unit) for batch 16 at 50 % and dense was measured too: 13.5 -> 13.2 us and
+// LDS (one workgroup per compute unit) for 16 staged rows at 50 % and dense was measured too: 13.5 -> 13.2 us and
 // 14.5 -> 15.4 us, so longer rows stay with the block-order form.
 int fc_path(int layout, int wdtype, int bh, int bw, int lds_tiles, int batch) {
     // the matrix-core kernels read A fragments from row-major (BRC) tiles only

@@ -16,7 +16,7 @@ static int launch_t(const FcArgs& a, int nbs, int nw, int xres, dim3 grid, size_
     switch (nbs) {
         case 4:  return xres ? launch_w<KIND, BH, BW, 4, 2>(a, nw, grid, smem, st) : launch_w<KIND, BH, BW, 4, 0>(a, nw, grid, smem, st);
         case 8:  return xres ? launch_w<KIND, BH, BW, 8, 2>(a, nw, grid, smem, st) : launch_w<KIND, BH, BW, 8, 0>(a, nw, grid, smem, st);
-        default: return xres ? launch_w<KIND, BH, BW, 16, 2>(a, nw, grid, smem, st) : launch_w<KIND, BH, BW, 16, 0>(a, nw, grid, smem, st);
+        default: set_error("internal: %d staged batch rows", nbs); return PIVOT_E_UNSUPPORTED;
     }
 }
 

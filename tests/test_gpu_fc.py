@@ -87,7 +87,7 @@ def test_batches_fp16_including_matrix_core_path(bh, bw, batch):
 @pytest.mark.parametrize("bh,bw", [(64, 16), (16, 32), (32, 64)])
 def test_fp16_small_batches_matrix_cores_fed_from_lds(bh, bw, batch):
     # batch 3..16 with few staged elements: the tile is the MFMA A operand, the B fragments come from the
-    # x-segments staged in LDS (4, 8 or 16 rows; rows past the batch are zero and never stored); whole block
+    # x-segments staged in LDS (4 or 8 rows per launch row; rows past the batch are zero and never stored); whole block
     # rows per work item, ragged M and K, one empty block row
     p = WL.gen_fc(3 * bh + 7, 6 * bw - 5, bh, bw, 0.6, seed=40 + batch, wdtype=WL.F16, batch=batch, act=WL.ACT_RELU)
     p.tile_mask[2, :] = 0
