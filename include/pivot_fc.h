@@ -191,10 +191,11 @@ int    pivot_workspace_init(void* ws_dev, size_t ws_bytes, void* stream);
  *   x_dev  device, [batch][K] of wdtype, row stride ldx elements, natural coordinates
  *   y_dev  device, [batch][M] fp32, row stride ldy elements, natural coordinates
  *   batch  1..64.  F16 plans whose tiles fit an MFMA shape use the matrix
- *          cores from batch 3 on: up to batch 16 fed from x-segments staged
+ *          cores from batch 3 on: fed from x-segments staged
  *          in LDS (4 or 8 batch rows per workgroup, gathered through the
  *          plan's source-ordered lists) while the staged rows of a work item
- *          fit in 48 KB, else (batch >= 8)
+ *          fit in 48 KB (beyond batch 16: and the launch rows together
+ *          stage at most 5120 columns per work item), else (batch >= 8)
  *          from a copy of x in block order made by one small extra kernel.
  */
 int  pivot_fc_run(const pivot_fc_plan_t* plan, const void* x_dev, int64_t ldx,

@@ -26,7 +26,7 @@ static int mfma_lds_rows(int batch) { return batch <= 4 ? 4 : 8; }
 
 // Which kernel applies the layer:
 //   kPathVector      batch 1-2 (and whatever the matrix cores cannot take): FMA / dot2 against x staged in LDS
-//   kPathMfmaLds     fp16, batch 3..16: MFMA with the B fragments read from x staged in LDS
+//   kPathMfmaLds     fp16, batch >= 3: MFMA with the B fragments read from x staged in LDS (4 or 8 batch rows per launch row)
 //   kPathMfmaGather  fp16, batch >= 8 otherwise: MFMA with B fragments read from an x in block order
 // Every work item of the LDS-fed form gathers its own x-segments for all batch rows (rows * tiles * bw
 // elements), the block-order form gathers x once in a launch of its own.  Measured (4096x4096, 64x16 tiles):
@@ -41,10 +41,16 @@ static int mfma_lds_rows(int batch) { return batch <= 4 ? 4 : 8; }
 int fc_path(int layout, int wdtype, int bh, int bw, int lds_tiles, int batch) {
     // the matrix-core kernels read A fragments from row-major (BRC) tiles only
     if (layout != PIVOT_BRC || mfma_kind(wdtype, bh, bw) < 0 || batch < 3) return kPathVector;
-    if (batch <= 16 && lds_tiles > 0) {
+    if (lds_tiles > 0) {
         const int rows = mfma_lds_rows(batch);
         const size_t xs_bytes = (size_t)rows * ((size_t)lds_tiles * bw + 8 + 16) * 2;   // + the paired form's zeroed columns
-        if (xs_bytes <= 48 * 1024) return kPathMfmaLds;
+        // every launch row of 8 batch rows streams the weights again and gathers its own rows: beyond two launch
+        // rows the form is kept while the launch rows together stage at most 5120 columns per work item
+        // (4096x4096, 64x16 tiles: batch 24 at 5 / 25 % kept 7.9 -> 5.6 us, 12.1 -> 10.7; batch 64 at 5 %
+        // 9.8 -> 8.5; but batch 24 dense 16.1 -> 19.1 and batch 64 at 25 % 14.4 -> 21.0, which stay with the
+        // block-order form)
+        const size_t launch_rows = (size_t)(batch + rows - 1) / rows;
+        if (xs_bytes <= 48 * 1024 && (launch_rows <= 2 || launch_rows * lds_tiles * bw <= 5120)) return kPathMfmaLds;
     }
     return batch >= 8 ? kPathMfmaGather : kPathVector;
 }

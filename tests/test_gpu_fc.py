@@ -125,6 +125,18 @@ def test_fp16_16_column_tiles_in_16_row_slices_pair_their_tiles(bh, sl, batch):
     G.check_fc(p, row_slices=sl)
 
 
+@pytest.mark.parametrize("batch", [16, 33, 64])
+def test_fp16_long_rows_use_the_block_order_copy(batch):
+    # work items too long for the LDS-fed form (8 batch rows of 4096 staged columns exceed its 48 KB; at batch 64
+    # eight launch rows of 1232 columns exceed its column budget): x is copied to block order by one small kernel
+    # and the matrix-core kernel reads its B fragments from the copy
+    p = WL.gen_fc(2 * 64 - 3, 4096, 64, 16, 1.0, seed=160 + batch, wdtype=WL.F16, batch=batch, mask="full", act=WL.ACT_RELU)
+    G.check_fc(p, chunk_tiles=256)
+    if batch == 64:
+        p = WL.gen_fc(3 * 64, 4096, 64, 16, 0.3, seed=170, wdtype=WL.F16, batch=batch, mask="balanced")
+        G.check_fc(p)
+
+
 def test_fp16_batches_beyond_the_gather_lists_range():
     # 2^19 input columns and more do not fit the packed list entries: the plan carries no lists and batch 3..16
     # falls back to the vector kernel (batch < 8) or to the block-order copy plus the matrix-core kernel
