@@ -23,7 +23,7 @@ def _case(rng, it, big):
     M = max(1, nbr * bh - int(rng.integers(0, bh)))
     K = max(1, nbc * bw - int(rng.integers(0, bw)))
     frac = float(rng.choice([0.1, 0.3, 0.6, 1.0]))
-    batch = int(rng.choice([1, 1, 1, 2, 3, 4, 5, 8, 9, 16, 17]))
+    batch = int(rng.choice([1, 1, 1, 2, 3, 4, 5, 8, 9, 16, 17, 24, 33, 64]))
     kw = dict(chunk_tiles=int(rng.choice([0, 0, 1, 2, 5, 12])), wg_waves=int(rng.choice([0, 4, 8, 16])),
               row_slices=int(rng.choice([0, 1, 2, 4, 8])),
               flags=int(rng.choice([0, 0, B.PIVOT_PLAN_GATHER_FROM_GLOBAL, B.PIVOT_PLAN_GATHER_FROM_LDS_COPY])))
