@@ -143,7 +143,8 @@ typedef struct pivot_plan_view {
                                   MFMA shape, K_pad < 2^19 - 1 and at most 8192 columns per piece: what the
                                   batch 3..16 kernel reads, so that neighbouring lanes gather neighbouring
                                   addresses */
-    const int32_t* xsort_blk;  /* same for an input already in block order (source = col_idx[t]*bw+c) */
+    const int32_t* xsort_blk;  /* same for an input already in block order (source = col_idx[t]*bw+c, all
+                                  ones for a padding column, i.e. one at or past K) */
 } pivot_plan_view;
 
 int         pivot_version(void);
@@ -176,10 +177,18 @@ int  pivot_fc_plan_host_view(const pivot_fc_plan_t* plan, pivot_plan_view* view)
 int  pivot_fc_plan_clone(const pivot_fc_plan_t* plan, pivot_fc_plan_t** out);
 void pivot_fc_plan_destroy(pivot_fc_plan_t* plan);   /* NULL-safe */
 
-/* Scratch a run needs for `batch` rows (partials of split block rows and
- * their arrival counters).  The buffer has to be cleared once with
- * pivot_workspace_init before its first use; every run leaves it ready for
- * the next one.  Two runs that overlap in time must not share a workspace. */
+/* Scratch a run needs for `batch` rows: arrival counters of split block rows
+ * (first; their size does not depend on the batch), their partial sums, and
+ * for the matrix-core form that wants it a copy of x in block order.
+ * Reuse rule: clear the buffer once with pivot_workspace_init before its first
+ * use with a plan; after that any number of runs of THAT plan may share it, in
+ * any order of batch sizes (every run leaves the counters at zero, nothing
+ * else is read before it is written), as long as it holds
+ * pivot_fc_workspace_bytes(plan, batch) for each of them.  Clear it again
+ * before using it with another plan (or chain): the counters of one plan lie
+ * where another plan keeps partial sums.  Two runs that overlap in time must
+ * not share a workspace.  The same rule holds for the chain and recurrent
+ * workspaces below. */
 size_t pivot_fc_workspace_bytes(const pivot_fc_plan_t* plan, int batch);
 int    pivot_workspace_init(void* ws_dev, size_t ws_bytes, void* stream);
 

@@ -49,8 +49,13 @@ int upload(pivot_fc_plan_t* p) {
         rowid.assign(h.M_pad, -1);
         chunks8.assign((size_t)h.nchunks * 8, 0);
     } catch (const std::bad_alloc&) { set_error("out of host memory"); return PIVOT_E_ALLOC; }
+    // (padding columns are -1 here too: a block-order x is never read past its K real columns, so whatever a
+    // reused workspace holds there cannot reach a sum)
     for (int t = 0; t < h.T; ++t)
-        for (int c = 0; c < h.d.bw; ++c) xblk[(size_t)t * h.d.bw + c] = h.col_idx[t] * h.d.bw + c;
+        for (int c = 0; c < h.d.bw; ++c) {
+            const int col = h.col_idx[t] * h.d.bw + c;
+            xblk[(size_t)t * h.d.bw + c] = col < h.d.K ? col : -1;
+        }
     for (int r = 0; r < h.d.M; ++r) rowid[r] = r;
     for (int j = 0; j < h.nchunks; ++j) {
         for (int q = 0; q < 4; ++q) chunks8[(size_t)8 * j + q] = h.chunks[(size_t)4 * j + q];
@@ -194,16 +199,15 @@ int pivot_workspace_init(void* ws_dev, size_t ws_bytes, void* stream) {
 
 namespace {
 
-// Fills the plan-dependent part of a launch and carves the workspace
-// ([arrival counters][partials]; `ws_bytes` must cover fc_workspace_bytes).
-int prepare(const pivot_fc_plan_t* plan, int batch, void* ws, size_t ws_bytes, FcLaunch& L) {
+// Fills the plan-dependent part of a launch.  `tickets`: fc_ticket_bytes(plan) of arrival counters that are zero
+// between runs; `partials`: fc_partial_bytes(plan, batch) of scratch (both may be NULL when the size is 0).
+int prepare(const pivot_fc_plan_t* plan, int batch, void* tickets, void* partials, FcLaunch& L) {
     if (!plan) { set_error("plan is NULL"); return PIVOT_E_NULL; }
     if (plan->device < 0) { set_error("host-only plan (device = -1) cannot run"); return PIVOT_E_NO_DEVICE; }
     if (batch < 1 || batch > 64) { set_error("batch %d outside 1..64", batch); return PIVOT_E_SHAPE; }
     const HostPlan& h = plan->host;
-    size_t need = fc_workspace_bytes(h, batch);
-    if (need > 0 && (!ws || ws_bytes < need)) { set_error("workspace too small: need %zu bytes, got %zu", need, ws ? ws_bytes : (size_t)0); return PIVOT_E_WORKSPACE; }
-    if (reinterpret_cast<uintptr_t>(ws) % 16 != 0) { set_error("workspace must be 16-byte aligned"); return PIVOT_E_WORKSPACE; }
+    if ((fc_ticket_bytes(h) > 0 && !tickets) || (fc_partial_bytes(h, batch) > 0 && !partials)) { set_error("workspace missing"); return PIVOT_E_WORKSPACE; }
+    if (reinterpret_cast<uintptr_t>(tickets) % 16 != 0 || reinterpret_cast<uintptr_t>(partials) % 16 != 0) { set_error("workspace must be 16-byte aligned"); return PIVOT_E_WORKSPACE; }
     const DevPlan& d = plan->dev;
     L.vals = d.vals; L.col_idx = d.col_idx; L.chunks = d.chunks; L.part_base = d.part_base; L.bias_p = d.bias_p;
     L.K = h.d.K; L.x_resident = (h.d.flags & PIVOT_PLAN_GATHER_FROM_GLOBAL) ? 0 : ((h.d.flags & PIVOT_PLAN_GATHER_FROM_LDS_COPY) ? 2 : 1);
@@ -213,10 +217,8 @@ int prepare(const pivot_fc_plan_t* plan, int batch, void* ws, size_t ws_bytes, F
     L.row_slices = h.row_slices;
     L.uniform_ct = h.uniform_ct; L.uniform_parts = h.uniform_parts;
     L.batch = batch;
-    int nbt = fc_batch_tile(h.d.layout, h.d.wdtype, h.d.bh, h.d.bw, h.lds_tiles(), batch);
-    int ngy = (batch + nbt - 1) / nbt;
-    L.tickets = reinterpret_cast<uint32_t*>(ws);
-    L.partials = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + fc_ticket_bytes(h.nbr, ngy, h.row_slices));
+    L.tickets = reinterpret_cast<uint32_t*>(tickets);
+    L.partials = reinterpret_cast<float*>(partials);
     return PIVOT_OK;
 }
 
@@ -238,22 +240,40 @@ int natural_input(const pivot_fc_plan_t* plan, const void* x_dev, int64_t ldx, i
 
 }  // namespace
 
-extern "C" {
+namespace pivot {
 
-int pivot_fc_run(const pivot_fc_plan_t* plan, const void* x_dev, int64_t ldx, void* y_dev, int64_t ldy,
-                 int batch, void* ws_dev, size_t ws_bytes, void* stream) {
+int run_layer(const pivot_fc_plan_t* plan, const void* x_dev, int64_t ldx, void* y_dev, int64_t ldy, int batch,
+              void* tickets, void* partials, void* xg, void* stream) {
     FcLaunch L{};
-    int rc = prepare(plan, batch, ws_dev, ws_bytes, L);
+    int rc = prepare(plan, batch, tickets, partials, L);
     if (rc != PIVOT_OK) return rc;
     if (!x_dev || !y_dev) { set_error("x_dev and y_dev are required"); return PIVOT_E_NULL; }
     if (ldx < plan->host.d.K || ldy < plan->host.d.M) { set_error("ldx/ldy smaller than K/M"); return PIVOT_E_SHAPE; }
-    const size_t base = fc_workspace_bytes(plan->host, batch);
-    if (ws_bytes < base + fc_gather_bytes(plan->host, batch)) { set_error("workspace too small: need %zu bytes", base + fc_gather_bytes(plan->host, batch)); return PIVOT_E_WORKSPACE; }
-    rc = natural_input(plan, x_dev, ldx, batch, reinterpret_cast<char*>(ws_dev) + base, stream, L);
+    if (fc_gather_bytes(plan->host, batch) > 0 && !xg) { set_error("workspace missing"); return PIVOT_E_WORKSPACE; }
+    rc = natural_input(plan, x_dev, ldx, batch, xg, stream, L);
     if (rc != PIVOT_OK) return rc;
     L.scatter = plan->dev.prow_pad;
     L.y = y_dev; L.ldy = ldy; L.out_f16 = 0; L.stream = stream;
     return launch_fc(L);
+}
+
+}  // namespace pivot
+
+extern "C" {
+
+int pivot_fc_run(const pivot_fc_plan_t* plan, const void* x_dev, int64_t ldx, void* y_dev, int64_t ldy,
+                 int batch, void* ws_dev, size_t ws_bytes, void* stream) {
+    if (!plan) { set_error("plan is NULL"); return PIVOT_E_NULL; }
+    if (plan->device < 0) { set_error("host-only plan (device = -1) cannot run"); return PIVOT_E_NO_DEVICE; }
+    if (batch < 1 || batch > 64) { set_error("batch %d outside 1..64", batch); return PIVOT_E_SHAPE; }
+    const HostPlan& h = plan->host;
+    const size_t nt = fc_ticket_bytes(h), np = fc_partial_bytes(h, batch), ng = fc_gather_bytes(h, batch);
+    if (nt + np + ng > 0 && (!ws_dev || ws_bytes < nt + np + ng)) {
+        set_error("workspace too small: need %zu bytes, got %zu", nt + np + ng, ws_dev ? ws_bytes : (size_t)0);
+        return PIVOT_E_WORKSPACE;
+    }
+    char* ws = reinterpret_cast<char*>(ws_dev);
+    return run_layer(plan, x_dev, ldx, y_dev, ldy, batch, ws, ws + nt, ws + nt + np, stream);
 }
 
 // ------------------------------------------------------------------ chains
@@ -366,24 +386,22 @@ void pivot_mlp_plan_destroy(pivot_mlp_plan_t* plan) {
 
 namespace {
 
-// Workspace of a chain: [scratch of layer 0] [scratch of layer 1] ... [block-order copy of x (matrix path)]
-// [intermediate 0] ...  Every layer has its own scratch: the arrival counters of split block rows rely on being
-// zero between launches, so no other layer's partial sums may land on them.
-// Intermediate l holds batch rows of K_pad_{l+1} elements of wdtype in the
-// consumer's block order; its padding columns stay zero from pivot_workspace_init.
-struct MlpLayout { size_t scratch, gather_off, total; std::vector<size_t> inter_off, scratch_off, scratch_len; };
+// Workspace of a chain: [arrival counters of layer 0] [of layer 1] ... [partial sums of layer 0] ... [block-order
+// copy of x (matrix path)] [intermediate 0] ...  The counters come first and their sizes do not depend on the
+// batch, so they are only ever touched as counters, whatever batches the workspace is reused with (they rely on
+// being zero between launches; every run leaves them so).  Every layer has its own.
+// Intermediate l holds batch rows of K_pad_{l+1} elements of wdtype in the consumer's block order; its padding
+// columns are never read by the kernels that stage x in LDS (their gather index is -1 there) and are cleared
+// before a kernel that reads the rows directly.
+struct MlpLayout { size_t gather_off, total; std::vector<size_t> inter_off, ticket_off, partial_off; };
 
 MlpLayout mlp_layout(const pivot_mlp_plan_t* mp, int batch) {
-    MlpLayout m{0, 0, 0, {}, {}, {}};
-    for (auto* l : mp->layers) {
-        const size_t len = align_up(fc_workspace_bytes(l->host, batch), 256);
-        m.scratch_off.push_back(m.scratch);
-        m.scratch_len.push_back(len);
-        m.scratch += len;
-    }
-    m.gather_off = m.scratch;
-    m.scratch += fc_gather_bytes(mp->layers[0]->host, batch);
-    size_t off = m.scratch;
+    MlpLayout m{0, 0, {}, {}, {}};
+    size_t off = 0;
+    for (auto* l : mp->layers) { m.ticket_off.push_back(off); off += align_up(fc_ticket_bytes(l->host), 256); }
+    for (auto* l : mp->layers) { m.partial_off.push_back(off); off += align_up(fc_partial_bytes(l->host, batch), 256); }
+    m.gather_off = off;
+    off += fc_gather_bytes(mp->layers[0]->host, batch);
     for (size_t l = 0; l + 1 < mp->layers.size(); ++l) {
         m.inter_off.push_back(off);
         off += align_up((size_t)batch * mp->layers[l + 1]->host.K_pad * elem_size(mp->layers[l + 1]->host.d.wdtype), 256);
@@ -439,7 +457,7 @@ int pivot_mlp_run(const pivot_mlp_plan_t* plan, const void* x_dev, int64_t ldx, 
     for (int l = 0; l < Lc; ++l) {
         const pivot_fc_plan_t* p = plan->layers[l];
         FcLaunch L{};
-        int rc = prepare(p, batch, ws + m.scratch_off[l], m.scratch_len[l], L);
+        int rc = prepare(p, batch, ws + m.ticket_off[l], ws + m.partial_off[l], L);
         if (rc != PIVOT_OK) return rc;
         L.stream = stream;
         if (l == 0) {
@@ -447,6 +465,10 @@ int pivot_mlp_run(const pivot_mlp_plan_t* plan, const void* x_dev, int64_t ldx, 
             if (rc != PIVOT_OK) return rc;
         } else {
             L.xidx = p->dev.xidx_blk; L.xsort = p->host.sorted_ok ? p->dev.xsort_blk : nullptr; L.x = ws + m.inter_off[l - 1]; L.ldx = p->host.K_pad; L.x_block_order = 1;
+            // the kernel that reads its B fragments straight from the rows also reads the padding columns
+            // (against zero weights): they must hold finite values, whatever the workspace held before
+            if (p->host.K_pad > p->host.d.K && fc_uses_matrix_cores(p->host.d.layout, p->host.d.wdtype, p->host.d.bh, p->host.d.bw, p->host.lds_tiles(), batch) &&
+                (rc = launch_zero_pad_cols(ws + m.inter_off[l - 1], p->host.d.K, p->host.K_pad, batch, elem_size(p->host.d.wdtype), stream)) != PIVOT_OK) return rc;
         }
         if (l + 1 < Lc) {
             // producer-side store through the composed boundary array; identity boundaries store contiguously
@@ -484,11 +506,13 @@ int pivot_mlp_status(const pivot_mlp_plan_t* plan, void* stream, int* status) {
 
 namespace {
 
-// [launch-per-step scratch][gate pre-activations][control words + partials of the one-launch form][inputs of all steps]
-struct LstmLayout { size_t scratch, z_off, ctl_off, part_off, xg_off, xg_step, total; };
+// [launch-per-step form: arrival counters, partial sums][gate pre-activations][control words + partials of the
+// one-launch form][inputs of all steps]
+struct LstmLayout { size_t tickets, scratch, z_off, ctl_off, part_off, xg_off, xg_step, total; };
 
 LstmLayout lstm_layout(const pivot_fc_plan_t* p, int steps, int batch) {
     LstmLayout m{};
+    m.tickets = fc_ticket_bytes(p->host);
     m.scratch = align_up(fc_workspace_bytes(p->host, batch), 256);
     m.z_off = m.scratch;
     m.ctl_off = m.z_off + align_up((size_t)batch * p->host.d.M * 4, 256);
@@ -554,7 +578,7 @@ int pivot_lstm_run(const pivot_fc_plan_t* plan, int H, int I, const void* xs_dev
     if ((rc = launch_lstm_place_state(h_dev, xg, plan->dev.invpcol, H, h.K_pad, batch, h.d.wdtype, stream)) != PIVOT_OK) return rc;
     for (int t = 0; t < steps; ++t) {
         FcLaunch L{};
-        rc = prepare(plan, batch, ws, m.scratch, L);
+        rc = prepare(plan, batch, ws, ws + m.tickets, L);
         if (rc != PIVOT_OK) return rc;
         L.xidx = plan->dev.xidx_blk; L.xsort = plan->host.sorted_ok ? plan->dev.xsort_blk : nullptr; L.x_block_order = 1;
         L.x = xg + m.xg_step * (size_t)t; L.ldx = h.K_pad;

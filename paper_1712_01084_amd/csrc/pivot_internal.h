@@ -127,7 +127,7 @@ int    fc_batch_tile(int layout, int wdtype, int bh, int bw, int lds_tiles, int 
 bool   fc_uses_matrix_cores(int layout, int wdtype, int bh, int bw, int lds_tiles, int batch);   // the form that needs x in block order
 int    fc_row_slices(int layout, int wdtype, int bh, int bw, int lds_tiles, int batch, int want);
 // Workspace of one layer application: [arrival counters][partials of split rows][x in block order (matrix path)]
-size_t fc_ticket_bytes(int nbr, int ngy, int slices);
+size_t fc_ticket_bytes(const HostPlan& hp);                   // the same for every batch (0 without split block rows)
 size_t fc_partial_bytes(const HostPlan& hp, int batch);
 size_t fc_workspace_bytes(const HostPlan& hp, int batch);     // counters + partials
 size_t fc_gather_bytes(const HostPlan& hp, int batch);        // block-order copy of a natural-order x
@@ -135,6 +135,8 @@ int    launch_fc(const FcLaunch& L);
 int    launch_gather_x(const void* x, int64_t ldx, const int32_t* pcol_pad, void* xg, int K_pad, int batch,
                        int wdtype, void* stream);
 int    launch_fill_zero(void* dev, size_t bytes, void* stream);
+// Zeroes columns [K, K_pad) of every row of a [batch][K_pad] buffer of `es`-byte elements.
+int    launch_zero_pad_cols(void* buf, int K, int K_pad, int batch, int es, void* stream);
 int    launch_null(void* stream);
 int    launch_stream_read(const void* buf, size_t bytes, float* out, void* stream);
 int    launch_dense(const void* W, int wdtype, int M, int K, const void* x, int64_t ldx,
@@ -198,6 +200,14 @@ int    chain_persist_status_offset();  // byte offset of the status word inside 
 int    launch_chain_persist(const ChainPersistLaunch& C);
 
 }  // namespace pivot
+
+namespace pivot {
+// One layer application on a natural-order x, its scratch given as three separate regions: arrival counters
+// (fc_ticket_bytes, zero between runs), partial sums (fc_partial_bytes) and the block-order copy of x
+// (fc_gather_bytes); a region of size 0 may be NULL.  Checks its arguments like pivot_fc_run.
+int run_layer(const pivot_fc_plan_t* plan, const void* x_dev, int64_t ldx, void* y_dev, int64_t ldy, int batch,
+              void* tickets, void* partials, void* xg, void* stream);
+}
 
 struct pivot_fc_plan {
     pivot::HostPlan host;

@@ -1,5 +1,7 @@
 // Chooses the kernel, the row slicing and the launch shape for one layer
 // application and sizes its workspace.
+#include <algorithm>
+
 #include "pivot_fc_kernels.h"
 
 namespace pivot {
@@ -97,7 +99,21 @@ int fc_row_slices(int layout, int wdtype, int bh, int bw, int lds_tiles, int bat
     return sl;
 }
 
-size_t fc_ticket_bytes(int nbr, int ngy, int slices) { return (size_t)4 * kTicketStride * nbr * ngy * slices; }
+// Arrival counters of split block rows: one 256-byte line per (launch row, block row, row slice).  The region is
+// sized for the largest number of launch rows any batch up to 64 can have, so that its size, and with it the
+// place of everything that follows it in a workspace, does not depend on the batch of a run: counters are only
+// ever touched as counters (every run leaves them at zero), never overlaid by another batch's partial sums.
+// Plans without split block rows use no counters.
+size_t fc_ticket_bytes(const HostPlan& hp) {
+    if (hp.max_parts <= 1) return 0;
+    int ngy_max = 1;
+    for (int batch = 1; batch <= 64; ++batch) {
+        const int nbt = fc_batch_tile(hp.d.layout, hp.d.wdtype, hp.d.bh, hp.d.bw, hp.lds_tiles(), batch);
+        ngy_max = std::max(ngy_max, (batch + nbt - 1) / nbt);
+    }
+    // counters are sized for the plan's slice count (a launch may use fewer)
+    return (size_t)4 * kTicketStride * hp.nbr * ngy_max * hp.row_slices;
+}
 
 size_t fc_partial_bytes(const HostPlan& hp, int batch) {
     if (hp.max_parts <= 1) return 0;
@@ -108,10 +124,7 @@ size_t fc_partial_bytes(const HostPlan& hp, int batch) {
 
 size_t fc_workspace_bytes(const HostPlan& hp, int batch) {
     if (batch < 1) return 0;
-    const int nbt = fc_batch_tile(hp.d.layout, hp.d.wdtype, hp.d.bh, hp.d.bw, hp.lds_tiles(), batch);
-    const int ngy = (batch + nbt - 1) / nbt;
-    // counters are sized for the plan's slice count (a launch may use fewer)
-    return fc_ticket_bytes(hp.nbr, ngy, hp.row_slices) + fc_partial_bytes(hp, batch);
+    return fc_ticket_bytes(hp) + fc_partial_bytes(hp, batch);
 }
 
 size_t fc_gather_bytes(const HostPlan& hp, int batch) {

@@ -40,6 +40,23 @@ __global__ void fill_zero_kernel(uint32_t* p, size_t nwords) {
     for (; i < nwords; i += stride) p[i] = 0u;
 }
 
+// columns [K, K_pad) of every row of a [batch][K_pad] buffer, in 2-byte units (es = 2 or 4 bytes per element)
+__global__ void zero_pad_cols_kernel(unsigned short* buf, int first, int row_len, int batch) {
+    const int n = row_len - first;
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n * batch; i += gridDim.x * blockDim.x)
+        buf[(size_t)(i / n) * row_len + first + i % n] = 0;
+}
+
+int launch_zero_pad_cols(void* buf, int K, int K_pad, int batch, int es, void* stream) {
+    if (K_pad <= K || batch < 1) return PIVOT_OK;
+    const int u = es / 2;                                  // 2-byte units per element
+    const int n = (K_pad - K) * u * batch;
+    hipLaunchKernelGGL(zero_pad_cols_kernel, dim3((n + 255) / 256), dim3(256), 0, reinterpret_cast<hipStream_t>(stream),
+                       reinterpret_cast<unsigned short*>(buf), K * u, K_pad * u, batch);
+    HIP_TRY(hipGetLastError());
+    return PIVOT_OK;
+}
+
 __global__ void null_kernel() {}
 
 int launch_null(void* stream) {

@@ -198,7 +198,10 @@ void build_sorted_gather(HostPlan& hp) {
             const uint32_t s = src[e] < 0 ? (uint32_t)kSortSrcNone : (uint32_t)src[e];
             hp.xsort[e0 + i] = (int32_t)(s | ((uint32_t)e << kSortSrcBits));
             const size_t g = e0 + i;                    // block order: position i reads column col_idx[t]*bw + c
-            const uint32_t sb = (uint32_t)hp.col_idx[g / d.bw] * d.bw + (uint32_t)(g % d.bw);
+            // (tiles are listed by ascending block column, so the padding columns, which only the last block
+            // column has, come last here as well)
+            const uint32_t col = (uint32_t)hp.col_idx[g / d.bw] * d.bw + (uint32_t)(g % d.bw);
+            const uint32_t sb = col < (uint32_t)d.K ? col : (uint32_t)kSortSrcNone;
             hp.xsort_blk[g] = (int32_t)(sb | ((uint32_t)i << kSortSrcBits));
         }
     }

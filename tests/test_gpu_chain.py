@@ -192,6 +192,36 @@ def test_one_launch_chain_falls_back():
     _check_chain(wide, want_one_launch=False)             # 1250 block rows: more work items than the form takes
 
 
+@pytest.mark.parametrize("wdtype", [WL.F32, WL.F16])
+def test_chain_workspace_reused_across_batch_sizes(wdtype):
+    # one workspace, cleared once, shared by runs of different batch sizes: ragged widths (padding columns in every
+    # intermediate), split block rows in every layer, fp16 at batch 16 through the kernel that reads its inputs
+    # straight from the block-order rows; each run is preceded by one of the same batch on NaN inputs
+    probs = WL.config4(seed=41, batch=16, dims=(203, 100, 77, 40), wdtype=wdtype, bh=32, bw=32, frac=0.6)
+    plans = [G.dev_plan(p, chunk_tiles=1) for p in probs]
+    mlp = B.pivot_mlp_plan(plans, 0)
+    try:
+        batches = (16, 1, 5, 1, 9, 3)
+        ws = G.workspace(max(B.pivot_mlp_workspace_bytes(mlp, b) for b in batches))
+        st = torch.cuda.current_stream().cuda_stream
+        bd = np.float16 if wdtype == WL.F16 else None
+        for b in batches:
+            x = np.ascontiguousarray(probs[0].x[:b])
+            for poison in (True, False):
+                xd = torch.from_numpy(np.full_like(x, np.nan) if poison else x).cuda()
+                yd = torch.full((b, probs[-1].M), float("nan"), dtype=torch.float32, device="cuda")
+                B.pivot_mlp_run(mlp, xd.data_ptr(), probs[0].K, yd.data_ptr(), probs[-1].M, b, ws.data_ptr(), ws.numel(), st)
+                torch.cuda.synchronize()
+            outs, scales, chain = O.oracle_mlp(_layers(probs), x, boundary_dtype=bd, return_all=True)
+            y = yd.cpu().numpy().astype(np.float64)
+            assert not np.isnan(y).any(), ("batch", b)
+            assert O.max_scaled_error(y, outs[-1], chain[-1]) <= G.TOL[wdtype], ("batch", b)
+    finally:
+        B.pivot_mlp_plan_destroy(mlp)
+        for h in plans:
+            B.pivot_fc_plan_destroy(h)
+
+
 # ------------------------------------------------------------------------ LSTM
 
 def _lstm_gpu(lp, plan, xs, h, c, want_z=True):

@@ -72,6 +72,56 @@ def test_plan_of_workload_shapes_scaled_down():
             assert v[name].tobytes() == want[name].tobytes(), (p.name, name)
 
 
+def _full_size_problems():
+    yield WL.config1(seed=0)
+    yield WL.config2(seed=0)
+    for frac in WL.CONFIG3_FRACS:
+        yield WL.config3(seed=0, frac=frac)
+    yield WL.config5(seed=0, steps=1).fc
+
+
+def test_plan_of_every_workload_at_full_size_is_bit_exact():
+    # configs 1, 2, 3 (all five densities) and 5 at full size, with the schedule the library itself picks
+    # (chunk_tiles = 0: the resolved chunk size is handed to the oracle's builder, which cuts and orders the
+    # schedule on its own)
+    for p in _full_size_problems():
+        plan = _host_plan(p, chunk_tiles=0)
+        v = B.pivot_fc_plan_host_view(plan)
+        B.pivot_fc_plan_destroy(plan)
+        want = O.oracle_plan(p.Wp, True, p.tile_mask, p.prow, p.pcol, p.bias, p.M, p.K, p.bh, p.bw, O.LAYOUT_BRC,
+                             v["chunk_tiles"])
+        assert (v["T"], v["M_pad"], v["K_pad"]) == (want["T"], want["M_pad"], want["K_pad"]), p.name
+        for name in PLAN_ARRAYS:
+            assert v[name].dtype == want[name].dtype and v[name].shape == want[name].shape, (p.name, name)
+            assert v[name].tobytes() == want[name].tobytes(), (p.name, name)
+
+
+@pytest.mark.parametrize("eliminated", [False, True])
+def test_config4_chain_plan_at_full_size_is_bit_exact(eliminated):
+    # the VGG-shaped chain: every layer's arrays and the composed boundary arrays q_l / dst_l (Section 4.2.1);
+    # identity boundaries exactly when pcol_{l+1} == prow_l (Section 4.2.3)
+    probs = WL.config4(seed=0, eliminated=eliminated)
+    plans = [_host_plan(p, chunk_tiles=0) for p in probs]
+    views = [B.pivot_fc_plan_host_view(h) for h in plans]
+    mlp = B.pivot_mlp_plan(plans, 0)
+    try:
+        mv = B.pivot_mlp_plan_host_view(mlp, views)
+    finally:
+        B.pivot_mlp_plan_destroy(mlp)
+        for h in plans:
+            B.pivot_fc_plan_destroy(h)
+    for p, v in zip(probs, views):
+        want = O.oracle_plan(p.Wp, True, p.tile_mask, p.prow, p.pcol, p.bias, p.M, p.K, p.bh, p.bw, O.LAYOUT_BRC,
+                             v["chunk_tiles"])
+        for name in PLAN_ARRAYS:
+            assert v[name].tobytes() == want[name].tobytes(), (p.name, name)
+    qs, dsts = O.oracle_mlp_plan([p.prow for p in probs], [p.pcol for p in probs], [p.nbr * p.bh for p in probs])
+    assert mv["identity"] == [int(eliminated)] * 2
+    for l in range(2):
+        assert mv["q"][l].tobytes() == qs[l].tobytes()
+        assert mv["dst"][l].tobytes() == dsts[l].tobytes()
+
+
 def test_null_bias_is_zero_and_default_chunking_is_valid():
     p = WL.gen_fc(64, 64, 8, 8, 0.5, seed=3)
     plan = _host_plan(p, chunk_tiles=0, bias=False)
@@ -123,7 +173,7 @@ def test_source_ordered_gather_lists():
                 assert np.all(np.diff(src) >= 0), (p.name, br)                    # padding (all ones) sorts last
                 want = (np.repeat(v["col_idx"][tb:te], bw) * bw + np.tile(np.arange(bw), te - tb)) if blk \
                     else v["xidx"][tb * bw:te * bw]
-                want = np.where(want < 0, none, want)[pos]
+                want = np.where((want >= v["K"]) if blk else (want < 0), none, want)[pos]   # padding columns
                 assert np.array_equal(src, want), (p.name, br, blk)
     for p in (WL.gen_fc(64, 64, 16, 32, 0.5, seed=1, wdtype=WL.F32), WL.gen_fc(64, 64, 8, 8, 0.5, seed=1, wdtype=WL.F16)):
         plan = _host_plan(p, chunk_tiles=0)

@@ -286,6 +286,116 @@ def test_mlp_boundary_rounding_happens_once_between_layers():
     assert np.array_equal(outs[1], want)
 
 
+def _chain_scale_loops(layers, x):
+    """S_L of a chain written out with scalar loops: S_1 = D_1, S_l[i] = sum_j |W_l[i][j]| S_{l-1}[j] + D_l[i],
+    D_l[i] = sum_j |W_l[i][j]| |h_{l-1}[j]| + |b_l[i]|, everything in natural coordinates from the definition of
+    the masked matrix (tile of block-space (r,c) kept), no call into the oracle."""
+    h = [float(v) for v in x]
+    S = None
+    for L in layers:
+        Wp, tm, prow, pcol, b = L["Wp"], L["tile_mask"], L["prow"], L["pcol"], L["bias"]
+        M, K, bh, bw = Wp.shape[0], Wp.shape[1], L["bh"], L["bw"]
+        Wd = [[0.0] * K for _ in range(M)]
+        for r in range(M):
+            for c in range(K):
+                if tm[r // bh][c // bw]:
+                    Wd[int(prow[r])][int(pcol[c])] = float(Wp[r][c])
+        z = [sum(Wd[i][j] * h[j] for j in range(K)) + float(b[i]) for i in range(M)]
+        D = [sum(abs(Wd[i][j]) * abs(h[j]) for j in range(K)) + abs(float(b[i])) for i in range(M)]
+        S = D if S is None else [sum(abs(Wd[i][j]) * S[j] for j in range(K)) + D[i] for i in range(M)]
+        h = [max(v, 0.0) for v in z] if L["act"] == O.ACT_RELU else z
+    return S, D, h
+
+
+def test_chain_error_scale_against_scalar_loops():
+    # the scale every chain parity gate divides by, recomputed with plain loops on a tiny three-layer chain
+    probs = WL.config4(seed=11, dims=(14, 9, 11, 6), bh=2, bw=3, frac=0.5)
+    layers = _as_layers(probs)
+    outs, scales, chain = O.oracle_mlp(layers, probs[0].x, return_all=True)
+    S, D, h = _chain_scale_loops(layers, probs[0].x[0])
+    assert np.allclose(chain[-1][0], S, rtol=1e-12, atol=0)
+    assert np.allclose(scales[-1][0], D, rtol=1e-12, atol=0)
+    assert np.allclose(outs[-1][0], h, rtol=1e-12, atol=1e-15)
+    # S_L >= D_L always, and strictly larger wherever an earlier layer feeds the output
+    assert np.all(chain[-1] >= scales[-1]) and np.any(chain[-1] > scales[-1] * 1.01)
+    # one layer: the chain scale is the layer scale
+    o1, s1, c1 = O.oracle_mlp(layers[:1], probs[0].x, return_all=True)
+    assert np.array_equal(c1[0], s1[0])
+
+
+def _perturbed_chain(layers, x, eps, target):
+    """The chain in float64 with every layer's pre-activation pushed by eps*D_l, signs chosen so that every push
+    moves output `target` of the last layer upwards (the worst case a per-layer relative error eps allows, to
+    first order).  Signs come from back-propagating through |.|-free products: sign of d out[target] / d z_l[i]."""
+    Wds = [O.dense_masked_natural(L["Wp"], L["tile_mask"], L["prow"], L["pcol"], L["bh"], L["bw"]) for L in layers]
+    hs, zs = [np.asarray(x, dtype=np.float64)], []
+    for L, Wd in zip(layers, Wds):
+        z = hs[-1] @ Wd.T + np.asarray(L["bias"], dtype=np.float64)
+        zs.append(z)
+        hs.append(np.maximum(z, 0) if L["act"] == O.ACT_RELU else z)
+    g = np.zeros(Wds[-1].shape[0]); g[target] = 1.0
+    signs = [None] * len(layers)
+    for l in range(len(layers) - 1, -1, -1):
+        if layers[l]["act"] == O.ACT_RELU:
+            g = g * (zs[l][0] > 0)
+        signs[l] = np.sign(g)
+        g = g @ Wds[l]
+    h = np.asarray(x, dtype=np.float64)
+    for l, (L, Wd) in enumerate(zip(layers, Wds)):
+        z = h @ Wd.T + np.asarray(L["bias"], dtype=np.float64)
+        D = np.abs(h) @ np.abs(Wd).T + np.abs(np.asarray(L["bias"], dtype=np.float64))
+        z = z + eps * signs[l] * D
+        h = np.maximum(z, 0) if L["act"] == O.ACT_RELU else z
+    return h
+
+
+def test_chain_error_scale_bounds_a_per_layer_relative_error_and_the_layer_scale_does_not():
+    # why chains are gated against eps*S_L: a relative error eps in EVERY layer (each within its own eps*D_l) can
+    # move the last output by more than eps*D_L, but never (to first order) by more than eps*S_L
+    probs = WL.config4(seed=12, dims=(48, 40, 32, 24), bh=4, bw=4, frac=0.5)
+    layers = _as_layers(probs)
+    outs, scales, chain = O.oracle_mlp(layers, probs[0].x, return_all=True)
+    eps = 1e-7
+    worst_S, worst_D = 0.0, 0.0
+    for target in range(24):
+        y = _perturbed_chain(layers, probs[0].x, eps, target)
+        d = abs(y[0][target] - outs[-1][0][target])
+        worst_S = max(worst_S, d / (eps * chain[-1][0][target]))
+        worst_D = max(worst_D, d / (eps * scales[-1][0][target]))
+    assert worst_S <= 1.0 + 1e-4            # never above eps*S_L (second-order terms are ~eps)
+    assert worst_S > 0.2                    # and S_L is not loose: the worst case reaches a third of it (the rest
+                                            # of S_L are paths through units the ReLU has switched off)
+    assert worst_D > 1.05                   # eps*D_L alone IS exceeded by an error every layer is allowed to make
+
+
+def test_gather_index_composed_with_the_tile_list():
+    # xidx[t*bw + c] = pcol_pad[col_idx[t]*bw + c]: x index of column c of kept tile t, -1 in padding columns
+    for M, K, bh, bw, seed in ((21, 30, 4, 8, 1), (12, 9, 2, 3, 2), (16, 16, 4, 4, 3)):
+        p = WL.gen_fc(M, K, bh, bw, 0.5, seed=seed)
+        plan = O.oracle_plan(p.Wp, True, p.tile_mask, p.prow, p.pcol, p.bias, M, K, bh, bw, O.LAYOUT_BRC, 2)
+        T = plan["T"]
+        assert plan["xidx"].shape == (T * bw,) and plan["xidx"].dtype == np.int32
+        t = 0
+        for i in range(p.nbr):
+            for j in range(p.nbc):
+                if not p.tile_mask[i][j]:
+                    continue
+                for c in range(bw):
+                    col = j * bw + c                                  # block-space column
+                    want = int(p.pcol[col]) if col < K else -1
+                    assert plan["xidx"][t * bw + c] == want
+                    assert plan["xidx"][t * bw + c] == plan["pcol_pad"][plan["col_idx"][t] * bw + c]
+                t += 1
+        assert t == T
+        # and it is the gather Listing 1 does: x[xidx] spells the x-segments of the kept tiles in block order
+        x = np.arange(K, dtype=np.float64) + 100.0
+        xg = np.concatenate([x[p.pcol], np.zeros(p.nbc * bw - K)])
+        seg = np.where(plan["xidx"] >= 0, x[np.maximum(plan["xidx"], 0)], 0.0)
+        for t in range(T):
+            j = plan["col_idx"][t]
+            assert np.array_equal(seg[t * bw:(t + 1) * bw], xg[j * bw:(j + 1) * bw])
+
+
 # -------------------------------------------------------------------- the plan
 
 def test_value_offset_hand_computed_and_bijective():
