@@ -31,17 +31,24 @@ HBM_PEAK_GBS = 8000.0            # MI355X published HBM3E peak
 COLD_FOOTPRINT = 2 * (256 + 32) * (1 << 20)   # rotate through >= 2 x (Infinity Cache + all L2)
 
 
+TRAFFIC_FILE = os.path.join("profiles", "fc_gemv_cfg2_hbm_traffic.txt")
+
+
 def parse_traffic():
-    """HBM bytes per launch measured with rocprofv3 --pmc (profiles/*.txt), or None."""
-    path = os.path.join(ROOT, "profiles", "fc_gemv_cfg2_hbm_traffic.txt")
+    """HBM bytes per launch as measured with rocprofv3 --pmc in an EARLIER run of this command (the committed
+    summary under profiles/; counters cannot be read from inside this process) and the date it was taken, or
+    (None, None)."""
+    val, date = None, None
     try:
-        with open(path) as f:
+        with open(os.path.join(ROOT, TRAFFIC_FILE)) as f:
             for line in f:
                 if line.startswith("traffic_bytes_per_launch"):
-                    return float(line.split("=")[1].split()[0])
+                    val = float(line.split("=")[1].split()[0])
+                elif line.startswith("measured_on"):
+                    date = line.split("=")[1].strip()
     except OSError:
         pass
-    return None
+    return val, date
 
 
 def main():
@@ -101,31 +108,44 @@ def main():
 
     # The K timed steps are replays of captured graphs of plain kernel launches, so that the host's
     # launch cost (about 5 us per call through Python, more than the GPU needs) is not what is timed.
-    # A graph holds a whole number of rotations through the cold copies; K = full replays + one
-    # remainder graph, exactly K launches between the two events.
+    # Cold protocol: launch i uses copy i % ncopies.  The warm-up is whole rotations through ALL copies (at
+    # least W launches, at least one rotation) and ends on the last copy; the timed region starts on copy 0.
+    # Every timed launch therefore finds ncopies - 1 other copies (>= 2 x Infinity Cache + L2) touched since
+    # its own copy was last read, whatever K is; K = whole-rotation graphs + one remainder graph, exactly K
+    # launches between the first and the last event.  An event after every replay gives the spread.
     def timed(K_, W_, rotate):
         per = ncopies * max(1, 80 // ncopies) if rotate else 100
-        per = min(per, K_)
         full, rem = divmod(K_, per)
-        g_full = BU.capture(lambda i, s: step(i, s, rotate), per)
+        g_rot = BU.capture(lambda i, s: step(i, s, rotate), per)
         g_rem = BU.capture(lambda i, s: step(i, s, rotate), rem) if rem else None
-        for _ in range(max(1, W_ // per)):
-            g_full.replay()
+        warm_replays = max(1, -(-W_ // per))
+        for _ in range(warm_replays):
+            g_rot.replay()
         torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(full + (1 if rem else 0) + 1)]
         t0 = time.perf_counter()
-        e0.record()
-        for _ in range(full):
-            g_full.replay()
+        # one more untimed rotation enqueued right in front of the first event: the timed launches then follow a
+        # busy queue back to back, as every later launch of a long run does (otherwise the start-up of the first
+        # replay from an idle device, several microseconds, is spread over the K launches and a short run
+        # reads 0.3 us per launch slower than a long one)
+        g_rot.replay()
+        ev[0].record()
+        for r in range(full):
+            g_rot.replay()
+            ev[r + 1].record()
         if g_rem is not None:
             g_rem.replay()
-        e1.record()
+            ev[-1].record()
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
-        return e0.elapsed_time(e1) / K_, wall / K_ * 1e3
+        counts = [per] * full + ([rem] if rem else [])
+        per_replay_us = [ev[r].elapsed_time(ev[r + 1]) * 1e3 / counts[r] for r in range(len(counts))]
+        return dict(ms=ev[0].elapsed_time(ev[-1]) / K_, wall_ms=wall / (K_ + per) * 1e3, replay_us=per_replay_us,
+                    warmup_launches=(warm_replays + 1) * per, copies_touched=ncopies if rotate else 1)
 
-    cold_ms, cold_wall_ms = timed(K, Wm, True)
-    warm_ms, _ = timed(K, Wm, False)
+    cold = timed(K, Wm, True)
+    warm = timed(K, Wm, False)
+    cold_ms, cold_wall_ms, warm_ms = cold["ms"], cold["wall_ms"], warm["ms"]
 
     # the same K steps launched eagerly from Python (host-bound for small layers; reported for reference)
     for i in range(Wm):
@@ -169,11 +189,8 @@ def main():
     dense_best_us = min(dense_us, torch_mv_us)
 
     cold_us, warm_us = cold_ms * 1e3, warm_ms * 1e3
-    # the instantiation the library launches for this plan (row slice height, tile width, batch rows, wavefronts,
-    # gather from an LDS copy of x: taken when a work item streams >= 48 KB and x fits)
-    slice_rows = p.bh // view["row_slices"]
-    lds_copy = view["chunk_tiles"] * slice_rows * p.bw * 4 >= 48 * 1024 and p.K % 4 == 0 and p.K * 4 <= 8 * view["wg_waves"] * 64 * 16
-    kernel_name = "pivot::fc_gemv_kernel<float, %d, %d, 1, %d, %d>" % (slice_rows, p.bw, view["wg_waves"], 1 if lds_copy else 0)
+    kernel_name = B.pivot_fc_kernel_name(plan0, 1)       # the instantiation the library launches for this plan
+    traffic, traffic_date = parse_traffic()
     kept = p.T / float(p.nbr * p.nbc)
     achieved = alg_bytes / (cold_us * 1e-6) / 1e9
     out = {
@@ -192,11 +209,17 @@ def main():
                    "seed": args.seed, "kept_fraction": round(kept, 5), "tiles": p.T,
                    "chunk_tiles": view["chunk_tiles"], "work_items": view["nchunks"] * view["row_slices"], "row_slices": view["row_slices"],
                    "wg_waves": view["wg_waves"],
-                   "cold_copies": ncopies},
+                   "cold_copies": ncopies, "cold_copies_touched": cold["copies_touched"],
+                   "warmup_launches": cold["warmup_launches"]},
+        "cold_us_per_replay": {"median": round(float(np.median(cold["replay_us"])), 3), "min": round(min(cold["replay_us"]), 3),
+                               "replays": len(cold["replay_us"])},
+        "warm_us_per_replay": {"median": round(float(np.median(warm["replay_us"])), 3), "min": round(min(warm["replay_us"]), 3)},
         "warm_us": round(warm_us, 3),
         "cold_host_clock_us": round(cold_wall_ms * 1e3, 3),
         "cold_eager_python_launch_us": round(eager_cold_us, 3),
-        "timing": "HIP events around replays of captured graphs of plain launches (exactly K launches)",
+        "timing": "HIP events around replays of captured graphs of plain launches (exactly K launches between the first "
+                  "and the last event; an untimed rotation through all copies is enqueued directly in front of the "
+                  "first event so that the timed launches follow a busy queue)",
         "null_kernel_us": round(null_us, 3),
         "read_only_launch_us": {"cold": round(floor_cold_us, 3), "warm": round(floor_warm_us, 3),
                                 "note": "one launch that only reads the same number of bytes (pivot_stream_read_run)"},
@@ -207,7 +230,9 @@ def main():
         "algorithmic_bytes": alg_bytes,
         "roofline": {"bound": "hbm", "kernel": kernel_name, "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": parse_traffic(),
+                     "traffic": traffic,
+                     "traffic_source": "%s: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command on %s, "
+                                       "not measured by this run" % (TRAFFIC_FILE, traffic_date),
                      "warm_effective": round(alg_bytes / (warm_us * 1e-6) / 1e9, 1)},
     }
 
@@ -222,15 +247,28 @@ def main():
         y_ref = O.fc_dense(Wd, p.x, p.bias, p.act)       # warm-up + parity of the timed configuration
         D = O.error_scale(Wd, p.x, p.bias)
         err = O.max_scaled_error(ys[0].cpu().numpy(), y_ref, D)
-        t0 = time.perf_counter()
-        n = 0
-        while time.perf_counter() - t0 < 10.0:
+        def time_oracle(seconds):
             O.fc_dense(Wd, p.x, p.bias, p.act)
-            n += 1
-        cpu_us = (time.perf_counter() - t0) / n * 1e6
+            t0 = time.perf_counter()
+            n = 0
+            while time.perf_counter() - t0 < seconds:
+                O.fc_dense(Wd, p.x, p.bias, p.act)
+                n += 1
+            return (time.perf_counter() - t0) / n * 1e6, n
+
+        cpu_us, n = time_oracle(10.0)
         out["cpu_baseline"] = {"value": round(cpu_us, 1), "unit": "us/layer", "cores": int(cores), "kind": "oracle",
                                "sample": "%d applications of the same layer (float64 dense masked matvec, matrix "
-                                         "prebuilt), about 10 s" % n}
+                                         "prebuilt), about 10 s; host cores visible: %d"
+                                         % (n, len(os.sched_getaffinity(0)))}
+        try:
+            from threadpoolctl import threadpool_limits
+            with threadpool_limits(limits=1):
+                cpu1_us, n1 = time_oracle(6.0)
+            out["cpu_baseline_1thread"] = {"value": round(cpu1_us, 1), "unit": "us/layer", "cores": 1, "kind": "oracle",
+                                           "sample": "%d applications, about 6 s, BLAS limited to one thread" % n1}
+        except Exception as exc:                            # threadpoolctl missing: say so instead of a number
+            out["cpu_baseline_1thread"] = {"value": None, "note": "not measured: %s" % exc}
         out["parity_max_scaled_error"] = err
         if not (err <= 1e-5):
             print("bench.py: parity check failed (%.3g)" % err, file=sys.stderr)

@@ -4,7 +4,10 @@ one MI355X: cache-cold and warm microseconds per layer application, effective
 GB/s against the 8 TB/s HBM roofline, and the same layer dense on the GPU.
 Prints one JSON line per case and a markdown table at the end.
 
-    python bench_configs.py [--configs 1,2,3,4,5] [--seed 0] [--iters 300]
+Every time is the median (and the minimum) of five measurements, each a HIP-event pair around several
+replays of a captured graph of plain launches.
+
+    python bench_configs.py [--configs 1,2,3,4,5] [--seeds 0,1,2]
 """
 from __future__ import annotations
 
@@ -49,8 +52,19 @@ def gt(enqueue, n_launch, replays=4):
     return BU.graph_time(enqueue, n_launch, replays=replays, repeats=3)
 
 
+def gts(enqueue, n_launch, replays=4):
+    """(median, min) of five such measurements."""
+    return BU.graph_time(enqueue, n_launch, replays=replays, repeats=5, stats=True)
+
+
 def emit(name, us_cold, us_warm, alg_bytes, dense_us=None, extra=None):
-    row = {"case": name, "cold_us": None if us_cold is None else round(us_cold, 2), "warm_us": round(us_warm, 2),
+    cold_min = warm_min = None
+    if isinstance(us_cold, tuple):
+        us_cold, cold_min = us_cold
+    if isinstance(us_warm, tuple):
+        us_warm, warm_min = us_warm
+    row = {"case": name, "cold_min_us": None if cold_min is None else round(cold_min, 2),
+           "warm_min_us": None if warm_min is None else round(warm_min, 2), "cold_us": None if us_cold is None else round(us_cold, 2), "warm_us": round(us_warm, 2),
            "alg_MB": round(alg_bytes / 1e6, 3),
            "cold_GBs": None if us_cold is None else round(alg_bytes / us_cold / 1e3, 1),
            "cold_frac": None if us_cold is None else round(alg_bytes / us_cold / 1e3 / HBM, 4),
@@ -87,8 +101,8 @@ def time_fc(p, iters, name, dense=True):
             B.pivot_fc_run(plans[j], xs[j].data_ptr(), p.K, yd.data_ptr(), p.M, batch, ws.data_ptr(), ws.numel(), s)
         return f
 
-    cold = gt(go(True), ncopies * max(1, 64 // ncopies))
-    warm = gt(go(False), 100)
+    cold = gts(go(True), ncopies * max(1, 64 // ncopies))
+    warm = gts(go(False), 100)
     dense_us = None
     if dense:
         Wnat = np.empty_like(p.Wp)
@@ -142,8 +156,8 @@ def time_chain(probs, iters, name, per_layer=False):
             B.pivot_mlp_run(sets[j][1], xs[j].data_ptr(), probs[0].K, yd.data_ptr(), M, 1, ws.data_ptr(), ws.numel(), s)
         return f
 
-    cold = gt(go(True), ncopies * max(1, 24 // ncopies))
-    warm = gt(go(False), 40)
+    cold = gts(go(True), ncopies * max(1, 24 // ncopies))
+    warm = gts(go(False), 40)
     torch.cuda.synchronize()
     for plans, mlp in sets:
         assert B.pivot_mlp_status(mlp, st) == 0
@@ -170,21 +184,41 @@ def time_lstm(lp, name, per_step=False):
         B.pivot_lstm_run(plan, lp.H, lp.I, xsd.data_ptr(), hd.data_ptr(), cd.data_ptr(), None, steps, batch,
                          ws.data_ptr(), ws.numel(), s)
 
-    total = gt(go, 1, replays=5)
+    total, total_min = gts(go, 1, replays=5)
     assert B.pivot_lstm_status(plan, steps, batch, ws.data_ptr(), st) == 0
+    # the first step finds the weights in HBM, the other 255 on chip: a one-step sequence timed over rotating
+    # copies of the plan (cold) and on one copy (warm); each includes the set-up kernels of a sequence
     alg = p.algorithmic_bytes(batch)
-    emit(name, None, total / steps, alg, None,
-         {"steps": steps, "total_us": round(total, 1), "note": "per-step time of the whole sequence (matvec + cell, set-up "
-          "kernels included); the weights stay on chip after step 1"})
-    B.pivot_fc_plan_destroy(plan)
+    ncopies = int(max(2, -(-COLD_FOOTPRINT // alg)))
+    plans = [plan] + [B.pivot_fc_plan_clone(plan) for _ in range(ncopies - 1)]
+    ws1 = workspace(B.pivot_lstm_workspace_bytes(plan, lp.H, lp.I, 1, batch))
+
+    def one(rot):
+        def f(i, s):
+            B.pivot_lstm_run(plans[i % ncopies if rot else 0], lp.H, lp.I, xsd.data_ptr(), hd.data_ptr(), cd.data_ptr(), None,
+                             1, batch, ws1.data_ptr(), ws1.numel(), s)
+        return f
+    first_cold = gts(one(True), ncopies)
+    first_warm = gts(one(False), 50)
+    emit(name, None, (total / steps, total_min / steps), alg, None,
+         {"steps": steps, "total_us": round(total, 1), "total_min_us": round(total_min, 1),
+          "first_step_cold_us": round(first_cold[0], 2), "first_step_cold_min_us": round(first_cold[1], 2),
+          "first_step_warm_us": round(first_warm[0], 2),
+          "note": "warm_us = per-step time of the whole sequence (matvec + cell, set-up kernels included; the weights stay "
+                  "on chip after step 1); first_step_* = a sequence of ONE step, set-up kernels included, over rotating "
+                  "copies of the plan (cold) or one copy (warm)"})
+    for h in plans:
+        B.pivot_fc_plan_destroy(h)
+    torch.cuda.empty_cache()
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--configs", default="1,2,3,4,5")
-    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--seeds", default="0,1,2")
     ap.add_argument("--iters", type=int, default=300)
     args = ap.parse_args()
+    seeds = [int(v) for v in args.seeds.split(",")]
     which = set(args.configs.split(","))
     assert torch.cuda.is_available(), "needs a GPU"
     B.lib()
@@ -194,35 +228,37 @@ def main():
         return gt(lambda i, s: B.pivot_null_run(s), 200, replays=10)
 
     print(json.dumps({"case": "null kernel back to back", "us": round(null_us(), 2)}), flush=True)
-    if "1" in which:
-        time_fc(WL.config1(seed=args.seed), args.iters, "cfg1 1024x1024 f32 16x16 25% b1")
-    if "2" in which:
-        time_fc(WL.config2(seed=args.seed), args.iters, "cfg2 4096x9216 f32 32x32 10% bal b1")
-    if "3" in which:
-        for frac in WL.CONFIG3_FRACS:
-            for batch in (1, 4, 16):
-                time_fc(WL.config3(seed=args.seed, batch=batch, frac=frac), args.iters,
-                        "cfg3 4096x4096 f16 64x16 %g%% b%d" % (frac * 100, batch))
-    if "4" in which:
-        for elim in (False, True):
-            for per_layer in (False, True):
-                time_chain(WL.config4(seed=args.seed, eliminated=elim), args.iters,
-                           "cfg4 MLP 25088-4096-4096-1000 f32 %s, %s" % ("eliminated" if elim else "composed",
-                                                                       "launch per layer" if per_layer else "one launch"),
-                           per_layer=per_layer)
-    if "5" in which:
-        time_lstm(WL.config5(seed=args.seed), "cfg5 LSTM gates 8192x3072 f16 16x32 zipf b8, 256 steps, one launch")
-        time_lstm(WL.config5(seed=args.seed), "cfg5 LSTM gates 8192x3072 f16 16x32 zipf b8, 256 steps, launch per step",
-                  per_step=True)
+    for seed in seeds:
+        tag = " seed %d" % seed
+        if "1" in which:
+            time_fc(WL.config1(seed=seed), args.iters, "cfg1 1024x1024 f32 16x16 25% b1" + tag)
+        if "2" in which:
+            time_fc(WL.config2(seed=seed), args.iters, "cfg2 4096x9216 f32 32x32 10% bal b1" + tag)
+        if "3" in which:
+            for frac in WL.CONFIG3_FRACS:
+                for batch in (1, 4, 16):
+                    time_fc(WL.config3(seed=seed, batch=batch, frac=frac), args.iters,
+                            "cfg3 4096x4096 f16 64x16 %g%% b%d" % (frac * 100, batch) + tag, dense=(seed == seeds[0]))
+        if "4" in which:
+            for elim in (False, True):
+                for per_layer in (False, True):
+                    time_chain(WL.config4(seed=seed, eliminated=elim), args.iters,
+                               "cfg4 MLP 25088-4096-4096-1000 f32 %s, %s" % ("eliminated" if elim else "composed",
+                                                                           "launch per layer" if per_layer else "one launch") + tag,
+                               per_layer=per_layer)
+        if "5" in which:
+            time_lstm(WL.config5(seed=seed), "cfg5 LSTM gates 8192x3072 f16 16x32 zipf b8, 256 steps, one launch" + tag)
+            time_lstm(WL.config5(seed=seed), "cfg5 LSTM gates 8192x3072 f16 16x32 zipf b8, 256 steps, launch per step" + tag,
+                      per_step=True)
 
-    print("\n| case | kept | cold us | cold GB/s | % of 8 TB/s | read-only launch, cold us | warm us | warm GB/s | dense us (best of own, rocBLAS) | speedup vs dense |")
-    print("|---|---|---|---|---|---|---|---|---|---|")
+    print("\n| case | kept | cold us (median) | cold us (min) | cold GB/s | % of 8 TB/s | read-only launch, cold us | warm us (median) | warm us (min) | warm GB/s | first step cold us | dense us (best of own, rocBLAS) | speedup vs dense |")
+    print("|---|---|---|---|---|---|---|---|---|---|---|---|---|")
     for r in ROWS:
         f = lambda k, fmt="%s": ("-" if r.get(k) is None else fmt % r[k])
-        print("| %s | %s | %s | %s | %s | %s | %s | %s | %s | %s |" % (
-            r["case"], f("kept"), f("cold_us"), f("cold_GBs"),
+        print("| %s | %s | %s | %s | %s | %s | %s | %s | %s | %s | %s | %s | %s |" % (
+            r["case"], f("kept"), f("cold_us"), f("cold_min_us"), f("cold_GBs"),
             "-" if r.get("cold_frac") is None else "%.1f" % (100 * r["cold_frac"]), f("read_only_cold_us"),
-            f("warm_us"), f("warm_GBs"), f("dense_us"), f("speedup_vs_dense")))
+            f("warm_us"), f("warm_min_us"), f("warm_GBs"), f("first_step_cold_us"), f("dense_us"), f("speedup_vs_dense")))
 
 
 if __name__ == "__main__":

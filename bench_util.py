@@ -37,8 +37,9 @@ def capture(enqueue, n_launch):
     return g
 
 
-def time_graph(g, n_launch, replays, warm_replays=2, repeats=1):
-    """us per launch: HIP events around `replays` replays of a graph of n_launch launches."""
+def time_graph(g, n_launch, replays, warm_replays=2, repeats=1, stats=False):
+    """us per launch: HIP events around `replays` replays of a graph of n_launch launches; the median over
+    `repeats` such measurements (stats=True: the pair (median, min))."""
     for _ in range(warm_replays):
         g.replay()
     torch.cuda.synchronize()
@@ -51,12 +52,14 @@ def time_graph(g, n_launch, replays, warm_replays=2, repeats=1):
         e1.record()
         torch.cuda.synchronize()
         ts.append(e0.elapsed_time(e1) * 1e3 / (replays * n_launch))
+    if stats:
+        return float(np.median(ts)), float(min(ts))
     return float(np.median(ts))
 
 
-def graph_time(enqueue, n_launch, replays=5, repeats=3):
+def graph_time(enqueue, n_launch, replays=5, repeats=3, stats=False):
     g = capture(enqueue, n_launch)
-    return time_graph(g, n_launch, replays, repeats=repeats)
+    return time_graph(g, n_launch, replays, repeats=repeats, stats=stats)
 
 
 _floor_cache = {}

@@ -211,6 +211,13 @@ int  pivot_fc_run(const pivot_fc_plan_t* plan, const void* x_dev, int64_t ldx,
                   void* y_dev, int64_t ldy, int batch,
                   void* ws_dev, size_t ws_bytes, void* stream);
 
+/* Which kernel instantiation pivot_fc_run launches for this plan at this
+ * batch ("pivot::fc_gemv_kernel<float, 16, 32, 1, 8, 1>": the name a profiler
+ * shows), for an x that is 16-byte aligned with densely packed rows (other
+ * inputs take the form that gathers from global memory).  buf receives at
+ * most buf_len bytes including the terminating 0.  Needs no device. */
+int  pivot_fc_kernel_name(const pivot_fc_plan_t* plan, int batch, char* buf, size_t buf_len);
+
 /*
  * Chains of layers (Section 4.2).  Between layer l and l+1 the producer's row
  * scatter and the consumer's column gather are composed at plan time into one
@@ -266,6 +273,17 @@ int    pivot_mlp_run(const pivot_mlp_plan_t* plan, const void* x_dev, int64_t ld
                      void* ws_dev, size_t ws_bytes, void* stream);
 /* *status = 0 if every one-launch run of this chain since the last call completed, 1 if a wait gave up. */
 int    pivot_mlp_status(const pivot_mlp_plan_t* plan, void* stream, int* status);
+/* The same information without a synchronising call: *word_dev receives the device address of the chain's
+ * status word (a uint32 owned by the chain plan; NULL if the chain has no one-launch form).  It reads 0 while
+ * every one-launch run since the last pivot_mlp_status completed and 1 once a wait has given up; the caller
+ * may read it on its own schedule, e.g. with an asynchronous copy to pinned host memory enqueued behind the
+ * run, or from a kernel of its own.  When it reads 1 the outputs of that run are undefined and the caller
+ * has to run the chain again through a chain plan made with PIVOT_MLP_LAUNCH_PER_LAYER (whose kernels wait
+ * for nothing).  When to choose which form: the one-launch form needs the device to itself for the few
+ * microseconds it runs (its workgroups wait for each other and must all be resident); a process that shares
+ * the GPU with other streams or processes that can occupy compute units for long should make its chain
+ * plans with PIVOT_MLP_LAUNCH_PER_LAYER, and its recurrent plans with PIVOT_PLAN_LSTM_LAUNCH_PER_STEP. */
+int    pivot_mlp_status_word(const pivot_mlp_plan_t* plan, const uint32_t** word_dev);
 
 /*
  * Recurrent use: an LSTM whose gate matrix (4H x (H+I), gate order i,f,g,o,
@@ -281,7 +299,7 @@ int    pivot_mlp_status(const pivot_mlp_plan_t* plan, void* stream, int* status)
  *   z_dbg    device, optional [batch][4H] fp32: gate pre-activations of the
  *            last step in natural order (NULL to skip)
  *
- * Two forms.  Plans with fp16 16x32 BRC tiles, batch <= 8, at most 16 kept
+ * Two forms.  Plans with fp16 16x32 BRC tiles, batch <= 8, at most 15 kept
  * tiles per wavefront of a full-device grid (one workgroup per compute unit,
  * all co-resident) and K_pad/32 <= that grid run the whole sequence in ONE
  * launch: the kept tiles stay in registers for all steps and per step only h,
@@ -297,6 +315,10 @@ int    pivot_mlp_status(const pivot_mlp_plan_t* plan, void* stream, int* status)
  */
 size_t pivot_lstm_workspace_bytes(const pivot_fc_plan_t* plan, int H, int I, int steps, int batch);
 int    pivot_lstm_status(const pivot_fc_plan_t* plan, int steps, int batch, const void* ws_dev, void* stream, int* status);
+/* Device address of that status word inside the workspace (for the same steps and batch), for callers that
+ * read it on their own schedule instead of synchronising; see pivot_mlp_status_word.  The launch-per-step
+ * form leaves it at 0. */
+int    pivot_lstm_status_word(const pivot_fc_plan_t* plan, int steps, int batch, const void* ws_dev, const uint32_t** word_dev);
 int    pivot_lstm_run(const pivot_fc_plan_t* plan, int H, int I, const void* xs_dev,
                       float* h_dev, float* c_dev, float* z_dbg, int steps, int batch,
                       void* ws_dev, size_t ws_bytes, void* stream);

@@ -29,10 +29,10 @@ PIVOT_E_ALLOC, PIVOT_E_HIP, PIVOT_E_WORKSPACE, PIVOT_E_NO_DEVICE = -5, -6, -7, -
 EXPORTS = [
     "pivot_version", "pivot_last_error",
     "pivot_fc_plan", "pivot_fc_plan_host_view", "pivot_fc_plan_clone", "pivot_fc_plan_destroy",
-    "pivot_fc_workspace_bytes", "pivot_workspace_init", "pivot_fc_run",
+    "pivot_fc_workspace_bytes", "pivot_workspace_init", "pivot_fc_run", "pivot_fc_kernel_name",
     "pivot_mlp_plan", "pivot_mlp_plan_host_view", "pivot_mlp_plan_destroy",
-    "pivot_mlp_workspace_bytes", "pivot_mlp_run", "pivot_mlp_status",
-    "pivot_lstm_workspace_bytes", "pivot_lstm_run", "pivot_lstm_status",
+    "pivot_mlp_workspace_bytes", "pivot_mlp_run", "pivot_mlp_status", "pivot_mlp_status_word",
+    "pivot_lstm_workspace_bytes", "pivot_lstm_run", "pivot_lstm_status", "pivot_lstm_status_word",
     "pivot_dense_run", "pivot_csr_run", "pivot_null_run", "pivot_stream_read_run", "pivot_feedback_search",
 ]
 
@@ -99,6 +99,7 @@ def lib():
     L.pivot_fc_workspace_bytes.restype = sz
     L.pivot_workspace_init.argtypes = [vp, sz, vp]
     L.pivot_fc_run.argtypes = [vp, vp, i64, vp, i64, i32, vp, sz, vp]
+    L.pivot_fc_kernel_name.argtypes = [vp, i32, C.c_char_p, sz]
     L.pivot_mlp_plan.argtypes = [C.POINTER(vp), i32, i32, C.POINTER(vp)]
     L.pivot_mlp_plan_host_view.argtypes = [vp, C.POINTER(pivot_mlp_view)]
     L.pivot_mlp_plan_destroy.argtypes = [vp]
@@ -107,6 +108,8 @@ def lib():
     L.pivot_mlp_workspace_bytes.restype = sz
     L.pivot_mlp_run.argtypes = [vp, vp, i64, vp, i64, i32, vp, sz, vp]
     L.pivot_mlp_status.argtypes = [vp, vp, C.POINTER(C.c_int)]
+    L.pivot_mlp_status_word.argtypes = [vp, C.POINTER(vp)]
+    L.pivot_lstm_status_word.argtypes = [vp, i32, i32, vp, C.POINTER(vp)]
     L.pivot_lstm_workspace_bytes.argtypes = [vp, i32, i32, i32, i32]
     L.pivot_lstm_workspace_bytes.restype = sz
     L.pivot_lstm_run.argtypes = [vp, i32, i32, vp, vp, vp, vp, i32, i32, vp, sz, vp]
@@ -203,6 +206,13 @@ def pivot_fc_run(plan, x_ptr, ldx, y_ptr, ldy, batch, ws_ptr, ws_bytes, stream=N
     _check(lib().pivot_fc_run(plan, x_ptr, ldx, y_ptr, ldy, batch, ws_ptr, ws_bytes, stream))
 
 
+def pivot_fc_kernel_name(plan, batch):
+    """Name of the kernel instantiation pivot_fc_run launches for this plan and batch."""
+    buf = C.create_string_buffer(256)
+    _check(lib().pivot_fc_kernel_name(plan, batch, buf, 256))
+    return buf.value.decode()
+
+
 def pivot_mlp_plan(layer_plans, flags=0):
     n = len(layer_plans)
     arr = (C.c_void_p * max(n, 1))(*[p.value if isinstance(p, C.c_void_p) else p for p in layer_plans])
@@ -242,6 +252,20 @@ def pivot_mlp_status(mlp, stream=None):
     st = C.c_int(0)
     _check(lib().pivot_mlp_status(mlp, stream, C.byref(st)))
     return int(st.value)
+
+
+def pivot_mlp_status_word(mlp):
+    """Device address of the chain's status word (0 if the chain has no one-launch form)."""
+    out = C.c_void_p()
+    _check(lib().pivot_mlp_status_word(mlp, C.byref(out)))
+    return out.value or 0
+
+
+def pivot_lstm_status_word(plan, steps, batch, ws_ptr):
+    """Device address of the recurrent run's status word inside its workspace."""
+    out = C.c_void_p()
+    _check(lib().pivot_lstm_status_word(plan, steps, batch, ws_ptr, C.byref(out)))
+    return out.value or 0
 
 
 def pivot_lstm_workspace_bytes(plan, H, I, steps, batch):

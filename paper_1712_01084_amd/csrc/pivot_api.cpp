@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cstdio>
 #include <cstring>
 #include <new>
 
@@ -500,6 +501,14 @@ int pivot_mlp_status(const pivot_mlp_plan_t* plan, void* stream, int* status) {
     return PIVOT_OK;
 }
 
+int pivot_mlp_status_word(const pivot_mlp_plan_t* plan, const uint32_t** word_dev) {
+    if (!plan || !word_dev) { set_error("plan and word_dev are required"); return PIVOT_E_NULL; }
+    *word_dev = nullptr;
+    if (!plan->persist_ok) return PIVOT_OK;
+    *word_dev = reinterpret_cast<const uint32_t*>(reinterpret_cast<const char*>(plan->persist_ctl) + chain_persist_status_offset());
+    return PIVOT_OK;
+}
+
 // --------------------------------------------------------------- recurrence
 
 }  // extern "C"
@@ -605,6 +614,35 @@ int pivot_lstm_status(const pivot_fc_plan_t* plan, int steps, int batch, const v
     API_HIP(hipStreamSynchronize(reinterpret_cast<hipStream_t>(stream)), (void)0);
     API_HIP(hipMemcpy(&word, reinterpret_cast<const char*>(ws_dev) + m.ctl_off + 1024, 4, hipMemcpyDeviceToHost), (void)0);
     *status = (int)word;
+    return PIVOT_OK;
+}
+
+int pivot_lstm_status_word(const pivot_fc_plan_t* plan, int steps, int batch, const void* ws_dev, const uint32_t** word_dev) {
+    if (!plan || !ws_dev || !word_dev) { set_error("plan, ws_dev and word_dev are required"); return PIVOT_E_NULL; }
+    LstmLayout m = lstm_layout(plan, steps, batch);
+    *word_dev = reinterpret_cast<const uint32_t*>(reinterpret_cast<const char*>(ws_dev) + m.ctl_off + 1024);
+    return PIVOT_OK;
+}
+
+int pivot_fc_kernel_name(const pivot_fc_plan_t* plan, int batch, char* buf, size_t buf_len) {
+    if (!plan || !buf || buf_len == 0) { set_error("plan and buf are required"); return PIVOT_E_NULL; }
+    buf[0] = 0;
+    if (batch < 1 || batch > 64) { set_error("batch %d outside 1..64", batch); return PIVOT_E_SHAPE; }
+    FcLaunch L{};
+    const HostPlan& h = plan->host;
+    L.K = h.d.K; L.x_resident = (h.d.flags & PIVOT_PLAN_GATHER_FROM_GLOBAL) ? 0 : ((h.d.flags & PIVOT_PLAN_GATHER_FROM_LDS_COPY) ? 2 : 1);
+    L.M_pad = h.M_pad; L.K_pad = h.K_pad; L.bh = h.d.bh; L.bw = h.d.bw; L.wdtype = h.d.wdtype; L.layout = h.d.layout; L.T = h.T; L.act = h.d.act;
+    L.nchunks = h.nchunks; L.nbr = h.nbr; L.chunk_tiles = h.chunk_tiles; L.wg_waves = h.wg_waves;
+    L.lds_tiles = h.lds_tiles(); L.row_slices = h.row_slices; L.uniform_ct = h.uniform_ct; L.uniform_parts = h.uniform_parts;
+    L.batch = batch;
+    // a natural-order x, 16-byte aligned, rows densely packed (what the matrix-core form reads is its own copy)
+    const bool blk = fc_uses_matrix_cores(h.d.layout, h.d.wdtype, h.d.bh, h.d.bw, h.lds_tiles(), batch);
+    L.x = reinterpret_cast<const void*>(uintptr_t(256)); L.ldx = blk ? h.K_pad : h.d.K; L.x_block_order = blk ? 1 : 0;
+    L.xsort = h.sorted_ok ? reinterpret_cast<const int32_t*>(uintptr_t(256)) : nullptr;
+    std::string name;
+    int rc = launch_fc(L, &name);
+    if (rc != PIVOT_OK) return rc;
+    snprintf(buf, buf_len, "%s", name.c_str());
     return PIVOT_OK;
 }
 

@@ -131,7 +131,8 @@ size_t fc_ticket_bytes(const HostPlan& hp);                   // the same for ev
 size_t fc_partial_bytes(const HostPlan& hp, int batch);
 size_t fc_workspace_bytes(const HostPlan& hp, int batch);     // counters + partials
 size_t fc_gather_bytes(const HostPlan& hp, int batch);        // block-order copy of a natural-order x
-int    launch_fc(const FcLaunch& L);
+// describe != NULL: nothing is launched, *describe receives the name of the kernel instantiation the call would run
+int    launch_fc(const FcLaunch& L, std::string* describe = nullptr);
 int    launch_gather_x(const void* x, int64_t ldx, const int32_t* pcol_pad, void* xg, int K_pad, int batch,
                        int wdtype, void* stream);
 int    launch_fill_zero(void* dev, size_t bytes, void* stream);

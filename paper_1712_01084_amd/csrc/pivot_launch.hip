@@ -1,6 +1,7 @@
 // Chooses the kernel, the row slicing and the launch shape for one layer
 // application and sizes its workspace.
 #include <algorithm>
+#include <cstdio>
 
 #include "pivot_fc_kernels.h"
 
@@ -132,7 +133,15 @@ size_t fc_gather_bytes(const HostPlan& hp, int batch) {
     return align_up((size_t)batch * hp.K_pad * elem_size(hp.d.wdtype), 256);
 }
 
-int launch_fc(const FcLaunch& L) {
+// "pivot::<kernel and template arguments>" as a profiler prints it
+template <typename... A>
+static std::string kernel_name(const char* fmt, A... args) {
+    char buf[160];
+    snprintf(buf, sizeof buf, fmt, args...);
+    return std::string("pivot::") + buf;
+}
+
+int launch_fc(const FcLaunch& L, std::string* describe) {
     const int path = fc_path(L.layout, L.wdtype, L.bh, L.bw, L.lds_tiles, L.batch);
     const bool mc = path == kPathMfmaGather, ml = path == kPathMfmaLds;
     const int nbt = fc_batch_tile(L.layout, L.wdtype, L.bh, L.bw, L.lds_tiles, L.batch);
@@ -160,6 +169,7 @@ int launch_fc(const FcLaunch& L) {
         a.xs_stride = 0;
         const int rw = nw < 4 ? nw : 4;
         size_t smem = (size_t)rw * bhs * nbt * 4;
+        if (describe) { *describe = kernel_name("fc_mfma_kernel<%d, %d, %d, %d>", mfma_kind(L.wdtype, L.bh, L.bw), bhs, L.bw, nw); return PIVOT_OK; }
         return launch_mfma_f16(a, mfma_kind(L.wdtype, L.bh, L.bw), bhs, L.bw, nw, grid, smem, st);
     }
     if (L.uniform_ct > 0xFFFF || L.uniform_parts > 0x7FFF) a.uniform_ct = a.uniform_parts = 0;   // packed into 16 bits each: fall back to loaded descriptors
@@ -218,6 +228,15 @@ int launch_fc(const FcLaunch& L) {
     size_t smem = xres ? xn_bytes + xs_bytes : xs_bytes;
     smem = align_up(smem > red_bytes ? smem : red_bytes, 16);
     if (smem > (size_t)(xres == 3 ? 150 : 64) * 1024) { set_error("chunk does not fit in LDS (%zu bytes)", smem); return PIVOT_E_UNSUPPORTED; }
+    if (describe) {
+        // the instantiation the per-path launchers pick for these values (they take 8 wavefronts for 16 where
+        // they have no 16-wavefront form, and know one LDS-copy form where the vector kernel knows three)
+        const char* wt = L.wdtype == PIVOT_F32 ? "float" : "_Float16";
+        if (L.layout != PIVOT_BRC) *describe = kernel_name("fc_colmajor_kernel<%s, %d, %d, %d, %d>", wt, L.layout, L.bh, L.bw, nw >= 8 ? 8 : 4);
+        else if (ml) *describe = kernel_name("fc_mfma_lds_kernel<%d, %d, %d, %d, %d, %d>", kind, bhs, L.bw, nbt, nw >= 8 ? 8 : 4, xres ? 2 : 0);
+        else *describe = kernel_name("fc_gemv_kernel<%s, %d, %d, %d, %d, %d>", wt, bhs, L.bw, nbt, nw, xres);
+        return PIVOT_OK;
+    }
     if (L.layout != PIVOT_BRC) return launch_colmajor(a, L.layout, L.wdtype, L.bh, L.bw, nw, grid, smem, st);
     if (ml) {
         if (!L.xsort) { set_error("internal: the LDS-fed matrix-core kernel needs the packed gather lists"); return PIVOT_E_UNSUPPORTED; }

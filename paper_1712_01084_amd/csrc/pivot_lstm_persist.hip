@@ -445,7 +445,26 @@ bool lstm_persist_supported(const HostPlan& hp, int H, int batch, int device, in
     G = std::max(G, std::max(hp.K_pad / kBW, cus / 2));
     G = std::min(G, cus);
     const int L = (hp.T + 4 * G - 1) / (4 * G);
-    if (L > 16) return false;                                             // tiles stay in registers
+    // tiles stay in registers (16 slots); with 16 tiles per wavefront the flushed accumulators alone would take
+    // the 64 KB of LDS a launch gets without asking for more, so 15 is the limit
+    if (L > 15) return false;
+    // every workgroup must be resident at once (they wait for each other): asked once per device and L
+    {
+        static int fits[16][16] = {};                                     // [device & 15][L]: 0 unknown, 1 yes, -1 no
+        int& f = fits[device & 15][L];
+        if (f == 0) {
+            int prev = -1, per_cu = 0;
+            if (hipGetDevice(&prev) != hipSuccess) { (void)hipGetLastError(); return false; }
+            if (prev != device && hipSetDevice(device) != hipSuccess) { (void)hipGetLastError(); return false; }
+            const size_t smem = (size_t)4 * L * kSlot * 4;
+            const hipError_t e = L <= 8 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, lstm_persist_kernel<8>, kNT, smem)
+                                        : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, lstm_persist_kernel<16>, kNT, smem);
+            if (prev != device) (void)hipSetDevice(prev);
+            if (e != hipSuccess) { (void)hipGetLastError(); return false; }
+            f = per_cu >= 1 ? 1 : -1;
+        }
+        if (f < 0) return false;
+    }
     if (grid_out) *grid_out = G;
     if (L_out) *L_out = L;
     return true;
@@ -475,17 +494,9 @@ int launch_lstm_persist(const LstmPersistLaunch& P) {
     a.partials = reinterpret_cast<unsigned long long*>(P.partials); a.ctl = P.ctl; a.h = P.h; a.c = P.c; a.z_dbg = P.z_dbg;
     a.T = P.hp->T; a.nbr = P.hp->nbr; a.H = P.H; a.I = P.I; a.K_pad = P.hp->K_pad; a.batch = P.batch; a.steps = P.steps; a.L = L;
     const size_t smem = (size_t)4 * L * kSlot * 4;
-    // every workgroup must be resident at once (they wait for each other)
-    int per_cu = 0;
-    if (L <= 8) {
-        HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, lstm_persist_kernel<8>, kNT, smem));
-        if (per_cu < 1) { set_error("persistent recurrent kernel does not fit on a compute unit"); return PIVOT_E_UNSUPPORTED; }
-        hipLaunchKernelGGL(lstm_persist_kernel<8>, dim3(G), dim3(kNT), smem, st, a);
-    } else {
-        HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, lstm_persist_kernel<16>, kNT, smem));
-        if (per_cu < 1) { set_error("persistent recurrent kernel does not fit on a compute unit"); return PIVOT_E_UNSUPPORTED; }
-        hipLaunchKernelGGL(lstm_persist_kernel<16>, dim3(G), dim3(kNT), smem, st, a);
-    }
+    // (that all workgroups fit on the device at once was checked by lstm_persist_supported)
+    if (L <= 8) hipLaunchKernelGGL(lstm_persist_kernel<8>, dim3(G), dim3(kNT), smem, st, a);
+    else        hipLaunchKernelGGL(lstm_persist_kernel<16>, dim3(G), dim3(kNT), smem, st, a);
     HIP_TRY(hipGetLastError());
     return PIVOT_OK;
 }

@@ -9,6 +9,7 @@ from paper_1712_01084_amd import binding as B
 from paper_1712_01084_amd import workloads as WL
 
 import gpu_util as G
+import lstm_window as LW
 
 pytestmark = pytest.mark.gpu
 
@@ -58,9 +59,13 @@ def _check_chain(probs, flags=0, chunk_tiles=0, want_one_launch=None, repeats=2)
     bd = np.float16 if probs[0].wdtype == WL.F16 else None
     outs, scales, chain = O.oracle_mlp(_layers(probs), probs[0].x, boundary_dtype=bd, return_all=True)
     assert not np.isnan(y).any()
+    # gate: a relative error of tol in EVERY layer, propagated to the output (chain scale S_L, see the oracle);
+    # also reported against the last layer's own scale D_L = |W_L||h_{L-1}| + |b_L|, which an error made in an
+    # earlier layer may legitimately exceed
     err = O.max_scaled_error(y, outs[-1], chain[-1])
+    err_d = O.max_scaled_error(y, outs[-1], scales[-1])
     assert err <= G.TOL[probs[0].wdtype], err
-    return err
+    return err, err_d
 
 
 @pytest.mark.parametrize("eliminated", [False, True])
@@ -82,13 +87,15 @@ def test_fp16_chain_batch16_uses_matrix_cores():
     _check_chain(probs, chunk_tiles=2)
 
 
+@pytest.mark.parametrize("seed", [0, 1, 2])
 @pytest.mark.parametrize("eliminated", [False, True])
-def test_config4_full(eliminated):
-    probs = WL.config4(seed=0, eliminated=eliminated)
-    err = _check_chain(probs, want_one_launch=True)
-    print("config4 eliminated=%s one launch: scaled error %.3g" % (eliminated, err))
-    err = _check_chain(probs, flags=B.PIVOT_MLP_LAUNCH_PER_LAYER, want_one_launch=False)
-    print("config4 eliminated=%s launch per layer: scaled error %.3g" % (eliminated, err))
+def test_config4_full(eliminated, seed):
+    probs = WL.config4(seed=seed, eliminated=eliminated)
+    for flags, one in ((0, True), (B.PIVOT_MLP_LAUNCH_PER_LAYER, False)):
+        err, err_d = _check_chain(probs, flags=flags, want_one_launch=one)
+        print("config4 seed %d eliminated=%s %s: error / S_L %.3g, error / D_L %.3g"
+              % (seed, eliminated, "one launch" if one else "launch per layer", err, err_d), flush=True)
+        assert err_d <= 1e-5          # fp32: also within the tolerance on the last layer's own scale
 
 
 @pytest.mark.parametrize("eliminated", [False, True])
@@ -222,7 +229,42 @@ def test_chain_workspace_reused_across_batch_sizes(wdtype):
             B.pivot_fc_plan_destroy(h)
 
 
+def test_chain_padding_columns_of_a_directly_read_intermediate_are_cleared():
+    # second layer: 3100 inputs (3104 with padding) in whole block rows of 97 tiles, batch 16: too long to stage
+    # in LDS, so the matrix-core kernel reads its B fragments straight from the intermediate's rows, padding
+    # columns included; a first run on another batch size leaves NaN where those columns are
+    probs = WL.config4(seed=43, batch=16, dims=(64, 3100, 40), wdtype=WL.F16, bh=32, bw=32, frac=1.0)
+    plans = [G.dev_plan(p, chunk_tiles=97) for p in probs]
+    mlp = B.pivot_mlp_plan(plans, 0)
+    try:
+        assert B.pivot_fc_workspace_bytes(plans[1], 16) > 0      # whole rows: all of it is the block-order copy
+        ws = G.workspace(max(B.pivot_mlp_workspace_bytes(mlp, b) for b in (64, 16)))
+        st = torch.cuda.current_stream().cuda_stream
+        for b, poison in ((64, True), (16, False)):
+            x = np.full((b, 64), np.nan, dtype=np.float16) if poison else probs[0].x
+            xd = torch.from_numpy(x).cuda()
+            yd = torch.full((b, probs[-1].M), float("nan"), dtype=torch.float32, device="cuda")
+            B.pivot_mlp_run(mlp, xd.data_ptr(), 64, yd.data_ptr(), probs[-1].M, b, ws.data_ptr(), ws.numel(), st)
+            torch.cuda.synchronize()
+        outs, scales, chain = O.oracle_mlp(_layers(probs), probs[0].x, boundary_dtype=np.float16, return_all=True)
+        y = yd.cpu().numpy().astype(np.float64)
+        assert not np.isnan(y).any()
+        assert O.max_scaled_error(y, outs[-1], chain[-1]) <= G.TOL[WL.F16]
+    finally:
+        B.pivot_mlp_plan_destroy(mlp)
+        for h in plans:
+            B.pivot_fc_plan_destroy(h)
+
+
 # ------------------------------------------------------------------------ LSTM
+
+# max |dh|, |dc| of a free run against the oracle's trajectory: about ten times the largest value measured over all
+# cases here (2.3e-5 on the small shapes, 4.8e-6 over the 256 steps of the full workload; see the printed lines);
+# no bound follows from the per-step tolerance.  WINDOW_GATE: the same for the worst step of a window, as a
+# fraction of the one-step bound at the 2e-3 tolerance (measured: at most 3.8e-3 of it)
+FREE_RUN_GATE = 2e-4
+WINDOW_GATE = 0.04
+
 
 def _lstm_gpu(lp, plan, xs, h, c, want_z=True):
     steps, batch = xs.shape[0], xs.shape[1]
@@ -240,13 +282,14 @@ def _lstm_gpu(lp, plan, xs, h, c, want_z=True):
     return hd.cpu().numpy().astype(np.float64), cd.cpu().numpy().astype(np.float64), zd.cpu().numpy().astype(np.float64)
 
 
-def _check_lstm_steps(lp, record, tol, per_step=False):
+def _check_lstm_steps(lp, record, tol, per_step=False, windows=(), window_len=12):
     # per_step=False: the library's choice (one launch for the whole sequence where the plan allows it);
     # per_step=True: one layer launch and one cell launch per step
     p = lp.fc
     Wd = O.dense_masked_natural(p.Wp, p.tile_mask, p.prow, p.pcol, p.bh, p.bw)
     sd = np.float16 if p.wdtype == WL.F16 else np.float32
-    h_end, c_end, rec = O.oracle_lstm(Wd, p.bias, lp.xs, lp.h0, lp.c0, lp.H, state_dtype=sd, record=record)
+    h_end, c_end, rec = O.oracle_lstm(Wd, p.bias, lp.xs, lp.h0, lp.c0, lp.H, state_dtype=sd,
+                                      record=tuple(record) + tuple(windows))
     plan = G.dev_plan(p, flags=B.PIVOT_PLAN_LSTM_LAUNCH_PER_STEP if per_step else 0)
     try:
         H = lp.H
@@ -257,17 +300,35 @@ def _check_lstm_steps(lp, record, tol, per_step=False):
             z_ref, h_ref, c_ref, D = O.oracle_lstm_step(Wd, p.bias, h_fed.astype(sd), lp.xs[t], c_prev, H)
             h, c, z = _lstm_gpu(lp, plan, lp.xs[t:t + 1], h_fed, c_prev)
             assert O.max_scaled_error(z, z_ref, D) <= tol, ("z", t)
-            # the cell is smooth: |dc| <= |dz_f||c|/4 + |dz_i|/4 + |dz_g|, |dh| <= |dz_o|/4 + |dc|
-            Di, Df, Dg, Do = D[:, :H], D[:, H:2 * H], D[:, 2 * H:3 * H], D[:, 3 * H:]
-            bc = tol * (Df * np.abs(c_prev) / 4 + Di / 4 + Dg) + 1e-5
+            bh, bc = LW.one_step_bounds(D, c_prev.astype(np.float64), H, tol)
             assert np.all(np.abs(c - c_ref) <= bc), ("c", t)
-            assert np.all(np.abs(h - h_ref) <= tol * Do / 4 + bc + 1e-5), ("h", t)
-        # free-running trajectory: reported, not gated beyond sanity ("parity unpinned")
+            assert np.all(np.abs(h - h_ref) <= bh), ("h", t)
+        # windows of several steps inside ONE run, from the oracle's state at t0: every step gated at the one-step
+        # bound against the oracle stepping from the device's own previous state (see lstm_window.py), and the
+        # end of the window against the oracle's own trajectory from the same state
+        for t0 in windows:
+            n_max = min(window_len, lp.xs.shape[0] - t0)
+            h0 = rec[t0]["h_fed"].astype(np.float32)
+            c0 = rec[t0]["c_prev"].astype(np.float32)
+            xs = lp.xs[t0:t0 + n_max]
+
+            def run(n):
+                h, c, _ = _lstm_gpu(lp, plan, xs[:n], h0, c0, want_z=False)
+                return h, c
+            rep = LW.chained_window_check(run, Wd, p.bias, xs, h0, c0, H, sd, tol, n_max)
+            assert max(max(r[1], r[2]) for r in rep) <= WINDOW_GATE
+            h_w, c_w, _ = O.oracle_lstm(Wd, p.bias, xs, h0, c0.astype(np.float64), H, state_dtype=sd)
+            h, c = run(n_max)
+            print("lstm window t0=%d, %d steps: worst step at %.3g / %.3g of the one-step bound; end of window vs "
+                  "oracle trajectory |dh| %.3g |dc| %.3g" % (t0, n_max, max(r[1] for r in rep), max(r[2] for r in rep),
+                                                             np.abs(h - h_w).max(), np.abs(c - c_w).max()), flush=True)
+        # free-running trajectory against the oracle's: reported, and gated by the caller at a few times what
+        # was measured (no bound follows from the per-step tolerance: the recurrence can amplify)
         h, c, _ = _lstm_gpu(lp, plan, lp.xs, lp.h0, lp.c0, want_z=False)
         h2, c2, _ = _lstm_gpu(lp, plan, lp.xs, lp.h0, lp.c0, want_z=False)
         assert np.array_equal(h, h2) and np.array_equal(c, c2)          # fixed summation order: bit-identical reruns
         dh, dc = float(np.abs(h - h_end).max()), float(np.abs(c - c_end).max())
-        print("lstm free run %d steps: max|dh| = %.3g, max|dc| = %.3g" % (lp.xs.shape[0], dh, dc))
+        print("lstm free run %d steps: max|dh| = %.3g, max|dc| = %.3g" % (lp.xs.shape[0], dh, dc), flush=True)
         assert np.isfinite(h).all() and np.isfinite(c).all()
         return dh, dc
     finally:
@@ -277,11 +338,11 @@ def _check_lstm_steps(lp, record, tol, per_step=False):
 @pytest.mark.parametrize("per_step", [False, True])
 @pytest.mark.parametrize("batch", [1, 2, 8])
 def test_lstm_small(batch, per_step):
-    lp = WL.config5(seed=3, batch=batch, H=64, I=32, steps=6, frac=0.5)
+    lp = WL.config5(seed=3, batch=batch, H=64, I=32, steps=14, frac=0.5)
     lp.h0 = np.random.default_rng(1).standard_normal(lp.h0.shape).astype(np.float32) * 0.5
     lp.c0 = np.random.default_rng(2).standard_normal(lp.c0.shape).astype(np.float32)
-    dh, dc = _check_lstm_steps(lp, record=(0, 1, 5), tol=2e-3, per_step=per_step)
-    assert dh < 0.05 and dc < 0.05
+    dh, dc = _check_lstm_steps(lp, record=(0, 1, 5), tol=2e-3, per_step=per_step, windows=(0, 2))
+    assert dh < FREE_RUN_GATE and dc < FREE_RUN_GATE
 
 
 @pytest.mark.parametrize("H,I,batch,frac", [(96, 40, 3, 0.3), (256, 128, 16, 0.2), (80, 8, 5, 1.0),
@@ -289,11 +350,11 @@ def test_lstm_small(batch, per_step):
                                              (512, 256, 4, 0.5)])     # fewer workgroups than compute units
 def test_lstm_one_launch_ragged_shapes(H, I, batch, frac):
     # K = H+I not a multiple of the tile width (padding columns), empty and split block rows, every tile kept
-    lp = WL.config5(seed=5, batch=batch, H=H, I=I, steps=9, frac=frac)
+    lp = WL.config5(seed=5, batch=batch, H=H, I=I, steps=13, frac=frac)
     lp.h0 = np.random.default_rng(3).standard_normal(lp.h0.shape).astype(np.float32) * 0.5
     lp.c0 = np.random.default_rng(4).standard_normal(lp.c0.shape).astype(np.float32)
-    dh, dc = _check_lstm_steps(lp, record=(0, 3, 8), tol=2e-3)
-    assert dh < 0.05 and dc < 0.05
+    dh, dc = _check_lstm_steps(lp, record=(0, 3, 8), tol=2e-3, windows=(0, 1))
+    assert dh < FREE_RUN_GATE and dc < FREE_RUN_GATE
 
 
 def test_lstm_one_launch_agrees_with_launch_per_step():
@@ -310,10 +371,62 @@ def test_lstm_one_launch_agrees_with_launch_per_step():
     assert np.abs(h1 - h2).max() < 2e-3 and np.abs(c1 - c2).max() < 4e-3 and np.abs(z1 - z2).max() < 2e-2
 
 
+@pytest.mark.parametrize("seed", [0, 1, 2])
 @pytest.mark.parametrize("per_step", [False, True])
-def test_lstm_config5_full(per_step):
-    lp = WL.config5(seed=0)
-    _check_lstm_steps(lp, record=(0, 1, 17, 255), tol=2e-3, per_step=per_step)
+def test_lstm_config5_full(per_step, seed):
+    # single steps from the oracle's state, three 12-step windows inside one run (the one-launch form's step-to-step
+    # exchange: marks, the rotation through eight partial buffers, the progress check from step 8 on), and the
+    # 256-step free run
+    lp = WL.config5(seed=seed)
+    dh, dc = _check_lstm_steps(lp, record=(0, 1, 17, 255), tol=2e-3, per_step=per_step,
+                               windows=(0, 100, 240) if seed == 0 or not per_step else (100,))
+    assert dh < FREE_RUN_GATE and dc < FREE_RUN_GATE
+
+
+def test_status_words_can_be_read_without_the_synchronising_calls():
+    # the device address of each one-launch form's status word: copied back here with a plain hipMemcpy issued by
+    # the test itself (a caller may equally read it from a kernel or an asynchronous copy behind the run)
+    import ctypes
+    hip = ctypes.CDLL("libamdhip64.so")
+    hip.hipMemcpy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int]
+
+    def read_word(addr):
+        w = ctypes.c_uint32(0xFFFFFFFF)
+        assert hip.hipMemcpy(ctypes.byref(w), ctypes.c_void_p(addr), 4, 2) == 0      # device to host
+        return w.value
+
+    probs = WL.config4(seed=37, dims=(300, 200, 70), frac=0.4)
+    plans = [G.dev_plan(p) for p in probs]
+    st = torch.cuda.current_stream().cuda_stream
+    for flags in (0, B.PIVOT_MLP_LAUNCH_PER_LAYER):
+        mlp = B.pivot_mlp_plan(plans, flags)
+        try:
+            addr = B.pivot_mlp_status_word(mlp)
+            assert (addr != 0) == (flags == 0)
+            xd = torch.from_numpy(probs[0].x).cuda()
+            yd = torch.empty((1, probs[-1].M), dtype=torch.float32, device="cuda")
+            ws = G.workspace(B.pivot_mlp_workspace_bytes(mlp, 1))
+            B.pivot_mlp_run(mlp, xd.data_ptr(), probs[0].K, yd.data_ptr(), probs[-1].M, 1, ws.data_ptr(), ws.numel(), st)
+            torch.cuda.synchronize()
+            if addr:
+                assert read_word(addr) == 0
+        finally:
+            B.pivot_mlp_plan_destroy(mlp)
+    for h in plans:
+        B.pivot_fc_plan_destroy(h)
+    lp = WL.config5(seed=8, batch=4, H=64, I=32, steps=5, frac=0.5)
+    plan = G.dev_plan(lp.fc)
+    try:
+        xsd = torch.from_numpy(lp.xs).cuda()
+        hd, cd = torch.from_numpy(lp.h0).cuda(), torch.from_numpy(lp.c0).cuda()
+        ws = G.workspace(B.pivot_lstm_workspace_bytes(plan, lp.H, lp.I, 5, 4))
+        B.pivot_lstm_run(plan, lp.H, lp.I, xsd.data_ptr(), hd.data_ptr(), cd.data_ptr(), None, 5, 4, ws.data_ptr(), ws.numel(), st)
+        torch.cuda.synchronize()
+        addr = B.pivot_lstm_status_word(plan, 5, 4, ws.data_ptr())
+        assert ws.data_ptr() <= addr < ws.data_ptr() + ws.numel() and read_word(addr) == 0
+        assert B.pivot_lstm_status(plan, 5, 4, ws.data_ptr(), st) == 0
+    finally:
+        B.pivot_fc_plan_destroy(plan)
 
 
 @pytest.mark.parametrize("seed", [1, 2, 3])
