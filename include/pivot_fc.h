@@ -219,6 +219,31 @@ int  pivot_fc_run(const pivot_fc_plan_t* plan, const void* x_dev, int64_t ldx,
 int  pivot_fc_kernel_name(const pivot_fc_plan_t* plan, int batch, char* buf, size_t buf_len);
 
 /*
+ * pivot_fc_run_static - pivot_fc_run for callers that cannot allocate device
+ * memory and have no workspace to hand over: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * kernels, same result bits as pivot_fc_run without the workspace: the scratch
+ * of the run (arrival counters and partial sums of split block rows, the
+ * block-order copy of x of the matrix-core form that wants one) is a fixed
+ * array in device memory that belongs to the library, PIVOT_STATIC_COUNTER_BYTES
+ * + PIVOT_STATIC_DATA_BYTES = 16 MiB on every GPU the library runs on, held
+ * until the process ends.  The call allocates and frees nothing and never
+ * synchronises; its first call on a device looks the array up and enqueues
+ * one small kernel on `stream` that clears the counters.
+ * A plan whose counters need more than PIVOT_STATIC_COUNTER_BYTES, or whose
+ * partial sums and staged input at this batch need more than
+ * PIVOT_STATIC_DATA_BYTES, is refused with PIVOT_E_WORKSPACE (use pivot_fc_run).
+ * All calls on one GPU share the one array: calls that overlap in time on one
+ * GPU (two streams, two threads) race and give undefined results; calls
+ * ordered on one stream, or by events, are fine, also with different plans
+ * and batch sizes in any order.
+ */
+#define PIVOT_STATIC_COUNTER_BYTES ((size_t)4 << 20)
+#define PIVOT_STATIC_DATA_BYTES    ((size_t)12 << 20)
+int  pivot_fc_run_static(const pivot_fc_plan_t* plan, const void* x_dev, int64_t ldx,
+                         void* y_dev, int64_t ldy, int batch, void* stream);
+
+/*
  * Chains of layers (Section 4.2).  Between layer l and l+1 the producer's row
  * scatter and the consumer's column gather are composed at plan time into one
  * index array q_l[c] = invprow_l[pcol_{l+1}[c]] (Section 4.2.1); the device

@@ -29,7 +29,7 @@ PIVOT_E_ALLOC, PIVOT_E_HIP, PIVOT_E_WORKSPACE, PIVOT_E_NO_DEVICE = -5, -6, -7, -
 EXPORTS = [
     "pivot_version", "pivot_last_error",
     "pivot_fc_plan", "pivot_fc_plan_host_view", "pivot_fc_plan_clone", "pivot_fc_plan_destroy",
-    "pivot_fc_workspace_bytes", "pivot_workspace_init", "pivot_fc_run", "pivot_fc_kernel_name",
+    "pivot_fc_workspace_bytes", "pivot_workspace_init", "pivot_fc_run", "pivot_fc_run_static", "pivot_fc_kernel_name",
     "pivot_mlp_plan", "pivot_mlp_plan_host_view", "pivot_mlp_plan_destroy",
     "pivot_mlp_workspace_bytes", "pivot_mlp_run", "pivot_mlp_status", "pivot_mlp_status_word",
     "pivot_lstm_workspace_bytes", "pivot_lstm_run", "pivot_lstm_status", "pivot_lstm_status_word",
@@ -100,6 +100,7 @@ def lib():
     L.pivot_workspace_init.argtypes = [vp, sz, vp]
     L.pivot_fc_run.argtypes = [vp, vp, i64, vp, i64, i32, vp, sz, vp]
     L.pivot_fc_kernel_name.argtypes = [vp, i32, C.c_char_p, sz]
+    L.pivot_fc_run_static.argtypes = [vp, vp, i64, vp, i64, i32, vp]
     L.pivot_mlp_plan.argtypes = [C.POINTER(vp), i32, i32, C.POINTER(vp)]
     L.pivot_mlp_plan_host_view.argtypes = [vp, C.POINTER(pivot_mlp_view)]
     L.pivot_mlp_plan_destroy.argtypes = [vp]
@@ -211,6 +212,10 @@ def pivot_fc_kernel_name(plan, batch):
     buf = C.create_string_buffer(256)
     _check(lib().pivot_fc_kernel_name(plan, batch, buf, 256))
     return buf.value.decode()
+
+
+def pivot_fc_run_static(plan, x_ptr, ldx, y_ptr, ldy, batch, stream=None):
+    _check(lib().pivot_fc_run_static(plan, x_ptr, ldx, y_ptr, ldy, batch, stream))
 
 
 def pivot_mlp_plan(layer_plans, flags=0):
