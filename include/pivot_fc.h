@@ -94,7 +94,7 @@ typedef struct pivot_fc_desc {
  * most 8 vectors per thread and 64 KB of LDS; at batch 1 up to 16 vectors per
  * thread and 150 KB when every work item has a compute unit of its own).  By
  * default the library takes the second form when it is possible and a work
- * item streams 48 KB of weights or more.  These bits force the first form, or
+ * item streams 32 KB of weights or more.  These bits force the first form, or
  * the second whenever possible.                                               */
 #define PIVOT_PLAN_GATHER_FROM_GLOBAL 1
 #define PIVOT_PLAN_GATHER_FROM_LDS_COPY 4

@@ -28,6 +28,14 @@ __device__ __forceinline__ void lds_barrier() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+// Orders the LDS writes of a wavefront before its own later LDS reads (other lanes' data): the hardware
+// completes one wavefront's LDS operations in order, so this only keeps the compiler from reordering them.
+__device__ __forceinline__ void wave_lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
+}
+
 // v + (v from lane ^ 1), ^2 via quad permutes; 4 and 8 via row mirrors (valid
 // because after the previous steps all lanes of the mirrored group agree);
 // 16 and 32 through the LDS crossbar (ds_bpermute, no memory traffic).

@@ -56,7 +56,25 @@ struct FcArgs {
     int chunk_tiles;            // the plan's chunk size (vector kernel: fixes the LDS row stride)
     int xn_vecs;                // x-resident vector kernel: 16-byte vectors per row of x (row length / VEC)
     int xn_stride;              //   elements between the LDS copies of consecutive batch rows (the row length)
+    long long* trace;           // timeline builds only (PIVOT_TRACE): eight time stamps per wavefront, else unused
 };
+
+// Timeline builds (-DPIVOT_TRACE, see bench_timeline.py): the vector kernel records the constant 100 MHz
+// clock at eight points per wavefront: 0 start, 1 every load issued, 2 copy of x stored to LDS, 3 past the
+// barrier behind it, 4 x-segments staged, 5 last weight consumed, 6 sums of all wavefronts in LDS, 7 outputs
+// stored.  In ordinary builds the stamps compile to nothing.
+#ifdef PIVOT_TRACE
+#define PIVOT_STAMP_DECL long long tr_[8] = {0, 0, 0, 0, 0, 0, 0, 0}
+#define PIVOT_STAMP(i) do { __builtin_amdgcn_sched_barrier(0); tr_[i] = wall_clock64(); __builtin_amdgcn_sched_barrier(0); } while (0)
+#define PIVOT_STAMP_FLUSH(a, nw, wave, lane)                                                                     \
+    do { if ((a).trace && (lane) == 0) {                                                                          \
+        long long* t_ = (a).trace + ((((size_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * (nw) + (wave)) * 8; \
+        for (int i_ = 0; i_ < 8; ++i_) t_[i_] = tr_[i_]; } } while (0)
+#else
+#define PIVOT_STAMP_DECL do {} while (0)
+#define PIVOT_STAMP(i) do {} while (0)
+#define PIVOT_STAMP_FLUSH(a, nw, wave, lane) do {} while (0)
+#endif
 
 // The seven pointers every wavefront needs first are separate leading kernel
 // arguments: with kernel-argument preloading they arrive in SGPRs with the
@@ -276,6 +294,65 @@ struct XStage<WT, BW, 1, NT, XP, false> {
     }
 };
 
+// One batch row, vector kernel: every wavefront stages the x-segments of ITS OWN groups of tiles only (groups
+// wave, wave + NW, ...: exactly those whose weights it streams), so a staged value is written and read by the
+// same wavefront and no workgroup barrier stands between the gather and the first FMA.  GE = staged elements
+// per group (TPL tiles of BW columns); the wavefront's e-th element belongs to its (e / GE)-th group and sits
+// at staged position (wave + (e / GE) * NW) * GE + e % GE, the place the whole-workgroup form gives it.
+// Lane l takes elements l, l + 64, ...; the first XP indices per lane are fetched before the weight stream.
+// Loads and LDS writes are unconditional: positions past the end read a clamped index and land in the dump slot.
+template <typename WT, int BW, int NW, int TPL, int XP>
+struct XStageWave {
+    static constexpr int GE = TPL * BW;
+    int src[XP];
+    static __device__ __forceinline__ int pos_of(int e, int wave) {
+        const int q = e / GE;
+        return (wave + q * NW) * GE + (e - q * GE);
+    }
+    __device__ __forceinline__ void load_idx(const int32_t* xidx, int tile_begin, int ne, int wave, int lane) {
+        const int32_t* xi = xidx + (size_t)tile_begin * BW;
+        const int emax = ne > 0 ? ne - 1 : 0;       // index arrays carry 16 bytes of padding: xi[0] is readable
+        #pragma unroll
+        for (int k = 0; k < XP; ++k) {
+            const int pos = pos_of(lane + k * 64, wave);
+            src[k] = xi[pos < emax ? pos : emax];
+        }
+    }
+    // `x`: the row of x, in global memory or (SRC_LDS) its copy in LDS
+    template <bool SRC_LDS>
+    __device__ __forceinline__ void gather(const int32_t* xidx, const WT* x, WT* xs, int xs_stride,
+                                           int tile_begin, int ne, int wave, int lane) {
+        const int dump = xs_stride - 1;
+        WT v[XP];
+        #pragma unroll
+        for (int k = 0; k < XP; ++k) v[k] = x[src[k] > 0 ? src[k] : 0];
+        #pragma unroll
+        for (int k = 0; k < XP; ++k) {
+            const int pos = pos_of(lane + k * 64, wave);
+            xs[pos < ne ? pos : dump] = (src[k] >= 0) ? v[k] : WT(0);
+        }
+        // longer work items: further rounds of XP elements per lane (the condition is the same in every lane)
+        const int32_t* xi = xidx + (size_t)tile_begin * BW;
+        const int emax = ne > 0 ? ne - 1 : 0;
+        for (int e0 = XP * 64; pos_of(e0, wave) < ne; e0 += XP * 64) {
+            int s2[XP];
+            #pragma unroll
+            for (int k = 0; k < XP; ++k) {
+                const int pos = pos_of(e0 + lane + k * 64, wave);
+                s2[k] = xi[pos < emax ? pos : emax];
+            }
+            WT v2[XP];
+            #pragma unroll
+            for (int k = 0; k < XP; ++k) v2[k] = x[s2[k] > 0 ? s2[k] : 0];
+            #pragma unroll
+            for (int k = 0; k < XP; ++k) {
+                const int pos = pos_of(e0 + lane + k * 64, wave);
+                xs[pos < ne ? pos : dump] = (s2[k] >= 0) ? v2[k] : WT(0);
+            }
+        }
+    }
+};
+
 // The whole of x copied into LDS with coalesced 16-byte loads that depend on
 // nothing (x-resident variant): issued first, together with the gather
 // indices, so that both arrive after ONE trip to memory and the gather itself
@@ -283,7 +360,7 @@ struct XStage<WT, BW, 1, NT, XP, false> {
 // (index, then x[index]) whose second leg queues behind the weight stream.
 // A thread holds up to XN vectors; the launcher only picks this variant when
 // NB rows of x fit (NB * xn_vecs <= XN * NT) and rows are 16-byte aligned.
-// Slots past the end load vector 0 again and are written to a dump vector.
+// Slots past the end are switched off lane by lane.
 template <typename WT, int NB, int NT, int XN = 8>
 struct XRes {
     using V = typename Elem<WT>::vec;
@@ -293,25 +370,28 @@ struct XRes {
         const int total = NB * xn_vecs;
         #pragma unroll
         for (int j = 0; j < XN; ++j) {
+            // Lanes past the end load nothing: a 16-byte load per lane occupies the compute unit's memory
+            // pipeline for 16 clocks per wavefront, needed or not (4096x9216 fp32, where 5 of the 8 slots are
+            // used: 3.64 -> 3.47 us warm; 4096x4096 fp16 dense, 1 of 8: 9.4 -> 9.0 us cold).  Predicated per
+            // lane, not skipped by a uniform branch around the slot: the branches cost 0.1 us cold.
             const int id = tid + j * NT;
             const int b = (NB == 1) ? 0 : id / xn_vecs;
             const int i = (NB == 1) ? id : id - b * xn_vecs;
             const bool ok = id < total && (b0 + b) < batch;
             const WT* row = reinterpret_cast<const WT*>(x) + (long long)(ok ? b0 + b : 0) * ldx;
-            v[j] = load16<V>(row + (size_t)(ok ? i : 0) * VEC);
+            if (ok) v[j] = load16<V>(row + (size_t)i * VEC);
         }
     }
     __device__ __forceinline__ void store(int batch, int xn_vecs, WT* xn, int b0, int tid) {
         const int total = NB * xn_vecs;
         const int xn_stride = xn_vecs * VEC;
-        const int dump = NB * xn_stride;                // one spare vector after the last row
         #pragma unroll
         for (int j = 0; j < XN; ++j) {
             const int id = tid + j * NT;
             const int b = (NB == 1) ? 0 : id / xn_vecs;
             const int i = (NB == 1) ? id : id - b * xn_vecs;
             const bool ok = id < total && (b0 + b) < batch;
-            *reinterpret_cast<V*>(xn + (ok ? b * xn_stride + i * VEC : dump)) = v[j];
+            if (ok) *reinterpret_cast<V*>(xn + b * xn_stride + i * VEC) = v[j];
         }
     }
 };
@@ -427,6 +507,8 @@ __global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(PIVOT_GEMV_PARAMS, FcA
     WT* xs = XR ? xn + NB * (int)((unsigned)q_misc >> 14) * VEC + VEC : xn;
     float* red = reinterpret_cast<float*>(smem);        // reused after the stream phase
 
+    PIVOT_STAMP_DECL;
+    PIVOT_STAMP(0);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int b0 = blockIdx.y * NB, slice = blockIdx.z;
@@ -448,8 +530,11 @@ __global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(PIVOT_GEMV_PARAMS, FcA
     const int tile_elems = q_bh_full * BW;
 
     if constexpr (XR == 1) xres.load(q_batch, q_ldx, q_xn_vecs, p_x, b0, tid);
-    XStage<WT, BW, NB, NT, (XR == 3) ? 8 : 4> xst;      // long inputs come with long work items: 8 indices up front
-    xst.load_idx(p_idx, tile_begin, ntiles * BW, tid);
+    constexpr int XPF = (XR == 3) ? 8 : 4;              // long inputs come with long work items: 8 indices up front
+    XStage<WT, BW, NB, NT, XPF> xst;                    // several batch rows: staged by the whole workgroup
+    XStageWave<WT, BW, NW, TPL, XPF> xsw;               // one batch row: every wavefront stages for itself
+    if constexpr (NB == 1) xsw.load_idx(p_idx, tile_begin, ntiles * BW, wave, lane);
+    else                   xst.load_idx(p_idx, tile_begin, ntiles * BW, tid);
 
     const int s  = lane / LPR;                          // row within the wave-load
     const int cg = lane % LPR;                          // column group
@@ -491,14 +576,22 @@ __global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(PIVOT_GEMV_PARAMS, FcA
     rp.load(p_bias, p_scatter, row0, tid);
     // every load above is issued before anything below waits for one of them
     __builtin_amdgcn_sched_barrier(0);
+    PIVOT_STAMP(1);
     if constexpr (XR != 0) {
         if constexpr (UH == U) xres.store(q_batch, q_xn_vecs, xn, b0, tid);
+        PIVOT_STAMP(2);
         lds_barrier();
-        xst.template gather<true>(q_batch, q_ldx, q_xn_vecs * VEC, q_xs_stride, p_idx, xn, xs, tile_begin, ntiles * BW, b0, tid);
+        PIVOT_STAMP(3);
+        if constexpr (NB == 1) xsw.template gather<true>(p_idx, xn, xs, q_xs_stride, tile_begin, ntiles * BW, wave, lane);
+        else xst.template gather<true>(q_batch, q_ldx, q_xn_vecs * VEC, q_xs_stride, p_idx, xn, xs, tile_begin, ntiles * BW, b0, tid);
     } else {
-        xst.template gather<false>(q_batch, q_ldx, 0, q_xs_stride, p_idx, reinterpret_cast<const WT*>(p_x), xs, tile_begin, ntiles * BW, b0, tid);
+        if constexpr (NB == 1) xsw.template gather<false>(p_idx, reinterpret_cast<const WT*>(p_x), xs, q_xs_stride, tile_begin, ntiles * BW, wave, lane);
+        else xst.template gather<false>(q_batch, q_ldx, 0, q_xs_stride, p_idx, reinterpret_cast<const WT*>(p_x), xs, tile_begin, ntiles * BW, b0, tid);
     }
-    lds_barrier();
+    // what a wavefront staged for itself only it reads: LDS operations of one wavefront complete in order
+    if constexpr (NB == 1) wave_lds_sync();
+    else                   lds_barrier();
+    PIVOT_STAMP(4);
 
     float acc[NL][NB];
     #pragma unroll
@@ -537,6 +630,7 @@ __global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(PIVOT_GEMV_PARAMS, FcA
         if (g < ngroups && g * TPL + ts < ntiles) consume(u, g);
     }
 
+    PIVOT_STAMP(5);
     // lanes -> rows
     #pragma unroll
     for (int j = 0; j < NL; ++j)
@@ -557,7 +651,13 @@ __global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(PIVOT_GEMV_PARAMS, FcA
         }
     }
     __syncthreads();
+    PIVOT_STAMP(6);
     finish_rows<BH, NB, NT>(a, red, NW, br, slot, first, nparts, rp, b0, tid, &s_flag);
+#ifdef PIVOT_TRACE
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // the stamp is taken when the stores have been acknowledged
+#endif
+    PIVOT_STAMP(7);
+    PIVOT_STAMP_FLUSH(a, NW, wave, lane);
 }
 
 // ---------------------------------------------------------------------------

@@ -2,6 +2,7 @@
 // application and sizes its workspace.
 #include <algorithm>
 #include <cstdio>
+#include <cstdlib>
 
 #include "pivot_fc_kernels.h"
 
@@ -161,6 +162,11 @@ int launch_fc(const FcLaunch& L, std::string* describe) {
     a.bh_full = L.bh; a.tile_elems = L.bh * L.bw;
     a.uniform_ct = L.uniform_ct; a.uniform_parts = L.uniform_parts;
     a.T = L.T; a.chunk_tiles = L.chunk_tiles;
+    a.trace = nullptr;
+#ifdef PIVOT_TRACE
+    // timeline builds: where the vector kernel puts its time stamps (8 x int64 per wavefront of the launch)
+    if (const char* e = getenv("PIVOT_TRACE_PTR")) a.trace = reinterpret_cast<long long*>(strtoull(e, nullptr, 0));
+#endif
     dim3 grid(L.nchunks, ngy, sl);
     hipStream_t st = reinterpret_cast<hipStream_t>(L.stream);
 
@@ -185,9 +191,11 @@ int launch_fc(const FcLaunch& L, std::string* describe) {
     // x-resident variant: every work item first copies the whole of x (nbt rows) into LDS with independent
     // coalesced loads and gathers from there.  Taken when the rows are 16-byte vectors (densely packed if there
     // is more than one: the kernel then derives the row stride from its preloaded arguments), a thread has to hold at
-    // most 8 of them, everything fits in 64 KB of LDS, and the work item streams at least 48 KB of weights
-    // (measured: below that the extra LDS pass and barrier cost 0.3 us warm and gain under 0.1 us cold;
-    // above it they gain 0.2-0.4 us cold).  With several batch rows the gather issues a load per element and
+    // most 8 of them, everything fits in 64 KB of LDS, and the work item streams at least 32 KB of weights
+    // (measured at batch 1, where the global form needs no barrier at all because every wavefront stages for
+    // itself: below that the copy and its barrier cost 0.3 us warm and gain nothing cold, 1024x1024 fp32 3.19
+    // either way, 4096x4096 fp32 at 10 % 4.02 / 4.03; at 40 KB they gain 0.2 us cold, 4096x4096 fp16 at 25 %
+    // 4.75 -> 4.54; at 58 KB 0.3 us, 4096x9216 fp32 5.63 -> 5.27; dense 4096x4096 fp16 0.2 us).  With several batch rows the gather issues a load per element and
     // row, so there the copy is also taken as soon as it needs no more loads than the gather would
     // (4096x4096 fp16 at 10 % kept: batch 2 4.16 -> 4.02 us cold, batch 4 4.75 -> 4.43; at 25 %, batch 2:
     // 5.49 -> 4.98; at 5 %, where the gather is the shorter, the copy was 0.1 us slower; warm launches pay
@@ -200,7 +208,7 @@ int launch_fc(const FcLaunch& L, std::string* describe) {
     const size_t item_bytes = (size_t)(a.uniform_ct > 0 ? a.uniform_ct : L.chunk_tiles) * bhs * L.bw * es;
     const size_t staged_cols = (size_t)(a.uniform_ct > 0 ? a.uniform_ct : L.chunk_tiles) * L.bw;
     if (L.layout == PIVOT_BRC && L.x_resident != 0 &&
-        (L.x_resident == 2 || item_bytes >= 48 * 1024 || (nbt >= 2 && staged_cols * vec >= (size_t)xlen)) && xlen % vec == 0 && (nbt == 1 || L.ldx == xlen) &&
+        (L.x_resident == 2 || item_bytes >= 32 * 1024 || (nbt >= 2 && staged_cols * vec >= (size_t)xlen)) && xlen % vec == 0 && (nbt == 1 || L.ldx == xlen) &&
         (reinterpret_cast<uintptr_t>(L.x) & 15) == 0) {
         const size_t vectors = (size_t)nbt * (xlen / vec);
         xn_bytes = (size_t)nbt * xlen * es + 16;
