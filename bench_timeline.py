@@ -10,7 +10,7 @@ prints, per phase, the median over wavefronts, the 90th percentile and the
 latest wavefront, all relative to the first wavefront's start.
 
     python bench_timeline.py --build            # on the CPU: builds paper_1712_01084_amd/libpivotfc_trace.so
-    python bench_timeline.py [--cases cfg2,cfg4l1,cfg1,cfg3d]    # on the GPU
+    python bench_timeline.py [--cases cfg2,cfg4l1,cfg4,cfg1,cfg3d]    # on the GPU (cfg4: the one-launch chain kernel)
 
 The stamps cost a few tens of nanoseconds per phase, so a traced launch is
 slightly slower than the product kernel; the table shows where the time goes,
@@ -87,6 +87,66 @@ def run_case(label, p, ncopies, bursts=14, **plan_kw):
     torch.cuda.empty_cache()
 
 
+CHAIN_PHASES = ["item started", "every load issued", "own x-segments staged (tagged input: producers' pairs arrived)",
+                "last weight consumed", "sums of all waves in LDS", "stores of the outputs issued"]
+
+
+def run_chain(label, probs, ncopies, bursts=12):
+    """The one-launch chain kernel: per layer, the stamps of every wavefront of the last launch of each burst."""
+    import numpy as np
+    import torch
+    from paper_1712_01084_amd import binding as B
+    from paper_1712_01084_amd import workloads as WL
+    wd = B.PIVOT_F32 if probs[0].wdtype == WL.F32 else B.PIVOT_F16
+    sets = []
+    for c in range(ncopies):
+        plans = ([B.pivot_fc_plan(p.M, p.K, p.bh, p.bw, wd, p.Wp, B.PIVOT_W_PIVOTED, p.tile_mask, p.prow, p.pcol, p.bias,
+                                  act=p.act, device=0) for p in probs] if not sets
+                 else [B.pivot_fc_plan_clone(h) for h in sets[0][0]])
+        sets.append((plans, B.pivot_mlp_plan(plans, 0)))
+    views = [B.pivot_fc_plan_host_view(h) for h in sets[0][0]]
+    assert B.pivot_mlp_plan_host_view(sets[0][1], views)["one_launch"] == 1
+    xs = [torch.from_numpy(probs[0].x.copy()).cuda() for _ in range(ncopies)]
+    M = probs[-1].M
+    yd = torch.empty((1, M), dtype=torch.float32, device="cuda")
+    wsb = max(256, B.pivot_mlp_workspace_bytes(sets[0][1], 1))
+    ws = torch.zeros(wsb, dtype=torch.uint8, device="cuda")
+    L = len(probs)
+    tr = torch.zeros((L, 1024, 8, 8), dtype=torch.int64, device="cuda")
+    os.environ["PIVOT_CHAIN_TRACE_PTR"] = str(tr.data_ptr())
+    st = torch.cuda.current_stream().cuda_stream
+    res, k = [], 0
+    for burst in range(bursts):
+        n = (ncopies if ncopies > 1 else 16) + burst
+        for _ in range(n):
+            j = k % ncopies
+            k += 1
+            B.pivot_mlp_run(sets[j][1], xs[j].data_ptr(), probs[0].K, yd.data_ptr(), M, 1, ws.data_ptr(), wsb, st)
+        torch.cuda.synchronize()
+        if burst >= 2:
+            res.append(tr.cpu().numpy().astype(np.float64))
+    assert all(B.pivot_mlp_status(m, st) == 0 for _, m in sets)
+    r = np.stack(res)                                         # [burst][layer][wg][wave][stamp]
+    t0 = np.array([b[0][b[0][:, :, 0] > 0][:, 0].min() for b in r])       # first wavefront of layer 1
+    print("\n### %s\n" % label)
+    print("%s, %d bursts; us since the first wavefront started; per stamp: median over wavefronts / 90th percentile / latest\n"
+          % ("cache-cold (rotating through %d copies of the chain)" % ncopies if ncopies > 1 else "warm (one copy)", len(res)))
+    print("| layer (work items) | " + " | ".join("%d %s" % (i, n) for i, n in enumerate(CHAIN_PHASES)) + " |")
+    print("|---|" + "---|" * len(CHAIN_PHASES))
+    for l in range(L):
+        nit = views[l]["nchunks"] * views[l]["row_slices"]
+        cells = []
+        for i in range(len(CHAIN_PHASES)):
+            a = np.stack([(r[b, l, :nit, :, i] - t0[b]) / 100.0 for b in range(len(res))])
+            cells.append("%.2f / %.2f / %.2f" % (np.median(a), np.percentile(a, 90), a.reshape(len(res), -1).max(axis=1).mean()))
+        print("| %d (%d) | %s |" % (l + 1, nit, " | ".join(cells)), flush=True)
+    for plans, mlp in sets:
+        B.pivot_mlp_plan_destroy(mlp)
+        for h in plans:
+            B.pivot_fc_plan_destroy(h)
+    torch.cuda.empty_cache()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--build", action="store_true")
@@ -115,6 +175,13 @@ def main():
         p = WL.config4(seed=0)[0]
         run_case("configs[3] layer 1: 4096x25088 fp32, 32x32 tiles, 10 % balanced, cold", p, 16)
         run_case("configs[3] layer 1: 4096x25088 fp32, 32x32 tiles, 10 % balanced, warm", p, 1)
+    if "cfg4" in cases:
+        for elim in (False, True):
+            probs = WL.config4(seed=0, eliminated=elim)
+            tag = "eliminated" if elim else "composed"
+            run_chain("configs[3] chain 25088-4096-4096-1000 fp32 in one launch, %s boundaries, cold" % tag, probs, 12)
+            if not elim:
+                run_chain("configs[3] chain in one launch, %s boundaries, warm" % tag, probs, 1)
     if "cfg1" in cases:
         p = WL.config1(seed=0)
         run_case("configs[0]: 1024x1024 fp32, 16x16 tiles, 25 % uniform, cold", p, 200)

@@ -25,6 +25,8 @@
 // Restricted to BRC plans of one weight type with whole block rows per work
 // item, batch 1; an fp16 chain rounds an intermediate to fp16 once, at the
 // producer's store, as the launch-per-layer form does.
+#include <cstdlib>
+
 #include "pivot_fc_kernels.h"
 
 namespace pivot {
@@ -53,7 +55,17 @@ struct ChainArgs {
     ChainLayer L[kMaxChainLayers];
     uint32_t*  ctl;             // [0, kChainMaxGrid): launch counter of every workgroup; [kChainStatus]: status
     int        nlayers;
+    long long* trace;           // timeline builds only (PIVOT_TRACE): [layer][workgroup][wavefront][8] time stamps
 };
+
+// Timeline builds: per layer and wavefront, the 100 MHz clock at 0 item start, 1 every load issued, 2 own
+// x-segments staged (tagged input: the pairs of its producers have arrived), 3 last weight consumed, 4 sums of
+// all wavefronts in LDS, 5 outputs stored.
+#ifdef PIVOT_TRACE
+#define CHAIN_STAMP(i) do { __builtin_amdgcn_sched_barrier(0); ctr_[i] = wall_clock64(); __builtin_amdgcn_sched_barrier(0); } while (0)
+#else
+#define CHAIN_STAMP(i) do {} while (0)
+#endif
 
 __device__ __forceinline__ unsigned long long cld64(const unsigned long long* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -78,6 +90,15 @@ __device__ __forceinline__ bool chain_keep_waiting(uint32_t* ctl, uint32_t& spin
     return true;
 }
 
+// Reads the fields of a layer description from the argument block here, while the current layer's loads are in
+// flight, so that they sit in the scalar cache when the next layer begins (fetched only where they are first
+// used, at the start of that layer, they cost a trip of about 0.7 us with nothing else to do).
+__device__ __forceinline__ void pin_layer(const ChainLayer& p) {
+    asm volatile("" :: "s"(p.chunks), "s"(p.xidx), "s"(p.vals), "s"(p.bias_p), "s"(p.dst), "s"(p.in), "s"(p.out));
+    asm volatile("" :: "s"(p.nitems), "s"(p.slices), "s"(p.bhs), "s"(p.bh_full), "s"(p.uniform_ct), "s"(p.uniform_parts),
+                 "s"(p.chunk_tiles), "s"(p.act), "s"(p.k_valid), "s"(p.xn_vecs));
+}
+
 // One work item of one layer (see fc_gemv_kernel for the streaming scheme).
 // No thread leaves early: every barrier is reached by the whole workgroup.
 // XIN says where the layer's input comes from, at compile time (a run-time branch around the gather loads would
@@ -91,7 +112,8 @@ __device__ __forceinline__ bool chain_keep_waiting(uint32_t* ctl, uint32_t& spin
 enum { kInPlain = 0, kInTagged = 1, kInCopy = 2 };
 template <typename WT, int BH, int BW, int NW, int XIN>
 __device__ __forceinline__ void chain_item(const ChainLayer& P, int item, bool out_tagged,
-                                           uint32_t tag, uint32_t counter, uint32_t* s_tag, uint32_t* ctl, char* smem) {
+                                           uint32_t tag, uint32_t counter, uint32_t* s_tag, uint32_t* ctl, char* smem,
+                                           long long* trace, const ChainLayer& next) {
     using V = typename Elem<WT>::vec;
     constexpr int VEC = Elem<WT>::VEC;
     constexpr int NT  = NW * 64;
@@ -110,6 +132,10 @@ __device__ __forceinline__ void chain_item(const ChainLayer& P, int item, bool o
     float* red = reinterpret_cast<float*>(smem);        // reused after the stream phase
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+#ifdef PIVOT_TRACE
+    long long ctr_[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#endif
+    CHAIN_STAMP(0);
     XRes<WT, 1, NT, 16> xres;
     if constexpr (XIN == kInCopy) xres.load(1, 0, P.xn_vecs, P.in, 0, tid);
     const int chunk = item / P.slices, slice = item - chunk * P.slices;
@@ -120,15 +146,16 @@ __device__ __forceinline__ void chain_item(const ChainLayer& P, int item, bool o
         const int4 cd = P.chunks[2 * chunk];
         br = cd.x; tile_begin = cd.y; ntiles = cd.z - cd.y;
     }
+    // Every wavefront stages the x-segments of its own groups of tiles only (see XStageWave): what it writes to
+    // LDS only it reads, so no workgroup barrier stands between the staging and the first FMA, and with tagged
+    // input a wavefront waits only for the producers of its own tiles.
     const int ne = ntiles * BW, emax = ne > 0 ? ne - 1 : 0;
-    const int dump = P.chunk_tiles * BW + VEC - 1;      // LDS row: chunk_tiles*BW staged elements + 16 bytes
+    const int xs_stride = P.chunk_tiles * BW + VEC;     // LDS row: chunk_tiles*BW staged elements + 16 bytes (dump slot last)
+    const int dump = xs_stride - 1;
     const int32_t* xi = P.xidx + (size_t)tile_begin * BW;
-    int src[XP];
-    #pragma unroll
-    for (int k = 0; k < XP; ++k) {
-        const int e = tid + k * NT;
-        src[k] = xi[e < emax ? e : emax];
-    }
+    using XSW = XStageWave<WT, BW, NW, TPL, XP>;
+    XSW xsw;
+    xsw.load_idx(P.xidx, tile_begin, ne, wave, lane);
 
     const int ngroups = (ntiles + TPL - 1) / TPL;
     const int gmax = ngroups > 0 ? ngroups - 1 : 0;
@@ -162,6 +189,8 @@ __device__ __forceinline__ void chain_item(const ChainLayer& P, int item, bool o
     const float bias = P.bias_p[orow];
     const int   dst  = P.dst[orow];
     __builtin_amdgcn_sched_barrier(0);                  // every load above is issued before anything below waits
+    pin_layer(next);                                    // the next layer's description: into the scalar cache
+    CHAIN_STAMP(1);
 
     // stage the x-segments: plain loads from the caller's x, or pairs re-read until they carry this launch's tag.
     // The first round stands outside the loop so that no loop header sits between its loads and the ones above.
@@ -169,52 +198,53 @@ __device__ __forceinline__ void chain_item(const ChainLayer& P, int item, bool o
         if constexpr (UH == U) xres.store(1, P.xn_vecs, xn, 0, tid);
         lds_barrier();
     }
-    auto stage = [&](int e0) {
-        if constexpr (!IN_TAGGED) {
-            const WT* x = (XIN == kInCopy) ? xn : reinterpret_cast<const WT*>(P.in);
-            WT v[XP];
-            #pragma unroll
-            for (int k = 0; k < XP; ++k) v[k] = x[src[k] > 0 ? src[k] : 0];
-            #pragma unroll
-            for (int k = 0; k < XP; ++k) {
-                const int e = e0 + k * NT;
-                xs[e < ne ? e : dump] = (src[k] >= 0) ? v[k] : WT(0);
-            }
-        } else {
-            const unsigned long long* xp = reinterpret_cast<const unsigned long long*>(P.in);
-            unsigned long long pv[XP];
-            uint32_t spins = 0;
-            for (;;) {
+    if constexpr (!IN_TAGGED) {
+        if constexpr (XIN == kInCopy) xsw.template gather<true>(P.xidx, xn, xs, xs_stride, tile_begin, ne, wave, lane);
+        else xsw.template gather<false>(P.xidx, reinterpret_cast<const WT*>(P.in), xs, xs_stride, tile_begin, ne, wave, lane);
+    } else {
+        // pairs re-read until they carry this launch's tag.  Only lanes that need a pair load one: these loads
+        // are not cached, every one of them is a trip through the fabric.
+        const unsigned long long* xp = reinterpret_cast<const unsigned long long*>(P.in);
+        uint32_t spins = 0;
+        for (int e0 = 0; XSW::pos_of(e0, wave) < ne; e0 += XP * 64) {       // the same trip count in every lane
+            int sr[XP];
+            if (e0 == 0) {
                 #pragma unroll
-                for (int k = 0; k < XP; ++k) pv[k] = cld64(xp + ((src[k] > 0 && src[k] < P.k_valid) ? src[k] : 0));
-                bool ok = true;
+                for (int k = 0; k < XP; ++k) sr[k] = xsw.src[k];
+            } else {
                 #pragma unroll
                 for (int k = 0; k < XP; ++k) {
-                    const int e = e0 + k * NT;
-                    const bool needed = e < ne && src[k] >= 0 && src[k] < P.k_valid;
-                    ok = ok && (!needed || (uint32_t)(pv[k] >> 32) == tag);
+                    const int pos = XSW::pos_of(e0 + lane + k * 64, wave);
+                    sr[k] = xi[pos < emax ? pos : emax];
                 }
-                if (ok) break;
+            }
+            unsigned long long pv[XP];
+            bool needed[XP];
+            #pragma unroll
+            for (int k = 0; k < XP; ++k) {
+                const int pos = XSW::pos_of(e0 + lane + k * 64, wave);
+                needed[k] = pos < ne && sr[k] >= 0 && sr[k] < P.k_valid;    // padding columns read as zero
+                pv[k] = 0;
+            }
+            for (;;) {
+                #pragma unroll
+                for (int k = 0; k < XP; ++k)
+                    if (needed[k] && (uint32_t)(pv[k] >> 32) != tag) pv[k] = cld64(xp + sr[k]);
+                bool ok = true;
+                #pragma unroll
+                for (int k = 0; k < XP; ++k) ok = ok && (!needed[k] || (uint32_t)(pv[k] >> 32) == tag);
+                if (!__any(!ok)) break;                                     // the whole wavefront leaves together
                 if (!chain_keep_waiting(ctl, spins)) break;
             }
             #pragma unroll
             for (int k = 0; k < XP; ++k) {
-                const int e = e0 + k * NT;
-                const bool real = src[k] >= 0 && src[k] < P.k_valid;    // padding columns read as zero
-                xs[e < ne ? e : dump] = real ? WT(__uint_as_float((uint32_t)pv[k])) : WT(0);
+                const int pos = XSW::pos_of(e0 + lane + k * 64, wave);
+                xs[pos < ne ? pos : dump] = needed[k] ? WT(__uint_as_float((uint32_t)pv[k])) : WT(0);
             }
         }
-    };
-    stage(tid);
-    for (int r = XP * NT; r < ne; r += XP * NT) {       // longer work items: further rounds (uniform trip count)
-        #pragma unroll
-        for (int k = 0; k < XP; ++k) {
-            const int e = tid + r + k * NT;
-            src[k] = xi[e < emax ? e : emax];
-        }
-        stage(tid + r);
     }
-    lds_barrier();
+    wave_lds_sync();
+    CHAIN_STAMP(2);
 
     float acc[NL];
     #pragma unroll
@@ -242,13 +272,17 @@ __device__ __forceinline__ void chain_item(const ChainLayer& P, int item, bool o
         const int g = g0 + u * NW;
         if (g < ngroups && g * TPL + ts < ntiles) consume(u, g);
     }
+    CHAIN_STAMP(3);
     #pragma unroll
     for (int j = 0; j < NL; ++j) {
         float v = group_sum<LPR>(acc[j]);
         if constexpr (TPL > 1) v = stride_sum<BH * LPR>(v);
         acc[j] = v;
     }
-    __syncthreads();                                    // xs no longer needed; red aliases it
+    // The barriers from here on order LDS traffic only (lds_barrier): __syncthreads() would also wait for every
+    // outstanding store, and the device-coherent stores of the PREVIOUS layer's outputs take about a microsecond
+    // to be acknowledged; nothing in this workgroup depends on them.
+    lds_barrier();                                      // xs no longer needed; red aliases it
     if (cg == 0 && (TPL == 1 || s < BH)) {
         #pragma unroll
         for (int j = 0; j < NL; ++j) {
@@ -259,7 +293,8 @@ __device__ __forceinline__ void chain_item(const ChainLayer& P, int item, bool o
     // a workgroup whose first layer is layer 0 learns its tag here: thread 0's load of the launch counter,
     // requested at kernel start, has long arrived and rides on this barrier to the other threads
     if (s_tag && tid == 0) *s_tag = counter + 1u;
-    __syncthreads();
+    lds_barrier();
+    CHAIN_STAMP(4);
     if (s_tag) tag = *s_tag;
     if (tid < BH) {
         float sum = 0.f;
@@ -276,7 +311,14 @@ __device__ __forceinline__ void chain_item(const ChainLayer& P, int item, bool o
                 reinterpret_cast<float*>(P.out)[dst] = v;
         }
     }
-    __syncthreads();                                    // the next layer's staging reuses the LDS
+#ifdef PIVOT_TRACE
+    CHAIN_STAMP(5);                                     // stores issued, not yet acknowledged
+    if (trace && lane == 0) {
+        long long* t_ = trace + ((size_t)item * NW + wave) * 8;
+        for (int i_ = 0; i_ < 8; ++i_) t_[i_] = ctr_[i_];
+    }
+#endif
+    lds_barrier();                                      // the next layer's staging reuses the LDS
 }
 
 // The first layer's pointers and shape come as separate leading arguments: those are preloaded into SGPRs with the
@@ -298,7 +340,7 @@ __global__ void __launch_bounds__(kChainNW * 64) mlp_persist_kernel(
     if (threadIdx.x == 0) counter = cld32(A.ctl + wg);
     uint32_t tag = 0;
     bool have_tag = false;
-    auto run_layer = [&](const ChainLayer& P, int l) {
+    auto run_layer = [&](const ChainLayer& P, int l, const ChainLayer& next) {
         const bool in_tagged = l > 0, out_tagged = l + 1 < A.nlayers;
         if (!have_tag && in_tagged) {
             if (threadIdx.x == 0) s_tag = counter + 1u;
@@ -308,26 +350,27 @@ __global__ void __launch_bounds__(kChainNW * 64) mlp_persist_kernel(
             if (threadIdx.x == 0) cst32(A.ctl + wg, tag);   // bumped by its only reader: no other workgroup touches it
         }
         uint32_t* st = have_tag ? nullptr : &s_tag;
+        long long* tr = A.trace ? A.trace + (size_t)l * kChainMaxGrid * kChainNW * 8 : nullptr;
         if (in_tagged) {
             switch (P.bhs) {
-                case 8:  chain_item<WT, 8,  BW, kChainNW, kInTagged>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
-                case 16: chain_item<WT, 16, BW, kChainNW, kInTagged>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
-                case 32: chain_item<WT, 32, BW, kChainNW, kInTagged>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
-                default: chain_item<WT, 64, BW, kChainNW, kInTagged>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
+                case 8:  chain_item<WT, 8,  BW, kChainNW, kInTagged>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next); break;
+                case 16: chain_item<WT, 16, BW, kChainNW, kInTagged>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next); break;
+                case 32: chain_item<WT, 32, BW, kChainNW, kInTagged>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next); break;
+                default: chain_item<WT, 64, BW, kChainNW, kInTagged>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next); break;
             }
         } else if (P.xn_vecs > 0) {
             switch (P.bhs) {
-                case 8:  chain_item<WT, 8,  BW, kChainNW, kInCopy>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
-                case 16: chain_item<WT, 16, BW, kChainNW, kInCopy>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
-                case 32: chain_item<WT, 32, BW, kChainNW, kInCopy>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
-                default: chain_item<WT, 64, BW, kChainNW, kInCopy>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
+                case 8:  chain_item<WT, 8,  BW, kChainNW, kInCopy>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next); break;
+                case 16: chain_item<WT, 16, BW, kChainNW, kInCopy>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next); break;
+                case 32: chain_item<WT, 32, BW, kChainNW, kInCopy>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next); break;
+                default: chain_item<WT, 64, BW, kChainNW, kInCopy>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next); break;
             }
         } else {
             switch (P.bhs) {
-                case 8:  chain_item<WT, 8,  BW, kChainNW, kInPlain>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
-                case 16: chain_item<WT, 16, BW, kChainNW, kInPlain>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
-                case 32: chain_item<WT, 32, BW, kChainNW, kInPlain>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
-                default: chain_item<WT, 64, BW, kChainNW, kInPlain>(P, wg, out_tagged, tag, counter, st, A.ctl, smem); break;
+                case 8:  chain_item<WT, 8,  BW, kChainNW, kInPlain>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next); break;
+                case 16: chain_item<WT, 16, BW, kChainNW, kInPlain>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next); break;
+                case 32: chain_item<WT, 32, BW, kChainNW, kInPlain>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next); break;
+                default: chain_item<WT, 64, BW, kChainNW, kInPlain>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next); break;
             }
         }
         if (!have_tag) {                                // s_tag was set inside the item, before its last barriers
@@ -336,6 +379,8 @@ __global__ void __launch_bounds__(kChainNW * 64) mlp_persist_kernel(
             if (threadIdx.x == 0) cst32(A.ctl + wg, tag);
         }
     };
+    // the description of the layer after the current one is touched inside the current item (pin_layer), so that
+    // it sits in the scalar cache when that layer begins
     if (wg < q0_nitems) {                               // uniform over the workgroup
         ChainLayer P0;
         P0.xidx = p0_xidx; P0.vals = p0_vals; P0.in = p0_in; P0.bias_p = p0_bias; P0.dst = p0_dst;
@@ -343,11 +388,11 @@ __global__ void __launch_bounds__(kChainNW * 64) mlp_persist_kernel(
         P0.slices = q0_shape & 0xFF; P0.bhs = (q0_shape >> 8) & 0xFF; P0.bh_full = (q0_shape >> 16) & 0xFF;
         P0.chunk_tiles = q0_chunk_tiles & 0xFFFF; P0.xn_vecs = q0_chunk_tiles >> 16; P0.nitems = q0_nitems;
         P0.chunks = A.L[0].chunks; P0.out = A.L[0].out; P0.act = A.L[0].act; P0.k_valid = A.L[0].k_valid;
-        run_layer(P0, 0);
+        run_layer(P0, 0, A.L[1]);                        // (a chain has at least two layers)
     }
     for (int l = 1; l < A.nlayers; ++l) {
         const ChainLayer& P = A.L[l];
-        if (wg < P.nitems) run_layer(P, l);             // uniform over the workgroup
+        if (wg < P.nitems) run_layer(P, l, A.L[l + 1 < A.nlayers ? l + 1 : l]);   // uniform over the workgroup
     }
 }
 
@@ -442,6 +487,11 @@ int launch_chain_persist(const ChainPersistLaunch& C) {
     const int Lc = (int)C.layers.size();
     A.nlayers = Lc;
     A.ctl = C.ctl;
+    A.trace = nullptr;
+#ifdef PIVOT_TRACE
+    // timeline builds: [layer][1024 workgroups][8 wavefronts][8] int64 time stamps
+    if (const char* e = getenv("PIVOT_CHAIN_TRACE_PTR")) A.trace = reinterpret_cast<long long*>(strtoull(e, nullptr, 0));
+#endif
     for (int l = 0; l < Lc; ++l) {
         const ChainPersistLayer& s = C.layers[l];
         const HostPlan& hp = *s.hp;
