@@ -12,6 +12,14 @@ latest wavefront, all relative to the first wavefront's start.
     python bench_timeline.py --build            # on the CPU: builds paper_1712_01084_amd/libpivotfc_trace.so
     python bench_timeline.py [--cases cfg2,cfg4l1,cfg4,cfg1,cfg3d]    # on the GPU (cfg4: the one-launch chain kernel)
 
+Ablations: builds of the same sources with -DPIVOT_ABLATE=bits leave one part
+of the vector kernel's work out (no x, no staging, no copy of x, no store, no
+epilogue; their results are wrong on purpose) and are timed like the product
+(cold and warm us per launch, replayed graphs), which prices each part:
+
+    python bench_timeline.py --build-ablations  # on the CPU (after the product build)
+    python bench_timeline.py --ablations        # on the GPU
+
 The stamps cost a few tens of nanoseconds per phase, so a traced launch is
 slightly slower than the product kernel; the table shows where the time goes,
 the product's time per launch comes from bench.py / bench_configs.py.
@@ -34,6 +42,67 @@ PHASES = ["wave started", "every load issued", "copy of x stored to LDS", "past 
 def build():
     from paper_1712_01084_amd import build as Bd
     print(Bd.build(out=TRACE_LIB, objdir=os.path.join(Bd.HERE, "_build_trace"), device_flags=Bd.DEVICE + ["-DPIVOT_TRACE"]))
+
+
+ABLATIONS = [(0, "product"), (1, "no x at all (no copy, no gather index, no staging)"),
+             (2, "x copied into LDS but never staged (no barrier behind the copy, no gather)"),
+             (4, "no copy of x (barrier and LDS-to-LDS gather kept)"), (8, "outputs computed but not stored"),
+             (16, "no reduction, no outputs"), (17, "no x and no reduction: the weight stream alone")]
+
+
+def ablation_lib(bits):
+    from paper_1712_01084_amd import build as Bd
+    return Bd.LIB if bits == 0 else os.path.join(Bd.HERE, "libpivotfc_abl%d.so" % bits)
+
+
+def build_ablations():
+    from paper_1712_01084_amd import build as Bd
+    for bits, _ in ABLATIONS:
+        if bits:
+            print(Bd.build(out=ablation_lib(bits), objdir=os.path.join(Bd.HERE, "_build_trace", "abl%d" % bits),
+                           device_flags=Bd.DEVICE + ["-DPIVOT_ABLATE=%d" % bits], only=["pivot_gemv_f32.hip"]))
+
+
+def time_ablations():
+    """Each library in a process of its own (one process cannot load two builds of the same symbols)."""
+    import json
+    import subprocess
+    print("# What each part of the batch-1 layer kernel costs: configs[1] (4096x9216 fp32, 32x32 tiles, 10 % balanced)\n")
+    print("| build | cold us / launch | warm us / launch |")
+    print("|---|---|---|")
+    for rep in range(2):
+        for bits, what in ABLATIONS:
+            lib = ablation_lib(bits)
+            if not os.path.exists(lib):
+                sys.exit("bench_timeline.py: %s is not built (run with --build-ablations first)" % lib)
+            out = subprocess.run([sys.executable, os.path.abspath(__file__), "--time-one", lib], stdout=subprocess.PIPE, text=True, check=True).stdout
+            r = json.loads(out.strip().splitlines()[-1])
+            print("| %s%s | %.2f | %.2f |" % (what, " (second pass)" if rep else "", r["cold"], r["warm"]), flush=True)
+
+
+def time_one(lib):
+    import json
+    import numpy as np
+    import torch
+    from paper_1712_01084_amd import binding as B
+    from paper_1712_01084_amd import workloads as WL
+    import bench_util as BU
+    B.LIB_PATH = lib
+    p = WL.config2(seed=0)
+    plan0 = B.pivot_fc_plan(p.M, p.K, p.bh, p.bw, B.PIVOT_F32, p.Wp, B.PIVOT_W_PIVOTED, p.tile_mask, p.prow, p.pcol, p.bias,
+                            act=p.act, device=0)
+    nc = 40
+    plans = [plan0] + [B.pivot_fc_plan_clone(plan0) for _ in range(nc - 1)]
+    xs = [torch.from_numpy(p.x.copy()).cuda() for _ in range(nc)]
+    ys = [torch.empty((1, p.M), dtype=torch.float32, device="cuda") for _ in range(nc)]
+    ws = torch.zeros(4096, dtype=torch.uint8, device="cuda")
+
+    def step(rot):
+        return lambda i, s: B.pivot_fc_run(plans[i % nc if rot else 0], xs[i % nc if rot else 0].data_ptr(), p.K,
+                                           ys[i % nc if rot else 0].data_ptr(), p.M, 1, ws.data_ptr(), ws.numel(), s)
+    cold = BU.graph_time(step(True), 80, replays=12, repeats=3)
+    warm = BU.graph_time(step(False), 100, replays=10, repeats=3)
+    print(json.dumps({"cold": cold, "warm": warm}))
 
 
 def run_case(label, p, ncopies, bursts=14, **plan_kw):
@@ -150,11 +219,23 @@ def run_chain(label, probs, ncopies, bursts=12):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--build", action="store_true")
+    ap.add_argument("--build-ablations", action="store_true")
+    ap.add_argument("--ablations", action="store_true")
+    ap.add_argument("--time-one", default=None, help=argparse.SUPPRESS)
     ap.add_argument("--cases", default="cfg2,cfg4l1")
     ap.add_argument("--lib", default=TRACE_LIB)
     args = ap.parse_args()
     if args.build:
         build()
+        return
+    if args.build_ablations:
+        build_ablations()
+        return
+    if args.time_one:
+        time_one(args.time_one)
+        return
+    if args.ablations:
+        time_ablations()
         return
     import torch
     from paper_1712_01084_amd import binding as B

@@ -45,13 +45,24 @@ def _compile(src, objdir=None, device_flags=None):
     return obj, out
 
 
-def build(verbose=False, out=None, objdir=None, device_flags=None):
+def build(verbose=False, out=None, objdir=None, device_flags=None, only=None):
     """Compiles every source and links the shared library.  ``out``, ``objdir``
-    and ``device_flags`` let an experiment build a variant beside the product."""
+    and ``device_flags`` let an experiment build a variant beside the product;
+    with ``only`` (a list of sources) just those are compiled with the variant's
+    flags and every other object is taken from the product build."""
     objdir = objdir or OBJDIR
     os.makedirs(objdir, exist_ok=True)
+
+    def one(src):
+        if only is not None and src not in only:
+            obj = os.path.join(OBJDIR, os.path.splitext(src)[0] + ".o")
+            if not os.path.exists(obj):
+                raise RuntimeError("%s missing: build the product first" % obj)
+            return obj, ""
+        return _compile(src, objdir, device_flags)
+
     with ThreadPoolExecutor(max_workers=8) as ex:
-        results = list(ex.map(lambda s: _compile(s, objdir, device_flags), SOURCES))
+        results = list(ex.map(one, SOURCES))
     if verbose:
         for _, log in results:
             if log.strip():

@@ -63,6 +63,16 @@ struct FcArgs {
 // clock at eight points per wavefront: 0 start, 1 every load issued, 2 copy of x stored to LDS, 3 past the
 // barrier behind it, 4 x-segments staged, 5 last weight consumed, 6 sums of all wavefronts in LDS, 7 outputs
 // stored.  In ordinary builds the stamps compile to nothing.
+// Ablation builds (-DPIVOT_ABLATE=bits, see bench_timeline.py --ablations): the vector kernel with one part of
+// its work left out, to measure what that part costs.  The results of such a build are wrong on purpose; every
+// access stays in bounds.  1: no x at all (no copy, no gather index, no staging; the FMAs read whatever the LDS
+// holds)  2: x copied into LDS but never staged (no barrier behind the copy, no gather)  4: no copy of x (barrier
+// and LDS-to-LDS gather kept, from an LDS region nobody filled)  8: outputs computed but not stored
+// 16: no reduction and no outputs (one value per workgroup is stored).  The product build has PIVOT_ABLATE 0.
+#ifndef PIVOT_ABLATE
+#define PIVOT_ABLATE 0
+#endif
+
 #ifdef PIVOT_TRACE
 #define PIVOT_STAMP_DECL long long tr_[8] = {0, 0, 0, 0, 0, 0, 0, 0}
 #define PIVOT_STAMP(i) do { __builtin_amdgcn_sched_barrier(0); tr_[i] = wall_clock64(); __builtin_amdgcn_sched_barrier(0); } while (0)
@@ -472,6 +482,7 @@ __device__ __forceinline__ void finish_rows(const FcArgs& a, const float* red, i
             for (int w = 0; w < nred; ++w) s += red[w * N + idx];
         }
         const float v = apply_act(s + rp.bias[k], a.act);
+        if ((PIVOT_ABLATE & 8) && !(v == 12345.678f)) continue;      // ablation: computed, never stored
         if (rp.dst[k] >= 0) store_out(a.y, (long long)(b0 + j) * a.ldy + rp.dst[k], v, a.out_f16);
     }
 }
@@ -521,7 +532,8 @@ __global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(PIVOT_GEMV_PARAMS, FcA
     const long long q_ldx = (NB == 1) ? 0 : (XR != 0) ? (long long)q_xn_vecs * VEC : a.ldx;
     // order of issue = order of arrival: (x,) gather indices, then the weights, then the epilogue operands
     XRes<WT, NB, NT, (XR == 3) ? 16 : 8> xres;
-    if constexpr (XR >= 2) xres.load(q_batch, q_ldx, q_xn_vecs, p_x, b0, tid);
+    constexpr bool kLoadX = !(PIVOT_ABLATE & (1 | 4)), kStageX = !(PIVOT_ABLATE & (1 | 2));
+    if constexpr (XR >= 2 && kLoadX) xres.load(q_batch, q_ldx, q_xn_vecs, p_x, b0, tid);
     const Chunk ck = load_chunk(q_uniform_ct, q_uniform_parts, p_chunks, a.part_base);
     const int br = ck.br, tile_begin = ck.tile_begin, ntiles = ck.ntiles, slot = ck.slot;
     const int first = ck.first, nparts = ck.nparts;
@@ -529,12 +541,13 @@ __global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(PIVOT_GEMV_PARAMS, FcA
     const int row0 = br * q_bh_full + slice * BH;
     const int tile_elems = q_bh_full * BW;
 
-    if constexpr (XR == 1) xres.load(q_batch, q_ldx, q_xn_vecs, p_x, b0, tid);
+    if constexpr (XR == 1 && kLoadX) xres.load(q_batch, q_ldx, q_xn_vecs, p_x, b0, tid);
     constexpr int XPF = (XR == 3) ? 8 : 4;              // long inputs come with long work items: 8 indices up front
     XStage<WT, BW, NB, NT, XPF> xst;                    // several batch rows: staged by the whole workgroup
     XStageWave<WT, BW, NW, TPL, XPF> xsw;               // one batch row: every wavefront stages for itself
-    if constexpr (NB == 1) xsw.load_idx(p_idx, tile_begin, ntiles * BW, wave, lane);
-    else                   xst.load_idx(p_idx, tile_begin, ntiles * BW, tid);
+    if constexpr (!kStageX) { /* ablation: no gather index */ }
+    else if constexpr (NB == 1) xsw.load_idx(p_idx, tile_begin, ntiles * BW, wave, lane);
+    else                        xst.load_idx(p_idx, tile_begin, ntiles * BW, tid);
 
     const int s  = lane / LPR;                          // row within the wave-load
     const int cg = lane % LPR;                          // column group
@@ -568,7 +581,7 @@ __global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(PIVOT_GEMV_PARAMS, FcA
     issue(wave, 0, UH);
     if constexpr (UH < U) {
         __builtin_amdgcn_sched_barrier(0);
-        xres.store(q_batch, q_xn_vecs, xn, b0, tid);
+        if constexpr (kLoadX) xres.store(q_batch, q_xn_vecs, xn, b0, tid);
         __builtin_amdgcn_sched_barrier(0);
         issue(wave, UH, U);
     }
@@ -578,14 +591,16 @@ __global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(PIVOT_GEMV_PARAMS, FcA
     __builtin_amdgcn_sched_barrier(0);
     PIVOT_STAMP(1);
     if constexpr (XR != 0) {
-        if constexpr (UH == U) xres.store(q_batch, q_xn_vecs, xn, b0, tid);
+        if constexpr (UH == U && kLoadX) xres.store(q_batch, q_xn_vecs, xn, b0, tid);
         PIVOT_STAMP(2);
-        lds_barrier();
+        if constexpr (kStageX) lds_barrier();
         PIVOT_STAMP(3);
-        if constexpr (NB == 1) xsw.template gather<true>(p_idx, xn, xs, q_xs_stride, tile_begin, ntiles * BW, wave, lane);
+        if constexpr (!kStageX) { /* ablation: nothing staged */ }
+        else if constexpr (NB == 1) xsw.template gather<true>(p_idx, xn, xs, q_xs_stride, tile_begin, ntiles * BW, wave, lane);
         else xst.template gather<true>(q_batch, q_ldx, q_xn_vecs * VEC, q_xs_stride, p_idx, xn, xs, tile_begin, ntiles * BW, b0, tid);
     } else {
-        if constexpr (NB == 1) xsw.template gather<false>(p_idx, reinterpret_cast<const WT*>(p_x), xs, q_xs_stride, tile_begin, ntiles * BW, wave, lane);
+        if constexpr (!kStageX) { /* ablation: nothing staged */ }
+        else if constexpr (NB == 1) xsw.template gather<false>(p_idx, reinterpret_cast<const WT*>(p_x), xs, q_xs_stride, tile_begin, ntiles * BW, wave, lane);
         else xst.template gather<false>(q_batch, q_ldx, 0, q_xs_stride, p_idx, reinterpret_cast<const WT*>(p_x), xs, tile_begin, ntiles * BW, b0, tid);
     }
     // what a wavefront staged for itself only it reads: LDS operations of one wavefront complete in order
@@ -631,6 +646,15 @@ __global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(PIVOT_GEMV_PARAMS, FcA
     }
 
     PIVOT_STAMP(5);
+    if constexpr (PIVOT_ABLATE & 16) {                  // ablation: one value per workgroup instead of the outputs
+        float t = rp.bias[0] + (float)rp.dst[0];
+        #pragma unroll
+        for (int j = 0; j < NL; ++j)
+            #pragma unroll
+            for (int b = 0; b < NB; ++b) t += acc[j][b];
+        if (tid == 0) reinterpret_cast<float*>(a.y)[0] = t;
+        return;
+    }
     // lanes -> rows
     #pragma unroll
     for (int j = 0; j < NL; ++j)
