@@ -38,6 +38,12 @@ constexpr int kChainNW = 8;                     // wavefronts per workgroup
 constexpr int kChainMaxGrid = 1024;             // launch-counter words
 constexpr int kChainStatus = 1024;              // index of the status word
 constexpr uint32_t kChainSpinLimit = 1u << 18;
+// LDS in front of the staged input: the wavefronts' partial sums, two slots used by a workgroup's items in turn.  With a
+// slot of their own the sums need ONE workgroup barrier per item (all sums written -> the finishing wavefront
+// reads them): a wavefront that is past it may stage the next layer's input and even write that layer's sums
+// (other slot) while the finishing wavefront still reads this layer's; it reaches the slot after that only past
+// the next item's barrier, which the finishing wavefront joins when it has read.
+constexpr int kChainRedBytes = 2 * kChainNW * 64 * 4;
 
 struct ChainLayer {
     const int4*    chunks;      // eight ints per chunk (irregular schedules)
@@ -113,7 +119,7 @@ enum { kInPlain = 0, kInTagged = 1, kInCopy = 2 };
 template <typename WT, int BH, int BW, int NW, int XIN>
 __device__ __forceinline__ void chain_item(const ChainLayer& P, int item, bool out_tagged,
                                            uint32_t tag, uint32_t counter, uint32_t* s_tag, uint32_t* ctl, char* smem,
-                                           long long* trace, const ChainLayer& next) {
+                                           long long* trace, const ChainLayer& next, int red_slot) {
     using V = typename Elem<WT>::vec;
     constexpr int VEC = Elem<WT>::VEC;
     constexpr int NT  = NW * 64;
@@ -126,10 +132,10 @@ __device__ __forceinline__ void chain_item(const ChainLayer& P, int item, bool o
     constexpr int XP  = IN_TAGGED ? 4 : 8;
     static_assert(BH <= NT, "one thread per output row");
 
-    // LDS: [copy of x + a dump vector (kInCopy)][staged x-segments]; the sums reuse it afterwards
-    WT* xn  = reinterpret_cast<WT*>(smem);
+    // LDS: [partial sums, two slots][copy of x + a dump vector (kInCopy)][staged x-segments]
+    WT* xn  = reinterpret_cast<WT*>(smem + kChainRedBytes);
     WT* xs  = (XIN == kInCopy) ? xn + (size_t)P.xn_vecs * VEC + VEC : xn;
-    float* red = reinterpret_cast<float*>(smem);        // reused after the stream phase
+    float* red = reinterpret_cast<float*>(smem) + red_slot * (NW * 64);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 #ifdef PIVOT_TRACE
@@ -279,10 +285,6 @@ __device__ __forceinline__ void chain_item(const ChainLayer& P, int item, bool o
         if constexpr (TPL > 1) v = stride_sum<BH * LPR>(v);
         acc[j] = v;
     }
-    // The barriers from here on order LDS traffic only (lds_barrier): __syncthreads() would also wait for every
-    // outstanding store, and the device-coherent stores of the PREVIOUS layer's outputs take about a microsecond
-    // to be acknowledged; nothing in this workgroup depends on them.
-    lds_barrier();                                      // xs no longer needed; red aliases it
     if (cg == 0 && (TPL == 1 || s < BH)) {
         #pragma unroll
         for (int j = 0; j < NL; ++j) {
@@ -293,6 +295,10 @@ __device__ __forceinline__ void chain_item(const ChainLayer& P, int item, bool o
     // a workgroup whose first layer is layer 0 learns its tag here: thread 0's load of the launch counter,
     // requested at kernel start, has long arrived and rides on this barrier to the other threads
     if (s_tag && tid == 0) *s_tag = counter + 1u;
+    // The item's only workgroup barrier.  It orders LDS traffic only (lds_barrier): __syncthreads() would also
+    // wait for every outstanding store, and the device-coherent stores of the PREVIOUS layer's outputs take about
+    // a microsecond to be acknowledged; nothing in this workgroup depends on them.  Behind it every wavefront has
+    // consumed its staged input, so the next item may overwrite that.
     lds_barrier();
     CHAIN_STAMP(4);
     if (s_tag) tag = *s_tag;
@@ -311,14 +317,13 @@ __device__ __forceinline__ void chain_item(const ChainLayer& P, int item, bool o
                 reinterpret_cast<float*>(P.out)[dst] = v;
         }
     }
-#ifdef PIVOT_TRACE
     CHAIN_STAMP(5);                                     // stores issued, not yet acknowledged
+#ifdef PIVOT_TRACE
     if (trace && lane == 0) {
         long long* t_ = trace + ((size_t)item * NW + wave) * 8;
         for (int i_ = 0; i_ < 8; ++i_) t_[i_] = ctr_[i_];
     }
 #endif
-    lds_barrier();                                      // the next layer's staging reuses the LDS
 }
 
 // The first layer's pointers and shape come as separate leading arguments: those are preloaded into SGPRs with the
@@ -340,6 +345,8 @@ __global__ void __launch_bounds__(kChainNW * 64) mlp_persist_kernel(
     if (threadIdx.x == 0) counter = cld32(A.ctl + wg);
     uint32_t tag = 0;
     bool have_tag = false;
+    int red_slot = 0;                                   // flips with every item this workgroup runs (not with the layer:
+                                                        // a workgroup may have no item in some layer)
     auto run_layer = [&](const ChainLayer& P, int l, const ChainLayer& next) {
         const bool in_tagged = l > 0, out_tagged = l + 1 < A.nlayers;
         if (!have_tag && in_tagged) {
@@ -353,27 +360,28 @@ __global__ void __launch_bounds__(kChainNW * 64) mlp_persist_kernel(
         long long* tr = A.trace ? A.trace + (size_t)l * kChainMaxGrid * kChainNW * 8 : nullptr;
         if (in_tagged) {
             switch (P.bhs) {
-                case 8:  chain_item<WT, 8,  BW, kChainNW, kInTagged>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next); break;
-                case 16: chain_item<WT, 16, BW, kChainNW, kInTagged>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next); break;
-                case 32: chain_item<WT, 32, BW, kChainNW, kInTagged>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next); break;
-                default: chain_item<WT, 64, BW, kChainNW, kInTagged>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next); break;
+                case 8:  chain_item<WT, 8,  BW, kChainNW, kInTagged>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next, red_slot); break;
+                case 16: chain_item<WT, 16, BW, kChainNW, kInTagged>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next, red_slot); break;
+                case 32: chain_item<WT, 32, BW, kChainNW, kInTagged>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next, red_slot); break;
+                default: chain_item<WT, 64, BW, kChainNW, kInTagged>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next, red_slot); break;
             }
         } else if (P.xn_vecs > 0) {
             switch (P.bhs) {
-                case 8:  chain_item<WT, 8,  BW, kChainNW, kInCopy>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next); break;
-                case 16: chain_item<WT, 16, BW, kChainNW, kInCopy>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next); break;
-                case 32: chain_item<WT, 32, BW, kChainNW, kInCopy>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next); break;
-                default: chain_item<WT, 64, BW, kChainNW, kInCopy>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next); break;
+                case 8:  chain_item<WT, 8,  BW, kChainNW, kInCopy>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next, red_slot); break;
+                case 16: chain_item<WT, 16, BW, kChainNW, kInCopy>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next, red_slot); break;
+                case 32: chain_item<WT, 32, BW, kChainNW, kInCopy>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next, red_slot); break;
+                default: chain_item<WT, 64, BW, kChainNW, kInCopy>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next, red_slot); break;
             }
         } else {
             switch (P.bhs) {
-                case 8:  chain_item<WT, 8,  BW, kChainNW, kInPlain>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next); break;
-                case 16: chain_item<WT, 16, BW, kChainNW, kInPlain>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next); break;
-                case 32: chain_item<WT, 32, BW, kChainNW, kInPlain>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next); break;
-                default: chain_item<WT, 64, BW, kChainNW, kInPlain>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next); break;
+                case 8:  chain_item<WT, 8,  BW, kChainNW, kInPlain>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next, red_slot); break;
+                case 16: chain_item<WT, 16, BW, kChainNW, kInPlain>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next, red_slot); break;
+                case 32: chain_item<WT, 32, BW, kChainNW, kInPlain>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next, red_slot); break;
+                default: chain_item<WT, 64, BW, kChainNW, kInPlain>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next, red_slot); break;
             }
         }
-        if (!have_tag) {                                // s_tag was set inside the item, before its last barriers
+        red_slot ^= 1;
+        if (!have_tag) {                                // s_tag was set inside the item, before its barrier
             tag = s_tag;
             have_tag = true;
             if (threadIdx.x == 0) cst32(A.ctl + wg, tag);
@@ -446,16 +454,15 @@ bool chain_persist_supported(const std::vector<const HostPlan*>& layers, int dev
         G = std::max(G, (int)items);
         const int ct = hp->uniform_ct > 0 ? hp->uniform_ct : hp->chunk_tiles;
         smem = std::max(smem, ((size_t)ct * bw + vec) * es);
-        smem = std::max(smem, (size_t)kChainNW * bhs * 4);
     }
-    smem = align_up(smem, 16);
+    smem = kChainRedBytes + align_up(smem, 16);
     if (smem > 64 * 1024) return no("staged x does not fit in LDS");
     // with the first layer's x copied into LDS whole (chosen at launch if x is 16-byte aligned): 0 = not possible
     size_t smem_copy = 0;
     {
         const HostPlan& f = *layers[0];
         const int ct = f.uniform_ct > 0 ? f.uniform_ct : f.chunk_tiles;
-        const size_t need = ((size_t)f.d.K + vec) * es + ((size_t)ct * bw + vec) * es;
+        const size_t need = kChainRedBytes + ((size_t)f.d.K + vec) * es + ((size_t)ct * bw + vec) * es;
         const size_t item_bytes = (size_t)ct * (f.d.bh / chain_slices(f)) * bw * es;  // same threshold as the layer kernel
         // worth it when the element gather would move at least twice the bytes of the copy (a cache line per element)
         if (item_bytes >= 48 * 1024 && (size_t)ct * bw * 128 >= 2 * (size_t)f.d.K * es && f.d.K % vec == 0 &&
