@@ -16,7 +16,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJDIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libpivotfc.so")
 
-SOURCES = ["pivot_gemv_f32.hip", "pivot_gemv_f16.hip", "pivot_mfma_f16.hip", "pivot_mfma_lds_f16.hip", "pivot_colmajor.hip", "pivot_misc.hip", "pivot_lstm_persist.hip", "pivot_mlp_persist.hip", "pivot_launch.hip", "pivot_static.hip",
+SOURCES = ["pivot_gemv_f32.hip", "pivot_gemv_f16.hip", "pivot_mfma_f16.hip", "pivot_mfma_lds_f16.hip", "pivot_mfma_xrow_f16.hip", "pivot_colmajor.hip", "pivot_misc.hip", "pivot_lstm_persist.hip", "pivot_mlp_persist.hip", "pivot_launch.hip", "pivot_static.hip",
            "pivot_plan.cpp", "pivot_search.cpp", "pivot_api.cpp"]
 
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"), "-I", CSRC,

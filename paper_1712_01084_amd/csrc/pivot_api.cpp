@@ -214,7 +214,7 @@ int prepare(const pivot_fc_plan_t* plan, int batch, void* tickets, void* partial
     L.K = h.d.K; L.x_resident = (h.d.flags & PIVOT_PLAN_GATHER_FROM_GLOBAL) ? 0 : ((h.d.flags & PIVOT_PLAN_GATHER_FROM_LDS_COPY) ? 2 : 1);
     L.M_pad = h.M_pad; L.K_pad = h.K_pad; L.bh = h.d.bh; L.bw = h.d.bw; L.wdtype = h.d.wdtype; L.layout = h.d.layout; L.T = h.T; L.act = h.d.act;
     L.nchunks = h.nchunks; L.nbr = h.nbr; L.chunk_tiles = h.chunk_tiles; L.wg_waves = h.wg_waves;
-    L.lds_tiles = h.lds_tiles();
+    L.lds_tiles = h.lds_tiles(); L.xrow_len = h.xrow_len();
     L.row_slices = h.row_slices;
     L.uniform_ct = h.uniform_ct; L.uniform_parts = h.uniform_parts;
     L.batch = batch;
@@ -229,7 +229,7 @@ int prepare(const pivot_fc_plan_t* plan, int batch, void* tickets, void* partial
 int natural_input(const pivot_fc_plan_t* plan, const void* x_dev, int64_t ldx, int batch, void* xg, void* stream,
                   FcLaunch& L) {
     const HostPlan& h = plan->host;
-    if (fc_uses_matrix_cores(h.d.layout, h.d.wdtype, h.d.bh, h.d.bw, h.lds_tiles(), batch)) {
+    if (fc_uses_matrix_cores(fc_shape(h), batch)) {
         int rc = launch_gather_x(x_dev, ldx, plan->dev.pcol_pad, xg, h.K_pad, batch, h.d.wdtype, stream);
         if (rc != PIVOT_OK) return rc;
         L.x = xg; L.ldx = h.K_pad; L.xidx = plan->dev.xidx_blk; L.xsort = plan->host.sorted_ok ? plan->dev.xsort_blk : nullptr; L.x_block_order = 1;
@@ -468,7 +468,7 @@ int pivot_mlp_run(const pivot_mlp_plan_t* plan, const void* x_dev, int64_t ldx, 
             L.xidx = p->dev.xidx_blk; L.xsort = p->host.sorted_ok ? p->dev.xsort_blk : nullptr; L.x = ws + m.inter_off[l - 1]; L.ldx = p->host.K_pad; L.x_block_order = 1;
             // the kernel that reads its B fragments straight from the rows also reads the padding columns
             // (against zero weights): they must hold finite values, whatever the workspace held before
-            if (p->host.K_pad > p->host.d.K && fc_uses_matrix_cores(p->host.d.layout, p->host.d.wdtype, p->host.d.bh, p->host.d.bw, p->host.lds_tiles(), batch) &&
+            if (p->host.K_pad > p->host.d.K && fc_uses_matrix_cores(fc_shape(p->host), batch) &&
                 (rc = launch_zero_pad_cols(ws + m.inter_off[l - 1], p->host.d.K, p->host.K_pad, batch, elem_size(p->host.d.wdtype), stream)) != PIVOT_OK) return rc;
         }
         if (l + 1 < Lc) {
@@ -633,10 +633,10 @@ int pivot_fc_kernel_name(const pivot_fc_plan_t* plan, int batch, char* buf, size
     L.K = h.d.K; L.x_resident = (h.d.flags & PIVOT_PLAN_GATHER_FROM_GLOBAL) ? 0 : ((h.d.flags & PIVOT_PLAN_GATHER_FROM_LDS_COPY) ? 2 : 1);
     L.M_pad = h.M_pad; L.K_pad = h.K_pad; L.bh = h.d.bh; L.bw = h.d.bw; L.wdtype = h.d.wdtype; L.layout = h.d.layout; L.T = h.T; L.act = h.d.act;
     L.nchunks = h.nchunks; L.nbr = h.nbr; L.chunk_tiles = h.chunk_tiles; L.wg_waves = h.wg_waves;
-    L.lds_tiles = h.lds_tiles(); L.row_slices = h.row_slices; L.uniform_ct = h.uniform_ct; L.uniform_parts = h.uniform_parts;
+    L.lds_tiles = h.lds_tiles(); L.xrow_len = h.xrow_len(); L.row_slices = h.row_slices; L.uniform_ct = h.uniform_ct; L.uniform_parts = h.uniform_parts;
     L.batch = batch;
     // a natural-order x, 16-byte aligned, rows densely packed (what the matrix-core form reads is its own copy)
-    const bool blk = fc_uses_matrix_cores(h.d.layout, h.d.wdtype, h.d.bh, h.d.bw, h.lds_tiles(), batch);
+    const bool blk = fc_uses_matrix_cores(fc_shape(h), batch);
     L.x = reinterpret_cast<const void*>(uintptr_t(256)); L.ldx = blk ? h.K_pad : h.d.K; L.x_block_order = blk ? 1 : 0;
     L.xsort = h.sorted_ok ? reinterpret_cast<const int32_t*>(uintptr_t(256)) : nullptr;
     std::string name;

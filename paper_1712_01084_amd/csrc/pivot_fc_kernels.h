@@ -107,13 +107,14 @@ struct FcArgs {
     const int32_t* __restrict__ p_scatter, int q_ct_parts, int q_misc
 #define PIVOT_GEMV_ARGS(a) (a).chunks, (a).xidx, (a).vals, (a).x, (a).bias_p, (a).scatter, \
     ((a).uniform_ct > 0 ? ((a).uniform_ct | ((a).uniform_parts << 16)) : (a).chunk_tiles), \
-    ((a).bh_full | ((a).batch << 7) | ((a).xn_vecs << 14))
+    ((a).bh_full | ((a).batch << 7) | (int)((unsigned)(a).xn_vecs << 14))
 
 // Per-dtype / per-path launchers, each in its own translation unit.
 int launch_gemv_f32(const FcArgs& a, int bhs, int bw, int nb, int nw, int xres, dim3 grid, size_t smem, hipStream_t st);
 int launch_gemv_f16(const FcArgs& a, int bhs, int bw, int nb, int nw, int xres, dim3 grid, size_t smem, hipStream_t st);
 int launch_mfma_f16(const FcArgs& a, int kind, int bhs, int bw, int nw, dim3 grid, size_t smem, hipStream_t st);
 int launch_mfma_lds_f16(const FcArgs& a, int kind, int bhs, int bw, int nbs, int nw, int xres, dim3 grid, size_t smem, hipStream_t st);
+int launch_mfma_xrow_f16(const FcArgs& a, int kind, int bhs, int bw, dim3 grid, size_t smem, hipStream_t st);
 int launch_colmajor(const FcArgs& a, int layout, int wdtype, int bh, int bw, int nw, dim3 grid, size_t smem, hipStream_t st);
 
 #define PIVOT_SHAPES(X) \
@@ -971,6 +972,190 @@ __global__ void __launch_bounds__(NW * 64) fc_mfma_lds_kernel(PIVOT_GEMV_PARAMS,
 
     // every wave's sums for the staged batch columns go to LDS; the epilogue adds the NW copies
     __syncthreads();                                    // xs no longer needed; red aliases it
+    if (li < NBS) {
+        #pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+            #pragma unroll
+            for (int v = 0; v < CV; ++v)
+                red[wave * N + li * BH + rb * MR + MF::row_of(lane, v)] = acc[rb][v];
+    }
+    __syncthreads();
+    finish_rows<BH, NBS, NT>(a, red, NW, br, slot, first, nparts, rp, b0, tid, &s_flag);
+}
+
+// ---------------------------------------------------------------------------
+// batch 9..16, fp16 weights: matrix cores with the B fragments gathered from a
+// copy of x in LDS (Listing 1: the group fetch through P_col, done where the
+// fragment is formed).  Staging the x-segments of 16 batch rows element by
+// element costs a work item more than streaming its weights (16 rows x tiles x
+// BW two-byte loads and LDS writes, repeated by every row slice of the block
+// row); here the 16 rows of x are copied into LDS whole, in natural order, with
+// independent 16-byte loads, the item's gather indices are copied beside them
+// as byte offsets, and the lane that supplies B[k 8g..8g+7][column n] reads
+// its eight indices with two 16-byte LDS reads and its eight values with eight
+// 2-byte LDS reads from row n.  Rows are 16 bytes apart from a power of two, so
+// the sixteen lanes that read the same column of different rows hit different
+// banks.  Index -1 (padding column) and the partner of a last, single tile
+// of the paired form point at the zeroed 16 bytes behind the row.
+// Needs 8 wavefronts (each copies two rows), at most 512 vectors per row and
+// 8192 staged columns per work item; q_misc bit 31: rows are whole 16-byte
+// vectors, 16-byte aligned and densely packed (else an element-wise copy).
+// ---------------------------------------------------------------------------
+template <int KIND, int BH, int BW>
+__global__ void __launch_bounds__(512) fc_mfma_xrow_kernel(PIVOT_GEMV_PARAMS, FcArgs a) {
+    using MF = Mfma<KIND>;
+    using acc_t = typename MF::acc_t;
+    using WT = _Float16;
+    constexpr int NW = 8, NT = NW * 64, NBS = 16;
+    constexpr int MR = MF::MR, MK = MF::MK, CV = MF::CV;
+    constexpr bool PAIR = (KIND == 2);                  // one MFMA step spans two consecutive tiles
+    constexpr int RB = BH / MR;                         // row blocks per tile slice
+    constexpr int KS = PAIR ? 1 : BW / MK;              // k steps per tile (pair)
+    constexpr int LT = RB * KS;                         // 16-byte weight loads per lane per tile (pair)
+    constexpr int U  = (LT >= 8) ? 1 : 8 / LT;          // tiles (pairs) in flight per wave
+    constexpr int N  = BH * NBS;
+    constexpr int STEP = PAIR ? 2 * BW : BW;            // staged columns per MFMA step along the block row
+    constexpr int XV = 8;                               // vectors of one row a lane copies (2 rows per wavefront)
+    constexpr int IV = 4;                               // int4 of gather indices a thread copies
+    static_assert(BH % MR == 0 && (PAIR ? BW * 2 == MK : BW % MK == 0), "tile shape does not fit this MFMA");
+
+    extern __shared__ __align__(16) char smem[];
+    __shared__ int s_flag;
+    const int q_uniform_parts = q_ct_parts >> 16, q_uniform_ct = q_uniform_parts > 0 ? (q_ct_parts & 0xFFFF) : 0;
+    const int q_bh_full = q_misc & 0x7F, q_batch = (q_misc >> 7) & 0x7F, q_xn_vecs = (q_misc >> 14) & 0x1FFFF;
+    const bool q_vec_rows = q_misc < 0;
+    const int row_bytes = q_xn_vecs * 16 + 16;          // a row of x and 16 zeroed bytes
+    const int zero_off = q_xn_vecs * 16;
+    int* xi_lds = reinterpret_cast<int*>(smem + NBS * row_bytes);
+    float* red = reinterpret_cast<float*>(smem);        // reused after the stream phase: NW * N floats
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int b0 = blockIdx.y * NBS, slice = blockIdx.z;
+
+    // The copy of x, requested first (weights requested first were measured 0.6-0.9 us slower: loads return in
+    // order, and x would wait for them).  Wavefront w takes rows w and w + 8, lane l vectors l, l + 64, ... of each.
+    f16x8 xv_[2][XV];
+    if (q_vec_rows) {
+        #pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            const int b = wave + r * NW;
+            const f16x8* src = reinterpret_cast<const f16x8*>(p_x) + (long long)(b0 + b) * q_xn_vecs;
+            #pragma unroll
+            for (int j = 0; j < XV; ++j) {
+                const int i = lane + j * 64;
+                if (i < q_xn_vecs && b0 + b < q_batch) xv_[r][j] = load16<f16x8>(reinterpret_cast<const WT*>(src + i));
+            }
+        }
+    }
+    const Chunk ck = load_chunk(q_uniform_ct, q_uniform_parts, p_chunks, a.part_base);
+    const int br = ck.br, tile_begin = ck.tile_begin, ntiles = ck.ntiles, slot = ck.slot;
+    const int first = ck.first, nparts = ck.nparts;
+    const int row0 = br * q_bh_full + slice * BH;
+    const int tile_elems = q_bh_full * BW;
+    const int nsteps = PAIR ? (ntiles + 1) / 2 : ntiles; // MFMA steps along the block row: tiles, or pairs of tiles
+    const int ne = ntiles * BW, ne_pad = nsteps * STEP;
+
+    // the item's gather indices (whole int4: a tile has at least 16 columns)
+    const int4* xi4 = reinterpret_cast<const int4*>(p_idx + (size_t)tile_begin * BW);
+    int4 iv[IV];
+    #pragma unroll
+    for (int j = 0; j < IV; ++j) {
+        const int e4 = tid + j * NT;
+        if (e4 * 4 < ne) iv[j] = xi4[e4];
+    }
+
+    const int li = lane % MR;                           // A row / B column of this lane
+    const int lg = lane / MR;                           // k group of 8
+    const _Float16* vbase = reinterpret_cast<const _Float16*>(p_vals) + (size_t)tile_begin * tile_elems
+                            + (size_t)slice * BH * BW + li * BW + (PAIR ? (lg & 1) : lg) * 8;
+    const int tmax = ntiles > 0 ? ntiles - 1 : 0;       // clamped, unconditional loads (see fc_gemv_kernel)
+    f16x8 w[U][LT];
+    auto fill = [&](int u, int t) {
+        const int tt = PAIR ? 2 * t + (lg >> 1) : t;    // this lane's tile
+        const int tc = tt < tmax ? tt : tmax;
+        #pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+            #pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                w[u][rb * KS + ks] = load16<f16x8>(vbase + (size_t)tc * tile_elems + rb * MR * BW + ks * MK);
+                if (PAIR && tt >= ntiles) w[u][rb * KS + ks] = f16x8(0);   // the missing half of the last pair
+            }
+    };
+    #pragma unroll
+    for (int u = 0; u < U; ++u) fill(u, wave + u * NW);
+
+    RowPre<BH, N, NT> rp;
+    rp.load(p_bias, p_scatter, row0, tid);
+    __builtin_amdgcn_sched_barrier(0);                  // every load above is issued before anything below waits
+
+    // x and the indices into LDS (they were requested first, so they arrive first)
+    if (q_vec_rows) {
+        #pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            const int b = wave + r * NW;
+            #pragma unroll
+            for (int j = 0; j < XV; ++j) {
+                const int i = lane + j * 64;
+                if (i < q_xn_vecs && b0 + b < q_batch) *reinterpret_cast<f16x8*>(smem + b * row_bytes + i * 16) = xv_[r][j];
+            }
+        }
+    } else {
+        // rows that are not whole aligned vectors: element by element (a.xn_stride = elements per row)
+        const WT* x = reinterpret_cast<const WT*>(p_x);
+        for (int b = wave; b < NBS; b += NW) {
+            if (b0 + b >= q_batch) continue;
+            for (int c = lane; c < a.xn_stride; c += 64)
+                *reinterpret_cast<WT*>(smem + b * row_bytes + c * 2) = x[(long long)(b0 + b) * a.ldx + c];
+        }
+    }
+    if (tid < NBS * 4) *reinterpret_cast<int*>(smem + (tid >> 2) * row_bytes + zero_off + (tid & 3) * 4) = 0;
+    #pragma unroll
+    for (int j = 0; j < IV; ++j) {
+        const int e4 = tid + j * NT;
+        if (e4 * 4 < ne) {
+            int4 o;
+            o.x = iv[j].x >= 0 ? iv[j].x * 2 : zero_off; o.y = iv[j].y >= 0 ? iv[j].y * 2 : zero_off;
+            o.z = iv[j].z >= 0 ? iv[j].z * 2 : zero_off; o.w = iv[j].w >= 0 ? iv[j].w * 2 : zero_off;
+            *reinterpret_cast<int4*>(xi_lds + e4 * 4) = o;
+        }
+    }
+    if (tid < ne_pad - ne) xi_lds[ne + tid] = zero_off;    // (paired form, odd tile count: BW <= NT entries)
+    lds_barrier();
+
+    acc_t acc[RB];
+    #pragma unroll
+    for (int rb = 0; rb < RB; ++rb) acc[rb] = acc_t(0);
+    const char* xrow = smem + (li < NBS ? li : 0) * row_bytes;
+    const int* xi_l = xi_lds + lg * 8;
+    auto consume = [&](int u, int t) {
+        #pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const int4 i0 = *reinterpret_cast<const int4*>(xi_l + t * STEP + ks * MK);
+            const int4 i1 = *reinterpret_cast<const int4*>(xi_l + t * STEP + ks * MK + 4);
+            f16x8 xv;
+            xv[0] = *reinterpret_cast<const WT*>(xrow + i0.x); xv[1] = *reinterpret_cast<const WT*>(xrow + i0.y);
+            xv[2] = *reinterpret_cast<const WT*>(xrow + i0.z); xv[3] = *reinterpret_cast<const WT*>(xrow + i0.w);
+            xv[4] = *reinterpret_cast<const WT*>(xrow + i1.x); xv[5] = *reinterpret_cast<const WT*>(xrow + i1.y);
+            xv[6] = *reinterpret_cast<const WT*>(xrow + i1.z); xv[7] = *reinterpret_cast<const WT*>(xrow + i1.w);
+            #pragma unroll
+            for (int rb = 0; rb < RB; ++rb) acc[rb] = MF::run(w[u][rb * KS + ks], xv, acc[rb]);
+        }
+    };
+    int t0 = wave;
+    for (; t0 + NW * U < nsteps; t0 += NW * U) {
+        #pragma unroll
+        for (int u = 0; u < U; ++u) {
+            consume(u, t0 + u * NW);
+            fill(u, t0 + u * NW + NW * U);
+        }
+    }
+    #pragma unroll
+    for (int u = 0; u < U; ++u)
+        if (t0 + u * NW < nsteps) consume(u, t0 + u * NW);
+
+    // every wave's sums for the staged batch columns go to LDS; the epilogue adds the NW copies
+    __syncthreads();                                    // x no longer needed; red aliases it
     if (li < NBS) {
         #pragma unroll
         for (int rb = 0; rb < RB; ++rb)

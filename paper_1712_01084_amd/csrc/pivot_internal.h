@@ -47,6 +47,7 @@ struct HostPlan {
     std::vector<int32_t> xsort, xsort_blk;
     bool sorted_ok = false;
     int lds_tiles() const { return sorted_ok ? chunk_tiles : 0; }   // what fc_path takes
+    int xrow_len() const { return K_pad; }                          // likewise: the longest row of x a run can bring
     std::vector<int32_t> chunks;       // nchunks x 4
     std::vector<int32_t> part_base;    // nbr + 1
     std::vector<float>   bias_p;
@@ -105,6 +106,7 @@ struct FcLaunch {
     const int32_t* scatter;     // [M_pad] block-space row -> index into y (-1 = padding row, not stored)
     int M_pad, K_pad, bh, bw, wdtype, layout, T, act, nchunks, nbr, chunk_tiles, wg_waves, row_slices;
     int lds_tiles;              // chunk_tiles if the plan carries the packed gather lists, else 0
+    int xrow_len;               // HostPlan::xrow_len()
     int uniform_ct, uniform_parts;  // > 0: regular schedule, the kernels compute the chunk descriptor
     int x_block_order;          // 1: x is [batch][K_pad] in block order (what the matrix-core kernel needs)
     int K;                      // row length of a natural-order x
@@ -120,12 +122,16 @@ struct FcLaunch {
 };
 
 // Batch rows one launch of the layer kernel covers (grid.y repeats it).
-enum { kPathVector = 0, kPathMfmaLds = 1, kPathMfmaGather = 2 };
-// `lds_tiles`: HostPlan::lds_tiles() (0 rules the LDS-fed matrix-core kernel out).
-int    fc_path(int layout, int wdtype, int bh, int bw, int lds_tiles, int batch);
-int    fc_batch_tile(int layout, int wdtype, int bh, int bw, int lds_tiles, int batch);
-bool   fc_uses_matrix_cores(int layout, int wdtype, int bh, int bw, int lds_tiles, int batch);   // the form that needs x in block order
-int    fc_row_slices(int layout, int wdtype, int bh, int bw, int lds_tiles, int batch, int want);
+enum { kPathVector = 0, kPathMfmaLds = 1, kPathMfmaGather = 2, kPathMfmaXrow = 3 };
+// What decides the path besides the batch.  `lds_tiles`: HostPlan::lds_tiles() (0 rules the LDS-fed matrix-core
+// kernel out); `chunk_tiles`, `xrow_len`: the plan's chunk size and HostPlan::xrow_len() (0 rules out the
+// matrix-core kernel that gathers its fragments from a copy of x in LDS).
+struct FcShape { int layout, wdtype, bh, bw, lds_tiles, chunk_tiles, xrow_len; };
+inline FcShape fc_shape(const HostPlan& h) { return FcShape{h.d.layout, h.d.wdtype, h.d.bh, h.d.bw, h.lds_tiles(), h.chunk_tiles, h.xrow_len()}; }
+int    fc_path(const FcShape& s, int batch);
+int    fc_batch_tile(const FcShape& s, int batch);
+bool   fc_uses_matrix_cores(const FcShape& s, int batch);   // the form that needs x in block order
+int    fc_row_slices(const FcShape& s, int batch, int want);
 // Workspace of one layer application: [arrival counters][partials of split rows][x in block order (matrix path)]
 size_t fc_ticket_bytes(const HostPlan& hp);                   // the same for every batch (0 without split block rows)
 size_t fc_partial_bytes(const HostPlan& hp, int batch);

@@ -28,6 +28,13 @@ static int device_cus() {
 // were slower again from 10 % kept on: the weights are then streamed four times).
 static int mfma_lds_rows(int batch) { return batch <= 4 ? 4 : 8; }
 
+// Fewest staged columns per work item (chunk size + 1 tiles) from which batch 9-16 takes the form that copies
+// all of x into LDS.
+#ifndef PIVOT_XROW_MIN_COLS
+#define PIVOT_XROW_MIN_COLS 0
+#endif
+constexpr int kXrowMinCols = PIVOT_XROW_MIN_COLS;
+
 // Which kernel applies the layer:
 //   kPathVector      batch 1-2 (and whatever the matrix cores cannot take): FMA / dot2 against x staged in LDS
 //   kPathMfmaLds     fp16, batch >= 3: MFMA with the B fragments read from x staged in LDS (4 or 8 batch rows per launch row)
@@ -42,9 +49,22 @@ static int mfma_lds_rows(int batch) { return batch <= 4 ? 4 : 8; }
 // 50 %, 14.2 -> 12.4 dense; batch 16: 7.3 -> 6.1 at 5 %, 11.0 -> 9.5 at 25 %).  Letting it take up to 136 KB of
 // LDS (one workgroup per compute unit) for 16 staged rows at 50 % and dense was measured too: 13.5 -> 13.2 us and
 // 14.5 -> 15.4 us, so longer rows stay with the block-order form.
-int fc_path(int layout, int wdtype, int bh, int bw, int lds_tiles, int batch) {
+//   kPathMfmaXrow    fp16, batch 9-16: MFMA with the B fragments gathered from a copy of the 16 rows of x in LDS
+// At batch 9-16 the staging itself bounds the LDS-fed form (16 rows x staged columns two-byte gathers per work
+// item, repeated by every row slice, and the weights streamed once per launch row of 8); gathering where the
+// fragment is formed needs one copy of x per work item instead, whatever the number of staged columns.
+int fc_path(const FcShape& s, int batch) {
+    const int layout = s.layout, wdtype = s.wdtype, bh = s.bh, bw = s.bw, lds_tiles = s.lds_tiles;
     // the matrix-core kernels read A fragments from row-major (BRC) tiles only
     if (layout != PIVOT_BRC || mfma_kind(wdtype, bh, bw) < 0 || batch < 3) return kPathVector;
+    if (batch > 8 && batch <= 16 && s.xrow_len > 0 && s.chunk_tiles > 0) {
+        // 16 rows of x (each with 16 zeroed bytes behind it) and the work item's gather indices in LDS; a lane
+        // copies at most 8 vectors of a row, a thread at most 4 int4 of indices
+        const size_t vecs = ((size_t)s.xrow_len + 7) / 8;
+        const size_t cols = ((size_t)s.chunk_tiles + 1) * bw;
+        const size_t lds = 16 * (vecs * 16 + 16) + cols * 4;
+        if (vecs <= 512 && cols <= 8192 && lds <= 156 * 1024 && cols >= (size_t)kXrowMinCols) return kPathMfmaXrow;
+    }
     if (lds_tiles > 0) {
         const int rows = mfma_lds_rows(batch);
         const size_t xs_bytes = (size_t)rows * ((size_t)lds_tiles * bw + 8 + 16) * 2;   // + the paired form's zeroed columns
@@ -59,16 +79,17 @@ int fc_path(int layout, int wdtype, int bh, int bw, int lds_tiles, int batch) {
     return batch >= 8 ? kPathMfmaGather : kPathVector;
 }
 
-bool fc_uses_matrix_cores(int layout, int wdtype, int bh, int bw, int lds_tiles, int batch) {
-    return fc_path(layout, wdtype, bh, bw, lds_tiles, batch) == kPathMfmaGather;
+bool fc_uses_matrix_cores(const FcShape& s, int batch) {
+    return fc_path(s, batch) == kPathMfmaGather;
 }
 
 // Batch rows one launch row covers in the kernel's epilogue and in the workspace (grid.y repeats it).
-int fc_batch_tile(int layout, int wdtype, int bh, int bw, int lds_tiles, int batch) {
-    if (layout != PIVOT_BRC) return 1;       // the column-major kernels take one batch row per launch row
-    const int path = fc_path(layout, wdtype, bh, bw, lds_tiles, batch);
-    if (path == kPathMfmaGather) return mfma_kind(wdtype, bh, bw) == 0 ? 16 : 32;
+int fc_batch_tile(const FcShape& s, int batch) {
+    if (s.layout != PIVOT_BRC) return 1;     // the column-major kernels take one batch row per launch row
+    const int path = fc_path(s, batch);
+    if (path == kPathMfmaGather) return mfma_kind(s.wdtype, s.bh, s.bw) == 0 ? 16 : 32;
     if (path == kPathMfmaLds) return mfma_lds_rows(batch);
+    if (path == kPathMfmaXrow) return 16;
     return batch >= 3 ? 4 : batch;
 }
 
@@ -76,18 +97,19 @@ int fc_batch_tile(int layout, int wdtype, int bh, int bw, int lds_tiles, int bat
 // slice of the vector kernel has at least 8 rows and is a whole number of 1 KB
 // wave-loads or a whole fraction of one (a wave-load then takes the same rows
 // of several consecutive tiles), a slice of the matrix kernel whole MFMA row blocks.
-int fc_row_slices(int layout, int wdtype, int bh, int bw, int lds_tiles, int batch, int want) {
+int fc_row_slices(const FcShape& s, int batch, int want) {
+    const int layout = s.layout, wdtype = s.wdtype, bh = s.bh, bw = s.bw;
     if (layout != PIVOT_BRC) return 1;       // a row slice is contiguous only in row-major tiles
     int sl = want < 1 ? 1 : want;
     while (sl > 1) {
         bool ok = (bh % sl == 0);
         const int bhs = bh / sl;
         if (ok) {
-            const int path = fc_path(layout, wdtype, bh, bw, lds_tiles, batch);
+            const int path = fc_path(s, batch);
             if (path != kPathVector) {
-                // whole MFMA row blocks: 16 rows (32 for tiles 16 columns wide, except in the LDS-fed kernel,
-                // which pairs such tiles)
-                const int mr = (mfma_kind(wdtype, bh, bw) == 0 || (path == kPathMfmaLds && bw == 16)) ? 16 : 32;
+                // whole MFMA row blocks: 16 rows (32 for tiles 16 columns wide, except in the kernels fed from
+                // LDS, which pair such tiles)
+                const int mr = (mfma_kind(wdtype, bh, bw) == 0 || (path != kPathMfmaGather && bw == 16)) ? 16 : 32;
                 ok = (bhs % mr == 0);
             } else {
                 const int vec = 16 / elem_size(wdtype);
@@ -110,7 +132,7 @@ size_t fc_ticket_bytes(const HostPlan& hp) {
     if (hp.max_parts <= 1) return 0;
     int ngy_max = 1;
     for (int batch = 1; batch <= 64; ++batch) {
-        const int nbt = fc_batch_tile(hp.d.layout, hp.d.wdtype, hp.d.bh, hp.d.bw, hp.lds_tiles(), batch);
+        const int nbt = fc_batch_tile(fc_shape(hp), batch);
         ngy_max = std::max(ngy_max, (batch + nbt - 1) / nbt);
     }
     // counters are sized for the plan's slice count (a launch may use fewer)
@@ -119,7 +141,7 @@ size_t fc_ticket_bytes(const HostPlan& hp) {
 
 size_t fc_partial_bytes(const HostPlan& hp, int batch) {
     if (hp.max_parts <= 1) return 0;
-    const int nbt = fc_batch_tile(hp.d.layout, hp.d.wdtype, hp.d.bh, hp.d.bw, hp.lds_tiles(), batch);
+    const int nbt = fc_batch_tile(fc_shape(hp), batch);
     const int ngy = (batch + nbt - 1) / nbt;
     return align_up((size_t)4 * hp.nchunks * hp.d.bh * nbt * ngy, 256);
 }
@@ -130,7 +152,7 @@ size_t fc_workspace_bytes(const HostPlan& hp, int batch) {
 }
 
 size_t fc_gather_bytes(const HostPlan& hp, int batch) {
-    if (!fc_uses_matrix_cores(hp.d.layout, hp.d.wdtype, hp.d.bh, hp.d.bw, hp.lds_tiles(), batch)) return 0;
+    if (!fc_uses_matrix_cores(fc_shape(hp), batch)) return 0;
     return align_up((size_t)batch * hp.K_pad * elem_size(hp.d.wdtype), 256);
 }
 
@@ -143,11 +165,12 @@ static std::string kernel_name(const char* fmt, A... args) {
 }
 
 int launch_fc(const FcLaunch& L, std::string* describe) {
-    const int path = fc_path(L.layout, L.wdtype, L.bh, L.bw, L.lds_tiles, L.batch);
-    const bool mc = path == kPathMfmaGather, ml = path == kPathMfmaLds;
-    const int nbt = fc_batch_tile(L.layout, L.wdtype, L.bh, L.bw, L.lds_tiles, L.batch);
+    const FcShape shape{L.layout, L.wdtype, L.bh, L.bw, L.lds_tiles, L.chunk_tiles, L.xrow_len};
+    const int path = fc_path(shape, L.batch);
+    const bool mc = path == kPathMfmaGather, ml = path == kPathMfmaLds, mx = path == kPathMfmaXrow;
+    const int nbt = fc_batch_tile(shape, L.batch);
     const int ngy = (L.batch + nbt - 1) / nbt;
-    const int sl = fc_row_slices(L.layout, L.wdtype, L.bh, L.bw, L.lds_tiles, L.batch, L.row_slices);
+    const int sl = fc_row_slices(shape, L.batch, L.row_slices);
     const int bhs = L.bh / sl;
     int nw = (L.wg_waves == 16 || L.wg_waves == 8) ? L.wg_waves : 4;
     if (ml && nw > 8) nw = 8;                // the LDS-fed matrix-core kernel comes with 4 or 8 wavefronts
@@ -179,6 +202,23 @@ int launch_fc(const FcLaunch& L, std::string* describe) {
         return launch_mfma_f16(a, mfma_kind(L.wdtype, L.bh, L.bw), bhs, L.bw, nw, grid, smem, st);
     }
     if (L.uniform_ct > 0xFFFF || L.uniform_parts > 0x7FFF) a.uniform_ct = a.uniform_parts = 0;   // packed into 16 bits each: fall back to loaded descriptors
+    if (mx) {
+        if (L.chunk_tiles > 0xFFFF || L.bh > 64) { set_error("shape outside the kernel's packed arguments"); return PIVOT_E_UNSUPPORTED; }
+        const int xlen = L.x_block_order ? L.K_pad : L.K;
+        int kind = mfma_kind(L.wdtype, L.bh, L.bw);
+        if (kind == 1 && L.bw == 16 && bhs % 32 != 0) kind = 2;
+        const int vecs = (xlen + 7) / 8;
+        // rows copied with 16-byte loads when they are whole aligned vectors, densely packed; else element by element
+        const bool vec_rows = xlen % 8 == 0 && L.ldx == xlen && (reinterpret_cast<uintptr_t>(L.x) & 15) == 0;
+        a.xn_vecs = vecs | (vec_rows ? (1 << 17) : 0); a.xn_stride = xlen; a.xs_stride = 0;
+        const size_t steps_cols = ((size_t)(a.uniform_ct > 0 ? a.uniform_ct : L.chunk_tiles) + 1) * L.bw;
+        size_t smem = (size_t)16 * (vecs * 16 + 16) + steps_cols * 4;
+        const size_t red_bytes = (size_t)8 * bhs * 16 * 4;
+        smem = align_up(smem > red_bytes ? smem : red_bytes, 16);
+        if (vecs > 512 || steps_cols > 8192 || smem > 158 * 1024) { set_error("internal: x does not fit the LDS copy (%zu bytes)", smem); return PIVOT_E_UNSUPPORTED; }
+        if (describe) { *describe = kernel_name("fc_mfma_xrow_kernel<%d, %d, %d>", kind, bhs, L.bw); return PIVOT_OK; }
+        return launch_mfma_xrow_f16(a, kind, bhs, L.bw, grid, smem, st);
+    }
     // staged x: nbt rows of (tiles per chunk)*bw elements, plus 16 bytes whose last element is the dump slot
     // (the vector kernel derives the same stride from its preloaded arguments)
     // the LDS-fed matrix-core kernel takes slices that are not whole 32-row blocks of 16-column tiles as pairs

@@ -125,6 +125,37 @@ def test_fp16_16_column_tiles_in_16_row_slices_pair_their_tiles(bh, sl, batch):
     G.check_fc(p, row_slices=sl)
 
 
+@pytest.mark.parametrize("batch", [9, 12, 16])
+@pytest.mark.parametrize("bh,bw,K", [(64, 16, 1024), (64, 16, 1000), (32, 32, 4096), (16, 64, 333), (64, 64, 2048)])
+def test_fp16_batch_9_to_16_gathers_fragments_from_a_copy_of_x(bh, bw, K, batch):
+    # batch 9..16: all 16 rows of x are copied into LDS and every lane gathers the eight values of its B fragment
+    # from there.  Rows that are whole aligned vectors are copied with 16-byte loads, anything else (K not a
+    # multiple of 8, a row stride above K, an x that starts off a 16-byte boundary) element by element; rows past
+    # the batch are never read from memory; whole and split block rows, every row-slice form, an empty block row
+    p = WL.gen_fc(3 * bh + 7, K, bh, bw, 0.3, seed=300 + batch + bh, wdtype=WL.F16, batch=batch, act=WL.ACT_RELU)
+    p.tile_mask[1, :] = 0
+    plan = G.dev_plan(p)
+    try:
+        assert "fc_mfma_xrow_kernel" in B.pivot_fc_kernel_name(plan, batch)
+        st = torch.cuda.current_stream().cuda_stream
+        ws = G.workspace(B.pivot_fc_workspace_bytes(plan, batch))
+        y_ref, D = G.oracle_of(p)
+        for ldx, off in ((K, 0), (K + 8, 0), (K + 3, 0), (K, 1)):
+            buf = torch.full((batch * ldx + 16,), float("nan"), dtype=torch.float16, device="cuda")
+            xv = buf[off:off + batch * ldx].view(batch, ldx)
+            xv[:, :K] = torch.from_numpy(p.x).cuda()
+            yd = torch.full((batch, p.M), float("nan"), dtype=torch.float32, device="cuda")
+            B.pivot_fc_run(plan, xv.data_ptr(), ldx, yd.data_ptr(), p.M, batch, ws.data_ptr(), ws.numel(), st)
+            torch.cuda.synchronize()
+            y = yd.cpu().numpy().astype(np.float64)
+            assert not np.isnan(y).any(), (ldx, off)
+            assert O.max_scaled_error(y, y_ref, D) <= G.TOL[p.wdtype], (ldx, off)
+    finally:
+        B.pivot_fc_plan_destroy(plan)
+    G.check_fc(p, chunk_tiles=5, wg_waves=8, row_slices=2)
+    G.check_fc(p, row_slices=4)
+
+
 @pytest.mark.parametrize("batch", [16, 33, 64])
 def test_fp16_long_rows_use_the_block_order_copy(batch):
     # work items too long for the LDS-fed form (8 batch rows of 4096 staged columns exceed its 48 KB; at batch 64
