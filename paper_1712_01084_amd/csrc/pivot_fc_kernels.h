@@ -1012,7 +1012,7 @@ __global__ void __launch_bounds__(512) fc_mfma_xrow_kernel(PIVOT_GEMV_PARAMS, Fc
     constexpr int RB = BH / MR;                         // row blocks per tile slice
     constexpr int KS = PAIR ? 1 : BW / MK;              // k steps per tile (pair)
     constexpr int LT = RB * KS;                         // 16-byte weight loads per lane per tile (pair)
-    constexpr int U  = (LT >= 8) ? 1 : 8 / LT;          // tiles (pairs) in flight per wave
+    constexpr int U  = (LT >= 8) ? 1 : 8 / LT;          // tiles (pairs) in flight per wave (16 KB: slower throughout)
     constexpr int N  = BH * NBS;
     constexpr int STEP = PAIR ? 2 * BW : BW;            // staged columns per MFMA step along the block row
     constexpr int XV = 8;                               // vectors of one row a lane copies (2 rows per wavefront)
@@ -1033,20 +1033,21 @@ __global__ void __launch_bounds__(512) fc_mfma_xrow_kernel(PIVOT_GEMV_PARAMS, Fc
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int b0 = blockIdx.y * NBS, slice = blockIdx.z;
 
-    // The copy of x, requested first (weights requested first were measured 0.6-0.9 us slower: loads return in
-    // order, and x would wait for them).  Wavefront w takes rows w and w + 8, lane l vectors l, l + 64, ... of each.
+    // The copy of x, requested first: loads return in order, so behind the weights it would wait for their trip
+    // to HBM (weights first: 0.6-0.9 us slower on 4096x4096 at every density; interleaved with them: 0.2-0.5 us
+    // slower; twice the weights in flight: 0.6-1.0 us slower).  Wavefront w takes rows w and w + 8, lane l
+    // vectors l, l + 64, ... of each.
     f16x8 xv_[2][XV];
+    auto xload = [&](int k) {                           // k-th of the thread's 2 * XV vectors
+        const int r = k / XV, j = k % XV;
+        const int b = wave + r * NW;
+        const f16x8* src = reinterpret_cast<const f16x8*>(p_x) + (long long)(b0 + b) * q_xn_vecs;
+        const int i = lane + j * 64;
+        if (i < q_xn_vecs && b0 + b < q_batch) xv_[r][j] = load16<f16x8>(reinterpret_cast<const WT*>(src + i));
+    };
     if (q_vec_rows) {
         #pragma unroll
-        for (int r = 0; r < 2; ++r) {
-            const int b = wave + r * NW;
-            const f16x8* src = reinterpret_cast<const f16x8*>(p_x) + (long long)(b0 + b) * q_xn_vecs;
-            #pragma unroll
-            for (int j = 0; j < XV; ++j) {
-                const int i = lane + j * 64;
-                if (i < q_xn_vecs && b0 + b < q_batch) xv_[r][j] = load16<f16x8>(reinterpret_cast<const WT*>(src + i));
-            }
-        }
+        for (int k = 0; k < 2 * XV; ++k) xload(k);
     }
     const Chunk ck = load_chunk(q_uniform_ct, q_uniform_parts, p_chunks, a.part_base);
     const int br = ck.br, tile_begin = ck.tile_begin, ntiles = ck.ntiles, slot = ck.slot;

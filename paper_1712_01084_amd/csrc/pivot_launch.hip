@@ -28,13 +28,6 @@ static int device_cus() {
 // were slower again from 10 % kept on: the weights are then streamed four times).
 static int mfma_lds_rows(int batch) { return batch <= 4 ? 4 : 8; }
 
-// Fewest staged columns per work item (chunk size + 1 tiles) from which batch 9-16 takes the form that copies
-// all of x into LDS.
-#ifndef PIVOT_XROW_MIN_COLS
-#define PIVOT_XROW_MIN_COLS 0
-#endif
-constexpr int kXrowMinCols = PIVOT_XROW_MIN_COLS;
-
 // Which kernel applies the layer:
 //   kPathVector      batch 1-2 (and whatever the matrix cores cannot take): FMA / dot2 against x staged in LDS
 //   kPathMfmaLds     fp16, batch >= 3: MFMA with the B fragments read from x staged in LDS (4 or 8 batch rows per launch row)
@@ -52,7 +45,11 @@ constexpr int kXrowMinCols = PIVOT_XROW_MIN_COLS;
 //   kPathMfmaXrow    fp16, batch 9-16: MFMA with the B fragments gathered from a copy of the 16 rows of x in LDS
 // At batch 9-16 the staging itself bounds the LDS-fed form (16 rows x staged columns two-byte gathers per work
 // item, repeated by every row slice, and the weights streamed once per launch row of 8); gathering where the
-// fragment is formed needs one copy of x per work item instead, whatever the number of staged columns.
+// fragment is formed needs one copy of x per work item instead, whatever the number of staged columns.  The copy
+// costs a work item 1.5-2.3 us (4096 columns: 128 KB through one compute unit's memory pipeline before its first
+// MFMA), the gathers 0.2-0.9 us, so the form is taken from a quarter of the columns staged per work item on
+// (4096x4096, 64x16 tiles, batch 16, cold: 8.3 -> 7.1 us at 25 % kept, 12.5 -> 9.1 at 50 %, 14.9 -> 12.7 dense;
+// at 10 % it would lose, 6.0 -> 6.3, at 5 % 4.8 -> 6.3).
 int fc_path(const FcShape& s, int batch) {
     const int layout = s.layout, wdtype = s.wdtype, bh = s.bh, bw = s.bw, lds_tiles = s.lds_tiles;
     // the matrix-core kernels read A fragments from row-major (BRC) tiles only
@@ -63,7 +60,7 @@ int fc_path(const FcShape& s, int batch) {
         const size_t vecs = ((size_t)s.xrow_len + 7) / 8;
         const size_t cols = ((size_t)s.chunk_tiles + 1) * bw;
         const size_t lds = 16 * (vecs * 16 + 16) + cols * 4;
-        if (vecs <= 512 && cols <= 8192 && lds <= 156 * 1024 && cols >= (size_t)kXrowMinCols) return kPathMfmaXrow;
+        if (vecs <= 512 && cols <= 8192 && lds <= 156 * 1024 && cols * 4 >= (size_t)s.xrow_len) return kPathMfmaXrow;
     }
     if (lds_tiles > 0) {
         const int rows = mfma_lds_rows(batch);

@@ -231,17 +231,18 @@ def test_chain_workspace_reused_across_batch_sizes(wdtype):
 
 
 def test_chain_padding_columns_of_a_directly_read_intermediate_are_cleared():
-    # second layer: 3100 inputs (3104 with padding) in whole block rows of 97 tiles, batch 16: too long to stage
-    # in LDS, so the matrix-core kernel reads its B fragments straight from the intermediate's rows, padding
-    # columns included; a first run on another batch size leaves NaN where those columns are
-    probs = WL.config4(seed=43, batch=16, dims=(64, 3100, 40), wdtype=WL.F16, bh=32, bw=32, frac=1.0)
+    # second layer: 3100 inputs (3104 with padding) in whole block rows of 97 tiles, batch 24: too long to stage
+    # in LDS (and past the 16 rows of the form that copies x there), so the matrix-core kernel reads its B fragments
+    # straight from the intermediate's rows, padding columns included; a first run on another batch size leaves
+    # NaN where those columns are
+    probs = WL.config4(seed=43, batch=24, dims=(64, 3100, 40), wdtype=WL.F16, bh=32, bw=32, frac=1.0)
     plans = [G.dev_plan(p, chunk_tiles=97) for p in probs]
     mlp = B.pivot_mlp_plan(plans, 0)
     try:
-        assert B.pivot_fc_workspace_bytes(plans[1], 16) > 0      # whole rows: all of it is the block-order copy
-        ws = G.workspace(max(B.pivot_mlp_workspace_bytes(mlp, b) for b in (64, 16)))
+        assert B.pivot_fc_workspace_bytes(plans[1], 24) > 0      # whole rows: all of it is the block-order copy
+        ws = G.workspace(max(B.pivot_mlp_workspace_bytes(mlp, b) for b in (64, 24)))
         st = torch.cuda.current_stream().cuda_stream
-        for b, poison in ((64, True), (16, False)):
+        for b, poison in ((64, True), (24, False)):
             x = np.full((b, 64), np.nan, dtype=np.float16) if poison else probs[0].x
             xd = torch.from_numpy(x).cuda()
             yd = torch.full((b, probs[-1].M), float("nan"), dtype=torch.float32, device="cuda")

@@ -48,10 +48,10 @@ def test_static_scratch_entry_point_two_calls_second_smaller():
 
 
 def test_static_scratch_entry_point_matrix_core_forms():
-    # fp16 at batch 16: staged in LDS (split rows), and with whole rows of 97 tiles read from a block-order copy
-    # of x that lives in the scratch; then a smaller batch of the first again
+    # fp16 at batch 16: staged in LDS (split rows); at batch 24 with whole rows of 97 tiles read from a block-order
+    # copy of x that lives in the scratch; then a smaller batch of the first again
     a = WL.gen_fc(200, 520, 64, 16, 0.5, seed=63, wdtype=WL.F16, batch=16)
-    b = WL.gen_fc(40, 3100, 32, 32, 1.0, seed=64, wdtype=WL.F16, batch=16, mask="full")
+    b = WL.gen_fc(40, 3100, 32, 32, 1.0, seed=64, wdtype=WL.F16, batch=24, mask="full")
     _both(a, a.x, chunk_tiles=4)
     _both(b, b.x, chunk_tiles=97)
     _both(a, a.x[:3], chunk_tiles=4)
