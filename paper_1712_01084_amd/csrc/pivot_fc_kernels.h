@@ -68,7 +68,11 @@ struct FcArgs {
 // access stays in bounds.  1: no x at all (no copy, no gather index, no staging; the FMAs read whatever the LDS
 // holds)  2: x copied into LDS but never staged (no barrier behind the copy, no gather)  4: no copy of x (barrier
 // and LDS-to-LDS gather kept, from an LDS region nobody filled)  8: outputs computed but not stored
-// 16: no reduction and no outputs (one value per workgroup is stored).  The product build has PIVOT_ABLATE 0.
+// 16: no reduction and no outputs (one value per workgroup is stored)  32: no permutations (batch 1, vector
+// kernel; for plans whose permutations are the identity and whose M and K are whole tiles, see
+// bench_paper_grid.py --gather-off): the launcher passes the tile list's block columns in place of the
+// per-column gather index, an x-segment is the BW contiguous elements at block column * BW, and an output row
+// is stored at its own index without a look-up.  The product build has PIVOT_ABLATE 0.
 #ifndef PIVOT_ABLATE
 #define PIVOT_ABLATE 0
 #endif
@@ -164,7 +168,7 @@ struct RowPre {
         for (int k = 0; k < CNT; ++k) {
             const int row = row0 + (tid + k * NT) % BH;
             bias[k] = bias_p[row];
-            dst[k] = scatter[row];
+            dst[k] = (PIVOT_ABLATE & 32) ? row : scatter[row];
         }
     }
 };
@@ -320,13 +324,17 @@ struct XStageWave {
         const int q = e / GE;
         return (wave + q * NW) * GE + (e - q * GE);
     }
+    // the source index of staged element p of the work item (ablation 32: `xidx` is the tile list's block columns)
+    static __device__ __forceinline__ int index_at(const int32_t* xidx, int tile_begin, int p) {
+        if constexpr ((PIVOT_ABLATE & 32) != 0) return xidx[tile_begin + p / BW] * BW + p % BW;
+        else return xidx[(size_t)tile_begin * BW + p];
+    }
     __device__ __forceinline__ void load_idx(const int32_t* xidx, int tile_begin, int ne, int wave, int lane) {
-        const int32_t* xi = xidx + (size_t)tile_begin * BW;
-        const int emax = ne > 0 ? ne - 1 : 0;       // index arrays carry 16 bytes of padding: xi[0] is readable
+        const int emax = ne > 0 ? ne - 1 : 0;       // index arrays carry 16 bytes of padding: entry 0 is readable
         #pragma unroll
         for (int k = 0; k < XP; ++k) {
             const int pos = pos_of(lane + k * 64, wave);
-            src[k] = xi[pos < emax ? pos : emax];
+            src[k] = index_at(xidx, tile_begin, pos < emax ? pos : emax);
         }
     }
     // `x`: the row of x, in global memory or (SRC_LDS) its copy in LDS
@@ -343,14 +351,13 @@ struct XStageWave {
             xs[pos < ne ? pos : dump] = (src[k] >= 0) ? v[k] : WT(0);
         }
         // longer work items: further rounds of XP elements per lane (the condition is the same in every lane)
-        const int32_t* xi = xidx + (size_t)tile_begin * BW;
         const int emax = ne > 0 ? ne - 1 : 0;
         for (int e0 = XP * 64; pos_of(e0, wave) < ne; e0 += XP * 64) {
             int s2[XP];
             #pragma unroll
             for (int k = 0; k < XP; ++k) {
                 const int pos = pos_of(e0 + lane + k * 64, wave);
-                s2[k] = xi[pos < emax ? pos : emax];
+                s2[k] = index_at(xidx, tile_begin, pos < emax ? pos : emax);
             }
             WT v2[XP];
             #pragma unroll

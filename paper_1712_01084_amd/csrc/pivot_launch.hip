@@ -282,6 +282,12 @@ int launch_fc(const FcLaunch& L, std::string* describe) {
         else *describe = kernel_name("fc_gemv_kernel<%s, %d, %d, %d, %d, %d>", wt, bhs, L.bw, nbt, nw, xres);
         return PIVOT_OK;
     }
+#if PIVOT_ABLATE & 32
+    // ablation build without permutations: batch 1 through the vector kernel only, which then reads the tile
+    // list's block columns where it otherwise reads the per-column gather index
+    if (L.layout != PIVOT_BRC || ml || nbt != 1) { set_error("this ablation build runs BRC plans at batch 1 only"); return PIVOT_E_UNSUPPORTED; }
+    a.xidx = L.col_idx;
+#endif
     if (L.layout != PIVOT_BRC) return launch_colmajor(a, L.layout, L.wdtype, L.bh, L.bw, nw, grid, smem, st);
     if (ml) {
         if (!L.xsort) { set_error("internal: the LDS-fed matrix-core kernel needs the packed gather lists"); return PIVOT_E_UNSUPPORTED; }
