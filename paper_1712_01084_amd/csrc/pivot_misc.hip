@@ -113,9 +113,12 @@ int launch_fill_zero(void* dev, size_t bytes, void* stream) {
 }
 
 // ---------------------------------------------------------------------------
-// dense comparator: y = act(W x + b), W streamed once, one wave per R rows.
+// dense comparator: y = act(W x + b), W streamed once, one wave per R rows,
+// UN steps of the row loop in flight.  At batch 1 two rows per wavefront and 8
+// steps (4096x9216 fp32 cold: 27.7 us = 5.5 TB/s; four rows and 2 steps, half
+// the wavefronts per compute unit, 32.7 us; one row and 8 steps 28.0 us).
 // ---------------------------------------------------------------------------
-template <typename WT, int NB, int R>
+template <typename WT, int NB, int R, int UN>
 __global__ void __launch_bounds__(256) dense_kernel(const WT* W, int M, int K, const WT* x, long long ldx,
                                                     const float* bias, float* y, long long ldy, int batch, int act) {
     using V = typename Elem<WT>::vec;
@@ -131,7 +134,7 @@ __global__ void __launch_bounds__(256) dense_kernel(const WT* W, int M, int K, c
     const WT* wrow[R];
     #pragma unroll
     for (int r = 0; r < R; ++r) wrow[r] = W + (size_t)((row0 + r < M) ? row0 + r : M - 1) * K;
-    #pragma unroll 2
+    #pragma unroll UN
     for (int k = lane * VEC; k < K; k += 64 * VEC) {
         V wv[R];
         #pragma unroll
@@ -153,12 +156,12 @@ __global__ void __launch_bounds__(256) dense_kernel(const WT* W, int M, int K, c
         }
 }
 
-template <typename WT, int NB, int R>
+template <typename WT, int NB, int R, int UN>
 static int launch_dense_t(const void* W, int M, int K, const void* x, int64_t ldx, const float* bias,
                           void* y, int64_t ldy, int batch, int act, hipStream_t st) {
     int rows_per_block = 4 * R;
     dim3 grid((M + rows_per_block - 1) / rows_per_block);
-    hipLaunchKernelGGL((dense_kernel<WT, NB, R>), grid, dim3(256), 0, st, (const WT*)W, M, K, (const WT*)x,
+    hipLaunchKernelGGL((dense_kernel<WT, NB, R, UN>), grid, dim3(256), 0, st, (const WT*)W, M, K, (const WT*)x,
                        (long long)ldx, bias, (float*)y, (long long)ldy, batch, act);
     HIP_TRY(hipGetLastError());
     return PIVOT_OK;
@@ -171,13 +174,13 @@ int launch_dense(const void* W, int wdtype, int M, int K, const void* x, int64_t
     if (K % vec != 0 || ldx % vec != 0) { set_error("dense comparator needs K and ldx to be multiples of %d", vec); return PIVOT_E_UNSUPPORTED; }
     if (batch < 1 || batch > 16) { set_error("dense comparator supports batch 1..16"); return PIVOT_E_UNSUPPORTED; }
     if (wdtype == PIVOT_F32) {
-        if (batch == 1) return launch_dense_t<float, 1, 4>(W, M, K, x, ldx, bias, y, ldy, batch, act, st);
-        if (batch <= 4) return launch_dense_t<float, 4, 2>(W, M, K, x, ldx, bias, y, ldy, batch, act, st);
-        return launch_dense_t<float, 16, 1>(W, M, K, x, ldx, bias, y, ldy, batch, act, st);
+        if (batch == 1) return launch_dense_t<float, 1, 2, 8>(W, M, K, x, ldx, bias, y, ldy, batch, act, st);
+        if (batch <= 4) return launch_dense_t<float, 4, 2, 2>(W, M, K, x, ldx, bias, y, ldy, batch, act, st);
+        return launch_dense_t<float, 16, 1, 2>(W, M, K, x, ldx, bias, y, ldy, batch, act, st);
     }
-    if (batch == 1) return launch_dense_t<_Float16, 1, 4>(W, M, K, x, ldx, bias, y, ldy, batch, act, st);
-    if (batch <= 4) return launch_dense_t<_Float16, 4, 2>(W, M, K, x, ldx, bias, y, ldy, batch, act, st);
-    return launch_dense_t<_Float16, 16, 1>(W, M, K, x, ldx, bias, y, ldy, batch, act, st);
+    if (batch == 1) return launch_dense_t<_Float16, 1, 2, 8>(W, M, K, x, ldx, bias, y, ldy, batch, act, st);
+    if (batch <= 4) return launch_dense_t<_Float16, 4, 2, 2>(W, M, K, x, ldx, bias, y, ldy, batch, act, st);
+    return launch_dense_t<_Float16, 16, 1, 2>(W, M, K, x, ldx, bias, y, ldy, batch, act, st);
 }
 
 // ---------------------------------------------------------------------------
