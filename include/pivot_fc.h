@@ -400,6 +400,27 @@ int  pivot_null_run(void* stream);
  * measured counterpart of the bandwidth roofline for layers of a few MB. */
 int  pivot_stream_read_run(const void* buf_dev, size_t bytes, float* out_dev, void* stream);
 
+/* Measurement aid for the one-launch forms, whose workgroups hand data to each
+ * other inside a launch (chains: Section 4.2; the recurrent loop): what ONE
+ * trip between two workgroups costs.  One launch of one workgroup per compute
+ * unit (at most 256); every workgroup publishes the number of the XCD it runs
+ * on, then workgroup 0 bounces a 4-byte word `rounds` times with a partner on
+ * its own XCD and with one on another XCD, timing each series with the
+ * device's 100 MHz clock:
+ *   out[1] same XCD, device-coherent store / load (what the kernels use)
+ *   out[2] same XCD, workgroup-scope atomics
+ *   out[3] other XCD, device-coherent store / load
+ *   out[6] same XCD, plain store, L1 invalidate + plain load (through the XCD's L2)
+ * each in clock ticks for the whole series (2 * rounds trips), or -1 if a wait
+ * gave up (every wait is bounded); out[0] = 1 when the probe ran, -1 if the
+ * workgroups were not all resident or no partner was found; out[4], out[5] =
+ * the partners.  scratch_dev: PIVOT_PROBE_SCRATCH_BYTES of device memory,
+ * 256-byte aligned; the call clears it (on `stream`) and leaves the results,
+ * eight int64, at its start.  rounds: 1..100000.  Asynchronous like the other
+ * run calls; PIVOT_E_* on bad arguments. */
+#define PIVOT_PROBE_SCRATCH_BYTES ((size_t)32768)
+int  pivot_exchange_probe_run(void* scratch_dev, size_t scratch_bytes, int rounds, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -33,7 +33,7 @@ EXPORTS = [
     "pivot_mlp_plan", "pivot_mlp_plan_host_view", "pivot_mlp_plan_destroy",
     "pivot_mlp_workspace_bytes", "pivot_mlp_run", "pivot_mlp_status", "pivot_mlp_status_word",
     "pivot_lstm_workspace_bytes", "pivot_lstm_run", "pivot_lstm_status", "pivot_lstm_status_word",
-    "pivot_dense_run", "pivot_csr_run", "pivot_null_run", "pivot_stream_read_run", "pivot_feedback_search",
+    "pivot_dense_run", "pivot_csr_run", "pivot_null_run", "pivot_stream_read_run", "pivot_exchange_probe_run", "pivot_feedback_search",
 ]
 
 
@@ -118,6 +118,7 @@ def lib():
     L.pivot_dense_run.argtypes = [vp, i32, i32, i32, vp, i64, vp, vp, i64, i32, i32, vp]
     L.pivot_null_run.argtypes = [vp]
     L.pivot_stream_read_run.argtypes = [vp, sz, vp, vp]
+    L.pivot_exchange_probe_run.argtypes = [vp, sz, C.c_int, vp]
     L.pivot_feedback_search.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp, C.POINTER(C.c_double)]
     L.pivot_csr_run.argtypes = [vp, vp, vp, i32, i32, i64, vp, vp, vp, i32, vp]
     _lib = L
@@ -294,6 +295,13 @@ def pivot_dense_run(W_ptr, wdtype, M, K, x_ptr, ldx, bias_ptr, y_ptr, ldy, batch
 
 def pivot_null_run(stream=None):
     _check(lib().pivot_null_run(stream))
+
+
+PIVOT_PROBE_SCRATCH_BYTES = 32768
+
+
+def pivot_exchange_probe_run(scratch_ptr, scratch_bytes, rounds, stream=None):
+    _check(lib().pivot_exchange_probe_run(scratch_ptr, scratch_bytes, rounds, stream))
 
 
 def pivot_stream_read_run(buf_ptr, nbytes, out_ptr, stream=None):

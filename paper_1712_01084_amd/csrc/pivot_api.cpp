@@ -648,6 +648,13 @@ int pivot_fc_kernel_name(const pivot_fc_plan_t* plan, int batch, char* buf, size
 
 int pivot_null_run(void* stream) { return launch_null(stream); }
 
+int pivot_exchange_probe_run(void* scratch_dev, size_t scratch_bytes, int rounds, void* stream) {
+    if (!scratch_dev) { set_error("scratch_dev is required"); return PIVOT_E_NULL; }
+    if (scratch_bytes < PIVOT_PROBE_SCRATCH_BYTES || (reinterpret_cast<uintptr_t>(scratch_dev) & 255) != 0) { set_error("the probe needs %zu bytes of scratch, 256-byte aligned", (size_t)PIVOT_PROBE_SCRATCH_BYTES); return PIVOT_E_WORKSPACE; }
+    if (rounds < 1 || rounds > 100000) { set_error("rounds %d outside 1..100000", rounds); return PIVOT_E_SHAPE; }
+    return launch_exchange_probe(scratch_dev, rounds, stream);
+}
+
 int pivot_stream_read_run(const void* buf_dev, size_t bytes, float* out_dev, void* stream) {
     if (!buf_dev || !out_dev) { set_error("buf_dev and out_dev are required"); return PIVOT_E_NULL; }
     if (bytes < 1024 || bytes > ((size_t)1 << 40) || (reinterpret_cast<uintptr_t>(buf_dev) & 15) != 0) { set_error("bytes must be >= 1024 and the buffer 16-byte aligned"); return PIVOT_E_SHAPE; }

@@ -146,6 +146,7 @@ int    launch_fill_zero(void* dev, size_t bytes, void* stream);
 int    launch_zero_pad_cols(void* buf, int K, int K_pad, int batch, int es, void* stream);
 int    launch_null(void* stream);
 int    launch_stream_read(const void* buf, size_t bytes, float* out, void* stream);
+int    launch_exchange_probe(void* scratch, int rounds, void* stream);
 int    launch_dense(const void* W, int wdtype, int M, int K, const void* x, int64_t ldx,
                     const float* bias, void* y, int64_t ldy, int batch, int act, void* stream);
 

@@ -101,6 +101,124 @@ int launch_stream_read(const void* buf, size_t bytes, float* out, void* stream) 
     return PIVOT_OK;
 }
 
+// ---------------------------------------------------------------------------
+// What one trip between two workgroups costs (see pivot_exchange_probe_run).
+// Scratch: [8 int64 results][pad to 1 KB][256 words: XCD + 1 of every workgroup][flag words, one per 256-byte line].
+// Every wait is bounded; a workgroup that gives up reports -1 and its partner runs into its own bound.
+// ---------------------------------------------------------------------------
+constexpr int kProbeMaxWg = 256;
+constexpr unsigned kProbeMaxSpin = 1u << 20;
+constexpr int kProbeTabOff = 1024, kProbeFlagOff = 4096;          // bytes
+
+template <int SCOPE>
+__device__ bool probe_bounce(unsigned* a2b, unsigned* b2a, bool is_a, int rounds) {
+    for (int i = 1; i <= rounds; ++i) {
+        const unsigned v = (unsigned)i;
+        unsigned spins = 0;
+        if (is_a) {
+            __hip_atomic_store(a2b, v, __ATOMIC_RELAXED, SCOPE);
+            while (__hip_atomic_load(b2a, __ATOMIC_RELAXED, SCOPE) != v) { if (++spins > kProbeMaxSpin) return false; }
+        } else {
+            while (__hip_atomic_load(a2b, __ATOMIC_RELAXED, SCOPE) != v) { if (++spins > kProbeMaxSpin) return false; }
+            __hip_atomic_store(b2a, v, __ATOMIC_RELAXED, SCOPE);
+        }
+    }
+    return true;
+}
+
+// plain stores (the L1 writes through to the XCD's L2), polls that invalidate the L1 first
+__device__ bool probe_bounce_l2(unsigned* a2b, unsigned* b2a, bool is_a, int rounds) {
+    volatile unsigned* va = a2b;
+    volatile unsigned* vb = b2a;
+    for (int i = 1; i <= rounds; ++i) {
+        const unsigned v = (unsigned)i;
+        unsigned spins = 0;
+        if (is_a) {
+            *va = v;
+            for (;;) { asm volatile("buffer_inv sc0" ::: "memory"); if (*vb == v) break; if (++spins > kProbeMaxSpin) return false; }
+        } else {
+            for (;;) { asm volatile("buffer_inv sc0" ::: "memory"); if (*va == v) break; if (++spins > kProbeMaxSpin) return false; }
+            *vb = v;
+        }
+    }
+    return true;
+}
+
+__global__ void __launch_bounds__(64) exchange_probe_kernel(char* scratch, int nwg, int rounds) {
+    extern __shared__ char one_per_cu[];                // sized so that a compute unit holds one workgroup
+    long long* out = reinterpret_cast<long long*>(scratch);
+    unsigned* tab = reinterpret_cast<unsigned*>(scratch + kProbeTabOff);
+    unsigned* f = reinterpret_cast<unsigned*>(scratch + kProbeFlagOff);
+    const int wg = blockIdx.x;
+    if (threadIdx.x != 0) return;
+    unsigned xcc = 0;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+    xcc &= 0xFu;
+    __hip_atomic_store(tab + wg, xcc + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // wait (bounded) until every workgroup has published, then pick the partners: the first workgroup on
+    // workgroup 0's XCD and the first on another one (every workgroup computes the same two)
+    bool all = false;
+    for (unsigned spin = 0; spin < 4096u && !all; ++spin) {
+        all = true;
+        for (int i = 0; i < nwg; ++i)
+            if (__hip_atomic_load(tab + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) { all = false; break; }
+    }
+    int pb = -1, pc = -1;
+    if (all) {
+        const unsigned x0 = __hip_atomic_load(tab + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int i = 1; i < nwg; ++i) {
+            const unsigned xi = __hip_atomic_load(tab + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (pb < 0 && xi == x0) pb = i;
+            if (pc < 0 && xi != x0) pc = i;
+        }
+    }
+    if (!all || pb < 0 || pc < 0) { if (wg == 0) out[0] = -1; return; }
+    if (wg != 0 && wg != pb && wg != pc) return;
+    const bool is_a = wg == 0;
+    if (wg == 0 || wg == pb) {
+        long long t0 = wall_clock64();
+        bool ok = probe_bounce<__HIP_MEMORY_SCOPE_AGENT>(f + 0, f + 64, is_a, rounds);
+        long long t1 = wall_clock64();
+        if (is_a) { out[1] = ok ? t1 - t0 : -1; out[4] = pb; }
+        t0 = wall_clock64();
+        ok = probe_bounce<__HIP_MEMORY_SCOPE_WORKGROUP>(f + 128, f + 192, is_a, rounds);
+        t1 = wall_clock64();
+        if (is_a) out[2] = ok ? t1 - t0 : -1;
+        t0 = wall_clock64();
+        ok = probe_bounce_l2(f + 256, f + 320, is_a, rounds);
+        t1 = wall_clock64();
+        if (is_a) out[6] = ok ? t1 - t0 : -1;
+    }
+    if (wg == 0 || wg == pc) {
+        const long long t0 = wall_clock64();
+        const bool ok = probe_bounce<__HIP_MEMORY_SCOPE_AGENT>(f + 384, f + 448, is_a, rounds);
+        const long long t1 = wall_clock64();
+        if (is_a) { out[3] = ok ? t1 - t0 : -1; out[5] = pc; }
+    }
+    if (is_a) out[0] = 1;
+}
+
+int launch_exchange_probe(void* scratch, int rounds, void* stream) {
+    int dev = 0, cus = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    const int nwg = cus < kProbeMaxWg ? cus : kProbeMaxWg;
+    if (nwg < 2) { set_error("the probe needs at least two compute units"); return PIVOT_E_UNSUPPORTED; }
+    // 96 KB of LDS per workgroup: no two on one compute unit, so all of them are resident at once
+    const size_t smem = 96 * 1024;
+    static bool allowed[16] = {};
+    if (!allowed[dev & 15]) {
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&exchange_probe_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+        allowed[dev & 15] = true;
+    }
+    int rc = launch_fill_zero(scratch, PIVOT_PROBE_SCRATCH_BYTES, stream);
+    if (rc != PIVOT_OK) return rc;
+    hipLaunchKernelGGL(exchange_probe_kernel, dim3(nwg), dim3(64), smem, reinterpret_cast<hipStream_t>(stream),
+                       reinterpret_cast<char*>(scratch), nwg, rounds);
+    HIP_TRY(hipGetLastError());
+    return PIVOT_OK;
+}
+
 int launch_fill_zero(void* dev, size_t bytes, void* stream) {
     if (bytes == 0) return PIVOT_OK;
     if (bytes % 4 != 0 || (reinterpret_cast<uintptr_t>(dev) % 4) != 0) { set_error("fill needs 4-byte alignment"); return PIVOT_E_SHAPE; }

@@ -42,3 +42,28 @@ def test_csr_comparator_matches_oracle(size, fill, wdtype):
     y_ref = O.fc_dense(Wd, p.x, p.bias, p.act)
     D = O.error_scale(Wd, p.x, p.bias)
     assert O.max_scaled_error(yd.cpu().numpy()[None, :], y_ref, D) <= G.TOL[wdtype]
+
+
+def test_exchange_probe_runs_and_reports_bounded_waits():
+    # the measurement aid for the one-launch forms: one trip between two workgroups, same XCD and other XCD.
+    # Every wait in it is bounded, so it returns whatever the memory system does: the device-coherent series must
+    # succeed (the one-launch kernels rely on exactly these accesses) with a trip of well under 20 us; the
+    # workgroup-scope series may give up (-1); bad arguments are refused on the host.
+    buf = torch.empty(B.PIVOT_PROBE_SCRATCH_BYTES + 256, dtype=torch.uint8, device="cuda")
+    off = (-buf.data_ptr()) % 256
+    st = torch.cuda.current_stream().cuda_stream
+    rounds = 200
+    B.pivot_exchange_probe_run(buf.data_ptr() + off, B.PIVOT_PROBE_SCRATCH_BYTES, rounds, st)
+    torch.cuda.synchronize()
+    out = buf[off:off + 64].cpu().numpy().view(np.int64)
+    assert out[0] == 1
+    assert out[4] > 0 and out[5] > 0 and out[4] != out[5]
+    for k in (1, 3):
+        us = out[k] / 100.0 / (2 * rounds)
+        assert 0.05 < us < 20.0, (k, us)
+    assert out[2] == -1 or out[2] > 0
+    assert out[6] == -1 or out[6] > 0
+    for kw in (dict(ptr=0), dict(nbytes=1024), dict(rounds=0), dict(ptr=buf.data_ptr() + off + 4)):
+        with pytest.raises(B.PivotError):
+            B.pivot_exchange_probe_run(kw.get("ptr", buf.data_ptr() + off), kw.get("nbytes", B.PIVOT_PROBE_SCRATCH_BYTES),
+                                       kw.get("rounds", rounds), st)
