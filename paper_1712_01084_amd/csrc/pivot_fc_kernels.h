@@ -157,7 +157,8 @@ __device__ __forceinline__ void store_out(void* y, long long idx, float v, int o
 // the bias and the destination index of every output this thread will finish
 // (outputs idx = tid + k*NT, idx = j*BH + r).  The loads are unconditional (the
 // row is always inside the padded block row), so no branch hides them from the
-// compiler's count of outstanding loads.
+// compiler's count of outstanding loads (loading only in the threads that finish
+// an output was measured: 4096x9216 fp32 0.06 us slower cold, others +-0.05).
 template <int BH, int N, int NT>
 struct RowPre {
     static constexpr int CNT = (N + NT - 1) / NT;
@@ -316,57 +317,92 @@ struct XStage<WT, BW, 1, NT, XP, false> {
 // at staged position (wave + (e / GE) * NW) * GE + e % GE, the place the whole-workgroup form gives it.
 // Lane l takes elements l, l + 64, ...; the first XP indices per lane are fetched before the weight stream.
 // Loads and LDS writes are unconditional: positions past the end read a clamped index and land in the dump slot.
-template <typename WT, int BW, int NW, int TPL, int XP>
+template <typename WT, int BW, int NW, int TPL, int XP, bool VEC4 = false>
 struct XStageWave {
     static constexpr int GE = TPL * BW;
+    static constexpr bool kVec = VEC4 && !(PIVOT_ABLATE & 32) && XP % 4 == 0;
     int src[XP];
     static __device__ __forceinline__ int pos_of(int e, int wave) {
         const int q = e / GE;
         return (wave + q * NW) * GE + (e - q * GE);
+    }
+    // Which of the wavefront's elements lane l takes in slot k of a round.  Vector form (VEC4): four consecutive
+    // ones per group of four slots, so that their indices are one 16-byte load and their staged values one LDS
+    // store (a 4-byte load per lane occupies the memory pipeline as long as a 16-byte one; the layer kernel gains
+    // 0.03-0.15 us warm on every workload, 4096x9216 fp32 3.45 -> 3.34 us, and 0.02-0.05 us cold; the chain
+    // kernel lost 0.1-0.2 us cold with it and keeps the scalar form); else l, l + 64, ...
+    static __device__ __forceinline__ int elem_of(int lane, int k) {
+        return kVec ? ((k >> 2) * 64 + lane) * 4 + (k & 3) : lane + k * 64;
     }
     // the source index of staged element p of the work item (ablation 32: `xidx` is the tile list's block columns)
     static __device__ __forceinline__ int index_at(const int32_t* xidx, int tile_begin, int p) {
         if constexpr ((PIVOT_ABLATE & 32) != 0) return xidx[tile_begin + p / BW] * BW + p % BW;
         else return xidx[(size_t)tile_begin * BW + p];
     }
-    __device__ __forceinline__ void load_idx(const int32_t* xidx, int tile_begin, int ne, int wave, int lane) {
-        const int emax = ne > 0 ? ne - 1 : 0;       // index arrays carry 16 bytes of padding: entry 0 is readable
-        #pragma unroll
-        for (int k = 0; k < XP; ++k) {
-            const int pos = pos_of(lane + k * 64, wave);
-            src[k] = index_at(xidx, tile_begin, pos < emax ? pos : emax);
+    // the indices of one round into s[]: clamped, unconditional loads (positions past the end read the last
+    // entries; index arrays carry 16 bytes of padding, so entries 0..3 are readable even for an empty item)
+    static __device__ __forceinline__ void round_idx(const int32_t* xidx, int tile_begin, int ne, int wave, int lane,
+                                                     int e0, int (&s)[XP]) {
+        if constexpr (kVec) {
+            const int32_t* xi = xidx + (size_t)tile_begin * BW;
+            const int last = ne >= 4 ? ne - 4 : 0;
+            #pragma unroll
+            for (int q = 0; q < XP / 4; ++q) {
+                const int pos = pos_of(e0 + elem_of(lane, 4 * q), wave);       // a multiple of 4: GE is one
+                const int4 v = *reinterpret_cast<const int4*>(xi + (pos < last ? pos : last));
+                s[4 * q] = v.x; s[4 * q + 1] = v.y; s[4 * q + 2] = v.z; s[4 * q + 3] = v.w;
+            }
+        } else {
+            const int emax = ne > 0 ? ne - 1 : 0;
+            #pragma unroll
+            for (int k = 0; k < XP; ++k) {
+                const int pos = pos_of(e0 + elem_of(lane, k), wave);
+                s[k] = index_at(xidx, tile_begin, pos < emax ? pos : emax);
+            }
         }
+    }
+    // the values of one round into LDS (padding columns as zero; positions past the end into the dump slots, the
+    // last four elements of the 16 bytes behind the staged row)
+    static __device__ __forceinline__ void round_store(WT* xs, int xs_stride, int ne, int wave, int lane, int e0,
+                                                       const int (&s)[XP], const WT (&v)[XP]) {
+        if constexpr (kVec) {
+            typedef WT vec4 __attribute__((ext_vector_type(4)));
+            #pragma unroll
+            for (int q = 0; q < XP / 4; ++q) {
+                const int pos = pos_of(e0 + elem_of(lane, 4 * q), wave);
+                vec4 o;
+                #pragma unroll
+                for (int c = 0; c < 4; ++c) o[c] = (s[4 * q + c] >= 0) ? v[4 * q + c] : WT(0);
+                *reinterpret_cast<vec4*>(xs + (pos < ne ? pos : xs_stride - 4)) = o;
+            }
+        } else {
+            const int dump = xs_stride - 1;
+            #pragma unroll
+            for (int k = 0; k < XP; ++k) {
+                const int pos = pos_of(e0 + elem_of(lane, k), wave);
+                xs[pos < ne ? pos : dump] = (s[k] >= 0) ? v[k] : WT(0);
+            }
+        }
+    }
+    __device__ __forceinline__ void load_idx(const int32_t* xidx, int tile_begin, int ne, int wave, int lane) {
+        round_idx(xidx, tile_begin, ne, wave, lane, 0, src);
     }
     // `x`: the row of x, in global memory or (SRC_LDS) its copy in LDS
     template <bool SRC_LDS>
     __device__ __forceinline__ void gather(const int32_t* xidx, const WT* x, WT* xs, int xs_stride,
                                            int tile_begin, int ne, int wave, int lane) {
-        const int dump = xs_stride - 1;
         WT v[XP];
         #pragma unroll
         for (int k = 0; k < XP; ++k) v[k] = x[src[k] > 0 ? src[k] : 0];
-        #pragma unroll
-        for (int k = 0; k < XP; ++k) {
-            const int pos = pos_of(lane + k * 64, wave);
-            xs[pos < ne ? pos : dump] = (src[k] >= 0) ? v[k] : WT(0);
-        }
+        round_store(xs, xs_stride, ne, wave, lane, 0, src, v);
         // longer work items: further rounds of XP elements per lane (the condition is the same in every lane)
-        const int emax = ne > 0 ? ne - 1 : 0;
         for (int e0 = XP * 64; pos_of(e0, wave) < ne; e0 += XP * 64) {
             int s2[XP];
-            #pragma unroll
-            for (int k = 0; k < XP; ++k) {
-                const int pos = pos_of(e0 + lane + k * 64, wave);
-                s2[k] = index_at(xidx, tile_begin, pos < emax ? pos : emax);
-            }
+            round_idx(xidx, tile_begin, ne, wave, lane, e0, s2);
             WT v2[XP];
             #pragma unroll
             for (int k = 0; k < XP; ++k) v2[k] = x[s2[k] > 0 ? s2[k] : 0];
-            #pragma unroll
-            for (int k = 0; k < XP; ++k) {
-                const int pos = pos_of(e0 + lane + k * 64, wave);
-                xs[pos < ne ? pos : dump] = (s2[k] >= 0) ? v2[k] : WT(0);
-            }
+            round_store(xs, xs_stride, ne, wave, lane, e0, s2, v2);
         }
     }
 };
@@ -552,7 +588,7 @@ __global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(PIVOT_GEMV_PARAMS, FcA
     if constexpr (XR == 1 && kLoadX) xres.load(q_batch, q_ldx, q_xn_vecs, p_x, b0, tid);
     constexpr int XPF = (XR == 3) ? 8 : 4;              // long inputs come with long work items: 8 indices up front
     XStage<WT, BW, NB, NT, XPF> xst;                    // several batch rows: staged by the whole workgroup
-    XStageWave<WT, BW, NW, TPL, XPF> xsw;               // one batch row: every wavefront stages for itself
+    XStageWave<WT, BW, NW, TPL, XPF, true> xsw;         // one batch row: every wavefront stages for itself
     if constexpr (!kStageX) { /* ablation: no gather index */ }
     else if constexpr (NB == 1) xsw.load_idx(p_idx, tile_begin, ntiles * BW, wave, lane);
     else                        xst.load_idx(p_idx, tile_begin, ntiles * BW, tid);
