@@ -113,10 +113,17 @@ __device__ __forceinline__ void pin_layer(const ChainLayer& p) {
 //   kInCopy   the caller's x, first copied whole into LDS with coalesced 16-byte loads (up to 16 per thread) and
 //             gathered from there: for a long x the element gather moves a whole cache line per element
 //   kInTagged (value, tag) pairs of the previous layer, re-read until they carry this launch's tag
+//             SHORT (a property of the whole chain, chosen by the launcher): no wavefront of any later layer
+//             stages more than 64 elements, and a lane fetches ONE gather index and polls one pair per round
+//             instead of four, three of which would be clamped and thrown away: a 4-byte load per lane occupies
+//             the memory pipeline for as long as a 16-byte one, and at a boundary the issue of the item's first
+//             loads is on the critical path (25088-4096-4096-1000: 15.6 -> 15.1-15.4 us cold, 13.05 -> 12.7
+//             warm).  A template argument of the kernel, not one more case per layer: with four more
+//             instantiations of the item inside one kernel the compiler copied the argument block to scratch.
 // The first layer (usually the long one) fetches eight gather indices per thread up front, so that up to 4096
 // staged elements need one round of dependent loads.
 enum { kInPlain = 0, kInTagged = 1, kInCopy = 2 };
-template <typename WT, int BH, int BW, int NW, int XIN>
+template <typename WT, int BH, int BW, int NW, int XIN, bool SHORT>
 __device__ __forceinline__ void chain_item(const ChainLayer& P, int item, bool out_tagged,
                                            uint32_t tag, uint32_t counter, uint32_t* s_tag, uint32_t* ctl, char* smem,
                                            long long* trace, const ChainLayer& next, int red_slot) {
@@ -129,7 +136,7 @@ __device__ __forceinline__ void chain_item(const ChainLayer& P, int item, bool o
     constexpr int TPL = (BH >= RPW) ? 1 : RPW / BH;
     constexpr int U   = (NL >= 8) ? 1 : 8 / NL;
     constexpr bool IN_TAGGED = (XIN == kInTagged);
-    constexpr int XP  = IN_TAGGED ? 4 : 8;
+    constexpr int XP  = IN_TAGGED ? (SHORT ? 1 : 4) : 8;
     static_assert(BH <= NT, "one thread per output row");
 
     // LDS: [partial sums, two slots][copy of x + a dump vector (kInCopy)][staged x-segments]
@@ -330,7 +337,7 @@ __device__ __forceinline__ void chain_item(const ChainLayer& P, int item, bool o
 // wave (14 dwords), so the first loads of the launch do not wait for a fetch of the argument block.
 // q0_ct_parts = uniform_ct | uniform_parts << 16; q0_shape = slices | bhs << 8 | bh_full << 16;
 // q0_chunk_tiles = chunk_tiles | xn_vecs << 16 (xn_vecs > 0: copy x into LDS first).
-template <typename WT, int BW>
+template <typename WT, int BW, bool SHORT>
 __global__ void __launch_bounds__(kChainNW * 64) mlp_persist_kernel(
         const int32_t* __restrict__ p0_xidx, const void* __restrict__ p0_vals, const void* __restrict__ p0_in,
         const float* __restrict__ p0_bias, const int32_t* __restrict__ p0_dst,
@@ -360,24 +367,24 @@ __global__ void __launch_bounds__(kChainNW * 64) mlp_persist_kernel(
         long long* tr = A.trace ? A.trace + (size_t)l * kChainMaxGrid * kChainNW * 8 : nullptr;
         if (in_tagged) {
             switch (P.bhs) {
-                case 8:  chain_item<WT, 8,  BW, kChainNW, kInTagged>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next, red_slot); break;
-                case 16: chain_item<WT, 16, BW, kChainNW, kInTagged>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next, red_slot); break;
-                case 32: chain_item<WT, 32, BW, kChainNW, kInTagged>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next, red_slot); break;
-                default: chain_item<WT, 64, BW, kChainNW, kInTagged>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next, red_slot); break;
+                case 8:  chain_item<WT, 8, BW, kChainNW, kInTagged, SHORT>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next, red_slot); break;
+                case 16: chain_item<WT, 16, BW, kChainNW, kInTagged, SHORT>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next, red_slot); break;
+                case 32: chain_item<WT, 32, BW, kChainNW, kInTagged, SHORT>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next, red_slot); break;
+                default: chain_item<WT, 64, BW, kChainNW, kInTagged, SHORT>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next, red_slot); break;
             }
         } else if (P.xn_vecs > 0) {
             switch (P.bhs) {
-                case 8:  chain_item<WT, 8,  BW, kChainNW, kInCopy>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next, red_slot); break;
-                case 16: chain_item<WT, 16, BW, kChainNW, kInCopy>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next, red_slot); break;
-                case 32: chain_item<WT, 32, BW, kChainNW, kInCopy>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next, red_slot); break;
-                default: chain_item<WT, 64, BW, kChainNW, kInCopy>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next, red_slot); break;
+                case 8:  chain_item<WT, 8, BW, kChainNW, kInCopy, SHORT>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next, red_slot); break;
+                case 16: chain_item<WT, 16, BW, kChainNW, kInCopy, SHORT>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next, red_slot); break;
+                case 32: chain_item<WT, 32, BW, kChainNW, kInCopy, SHORT>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next, red_slot); break;
+                default: chain_item<WT, 64, BW, kChainNW, kInCopy, SHORT>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next, red_slot); break;
             }
         } else {
             switch (P.bhs) {
-                case 8:  chain_item<WT, 8,  BW, kChainNW, kInPlain>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next, red_slot); break;
-                case 16: chain_item<WT, 16, BW, kChainNW, kInPlain>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next, red_slot); break;
-                case 32: chain_item<WT, 32, BW, kChainNW, kInPlain>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next, red_slot); break;
-                default: chain_item<WT, 64, BW, kChainNW, kInPlain>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next, red_slot); break;
+                case 8:  chain_item<WT, 8, BW, kChainNW, kInPlain, SHORT>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next, red_slot); break;
+                case 16: chain_item<WT, 16, BW, kChainNW, kInPlain, SHORT>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next, red_slot); break;
+                case 32: chain_item<WT, 32, BW, kChainNW, kInPlain, SHORT>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next, red_slot); break;
+                default: chain_item<WT, 64, BW, kChainNW, kInPlain, SHORT>(P, wg, out_tagged, tag, counter, st, A.ctl, smem, tr, next, red_slot); break;
             }
         }
         red_slot ^= 1;
@@ -404,27 +411,48 @@ __global__ void __launch_bounds__(kChainNW * 64) mlp_persist_kernel(
     }
 }
 
-const void* chain_kernel_for(int wdtype, int bw) {
+template <bool SHORT>
+static const void* chain_kernel_of(int wdtype, int bw) {
     if (wdtype == PIVOT_F32) {
         switch (bw) {
-            case 16: return reinterpret_cast<const void*>(&mlp_persist_kernel<float, 16>);
-            case 32: return reinterpret_cast<const void*>(&mlp_persist_kernel<float, 32>);
-            case 64: return reinterpret_cast<const void*>(&mlp_persist_kernel<float, 64>);
+            case 16: return reinterpret_cast<const void*>(&mlp_persist_kernel<float, 16, SHORT>);
+            case 32: return reinterpret_cast<const void*>(&mlp_persist_kernel<float, 32, SHORT>);
+            case 64: return reinterpret_cast<const void*>(&mlp_persist_kernel<float, 64, SHORT>);
             default: return nullptr;
         }
     }
     switch (bw) {
-        case 16: return reinterpret_cast<const void*>(&mlp_persist_kernel<_Float16, 16>);
-        case 32: return reinterpret_cast<const void*>(&mlp_persist_kernel<_Float16, 32>);
-        case 64: return reinterpret_cast<const void*>(&mlp_persist_kernel<_Float16, 64>);
+        case 16: return reinterpret_cast<const void*>(&mlp_persist_kernel<_Float16, 16, SHORT>);
+        case 32: return reinterpret_cast<const void*>(&mlp_persist_kernel<_Float16, 32, SHORT>);
+        case 64: return reinterpret_cast<const void*>(&mlp_persist_kernel<_Float16, 64, SHORT>);
         default: return nullptr;
     }
+}
+
+const void* chain_kernel_for(int wdtype, int bw, bool short_items) {
+    return short_items ? chain_kernel_of<true>(wdtype, bw) : chain_kernel_of<false>(wdtype, bw);
 }
 
 // Row slices of a layer inside the chain kernel: the plan's own choice, lowered until a slice holds at least
 // one 1 KB wave-load and 8 rows (the same rule as the layer kernel's).
 int chain_slices(const HostPlan& hp) {
     return fc_row_slices(FcShape{hp.d.layout, hp.d.wdtype, hp.d.bh, hp.d.bw, hp.chunk_tiles, hp.chunk_tiles, 0}, 1, hp.row_slices);
+}
+
+// True if no wavefront of an item of this layer stages more than 64 elements: its groups (wave, wave + 8, ...)
+// of TPL tiles of bw columns.
+static bool chain_layer_short(const HostPlan& hp) {
+    const int vec = 16 / elem_size(hp.d.wdtype), lpr = hp.d.bw / vec, rpw = 64 / (lpr > 0 ? lpr : 1);
+    const int bhs = hp.d.bh / chain_slices(hp);
+    const int tpl = bhs >= rpw ? 1 : rpw / bhs;
+    const int ct = hp.uniform_ct > 0 ? hp.uniform_ct : hp.chunk_tiles;
+    const int ngroups = (ct + tpl - 1) / tpl;
+    return ((ngroups + kChainNW - 1) / kChainNW) * tpl * hp.d.bw <= 64;
+}
+// The kernel form for a chain: SHORT when every layer behind the first is.
+static bool chain_short(const std::vector<const HostPlan*>& layers) {
+    for (size_t l = 1; l < layers.size(); ++l) if (!chain_layer_short(*layers[l])) return false;
+    return true;
 }
 
 }  // namespace
@@ -438,7 +466,7 @@ bool chain_persist_supported(const std::vector<const HostPlan*>& layers, int dev
     if (Lc < 2 || Lc > kMaxChainLayers) return no("2..8 layers");
     const int bw = layers[0]->d.bw, wdtype = layers[0]->d.wdtype;
     const int es = elem_size(wdtype), vec = 16 / es;
-    if (!chain_kernel_for(wdtype, bw)) return no("tile width 16, 32 or 64");
+    if (!chain_kernel_for(wdtype, bw, false)) return no("tile width 16, 32 or 64");
     int G = 0;
     size_t smem = 0;
     for (const HostPlan* hp : layers) {
@@ -471,7 +499,7 @@ bool chain_persist_supported(const std::vector<const HostPlan*>& layers, int dev
     }
     if (device >= 0) {
         int per_cu = 0, cus = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, chain_kernel_for(wdtype, bw), kChainNW * 64, smem) != hipSuccess ||
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, chain_kernel_for(wdtype, bw, chain_short(layers)), kChainNW * 64, smem) != hipSuccess ||
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess) {
             (void)hipGetLastError();
             return no("occupancy query failed");
@@ -499,6 +527,7 @@ int launch_chain_persist(const ChainPersistLaunch& C) {
     // timeline builds: [layer][1024 workgroups][8 wavefronts][8] int64 time stamps
     if (const char* e = getenv("PIVOT_CHAIN_TRACE_PTR")) A.trace = reinterpret_cast<long long*>(strtoull(e, nullptr, 0));
 #endif
+    bool short_items = true;
     for (int l = 0; l < Lc; ++l) {
         const ChainPersistLayer& s = C.layers[l];
         const HostPlan& hp = *s.hp;
@@ -511,18 +540,19 @@ int launch_chain_persist(const ChainPersistLaunch& C) {
         P.uniform_ct = hp.uniform_ct; P.uniform_parts = hp.uniform_parts;
         P.chunk_tiles = hp.uniform_ct > 0 ? hp.uniform_ct : hp.chunk_tiles;
         P.act = hp.d.act; P.k_valid = hp.d.K; P.xn_vecs = 0;
+        if (l > 0 && !chain_layer_short(hp)) short_items = false;
     }
     size_t smem = C.smem;
     if (C.smem_copy > 0 && (reinterpret_cast<uintptr_t>(A.L[0].in) & 15) == 0) {
         A.L[0].xn_vecs = C.layers[0].hp->d.K / (16 / elem_size(C.wdtype));
         smem = C.smem_copy;
         if (smem > 64 * 1024) {                         // more than 64 KB of dynamic LDS has to be allowed per kernel and device
-            static size_t allowed[16][6] = {};
+            static size_t allowed[16][12] = {};
             int dev = 0;
             HIP_TRY(hipGetDevice(&dev));
-            size_t& a = allowed[dev & 15][(C.wdtype == PIVOT_F32 ? 0 : 3) + (C.bw == 16 ? 0 : (C.bw == 32 ? 1 : 2))];
+            size_t& a = allowed[dev & 15][(short_items ? 6 : 0) + (C.wdtype == PIVOT_F32 ? 0 : 3) + (C.bw == 16 ? 0 : (C.bw == 32 ? 1 : 2))];
             if (smem > a) {
-                HIP_TRY(hipFuncSetAttribute(chain_kernel_for(C.wdtype, C.bw), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+                HIP_TRY(hipFuncSetAttribute(chain_kernel_for(C.wdtype, C.bw, short_items), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
                 a = smem;
             }
         }
@@ -535,7 +565,7 @@ int launch_chain_persist(const ChainPersistLaunch& C) {
     int q0_ct_parts = F.uniform_ct | (F.uniform_parts << 16), q0_shape = F.slices | (F.bhs << 8) | (F.bh_full << 16);
     int q0_chunk_tiles = F.chunk_tiles | (F.xn_vecs << 16), q0_nitems = F.nitems;
     void* args[] = {&p0_xidx, &p0_vals, &p0_in, &p0_bias, &p0_dst, &q0_ct_parts, &q0_shape, &q0_chunk_tiles, &q0_nitems, &A};
-    HIP_TRY(hipLaunchKernel(chain_kernel_for(C.wdtype, C.bw), dim3(C.grid), dim3(kChainNW * 64), args, smem, st));
+    HIP_TRY(hipLaunchKernel(chain_kernel_for(C.wdtype, C.bw, short_items), dim3(C.grid), dim3(kChainNW * 64), args, smem, st));
     return PIVOT_OK;
 }
 

@@ -29,3 +29,22 @@ def test_plan_builder_and_search_under_asan_ubsan(tmp_path):
     r = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, env=env, timeout=300)
     assert r.returncode == 0, r.stdout[-4000:]
     assert "all checks passed" in r.stdout
+
+
+def test_one_launch_kernels_use_no_scratch(tmp_path):
+    # The one-launch kernels index their argument block at run time; when the compiler cannot keep that block in
+    # the argument segment it copies it to per-lane scratch memory, which once made the chain kernel 2.5 times
+    # slower without changing a result.  hipcc cross-compiles without a GPU and reports the scratch of every kernel.
+    hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+    if not os.path.exists(hipcc):
+        pytest.skip("hipcc not available")
+    import re
+    from paper_1712_01084_amd import build as Bd
+    for src in ("pivot_mlp_persist.hip", "pivot_lstm_persist.hip", "pivot_mfma_xrow_f16.hip"):
+        cmd = [hipcc] + Bd.COMMON + Bd.DEVICE + ["-Rpass-analysis=kernel-resource-usage", "-c", os.path.join(CSRC, src),
+                                                 "-o", str(tmp_path / (src + ".o"))]
+        r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        assert r.returncode == 0, r.stdout[-2000:]
+        scratch = [int(m) for m in re.findall(r"ScratchSize \[bytes/lane\]: (\d+)", r.stdout)]
+        assert scratch, "no resource report for " + src
+        assert max(scratch) == 0, "%s: a kernel uses %d bytes of scratch per lane" % (src, max(scratch))
