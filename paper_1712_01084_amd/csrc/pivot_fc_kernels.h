@@ -603,7 +603,9 @@ __global__ void __launch_bounds__(NW * 64) fc_gemv_kernel(PIVOT_GEMV_PARAMS, FcA
 
     // Loads are unconditional (group index clamped; the value array is padded by
     // one group of zeros, so even an empty chunk reads valid memory): no branch
-    // sits between the loads and the compiler can wait for exactly the ones it needs.
+    // sits between the loads and the compiler can wait for exactly the ones it needs (skipping the duplicates
+    // of the last group with a wave-uniform branch was measured: 4096x9216 fp32 5.3 -> 5.8 us cold, 4096x4096
+    // fp16 at 25-100 % kept 0.6-0.9 us slower; only the chain kernel's short later layers gain from it).
     const int gmax = ngroups > 0 ? ngroups - 1 : 0;
     V w[U][NL];
     auto issue = [&](int g0, int u0, int u1) {
