@@ -17,6 +17,7 @@ PIVOT_BRC, PIVOT_BCR, PIVOT_CBR = 0, 1, 2
 PIVOT_PLAN_GATHER_FROM_GLOBAL = 1
 PIVOT_PLAN_LSTM_LAUNCH_PER_STEP = 2
 PIVOT_PLAN_GATHER_FROM_LDS_COPY = 4
+PIVOT_PLAN_LSTM_ONE_LAUNCH_ALWAYS = 8
 PIVOT_ACT_NONE, PIVOT_ACT_RELU = 0, 1
 PIVOT_W_NATURAL, PIVOT_W_PIVOTED = 0, 1
 PIVOT_MLP_KEEP_FINAL_BLOCK_ORDER = 1

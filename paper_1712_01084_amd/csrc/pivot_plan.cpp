@@ -218,7 +218,7 @@ int build_host_plan(const pivot_fc_desc& d, const void* W, int w_space, const ui
     if (d.act != PIVOT_ACT_NONE && d.act != PIVOT_ACT_RELU) { set_error("unknown activation %d", d.act); return PIVOT_E_UNSUPPORTED; }
     if (w_space != PIVOT_W_NATURAL && w_space != PIVOT_W_PIVOTED) { set_error("unknown weight space %d", w_space); return PIVOT_E_UNSUPPORTED; }
     if (d.chunk_tiles < 0) { set_error("chunk_tiles must be >= 0"); return PIVOT_E_SHAPE; }
-    if (d.flags & ~(PIVOT_PLAN_GATHER_FROM_GLOBAL | PIVOT_PLAN_LSTM_LAUNCH_PER_STEP | PIVOT_PLAN_GATHER_FROM_LDS_COPY)) { set_error("unknown flags"); return PIVOT_E_UNSUPPORTED; }
+    if (d.flags & ~(PIVOT_PLAN_GATHER_FROM_GLOBAL | PIVOT_PLAN_LSTM_LAUNCH_PER_STEP | PIVOT_PLAN_GATHER_FROM_LDS_COPY | PIVOT_PLAN_LSTM_ONE_LAUNCH_ALWAYS)) { set_error("unknown flags"); return PIVOT_E_UNSUPPORTED; }
     if (d.wg_waves != 0 && d.wg_waves != 4 && d.wg_waves != 8 && d.wg_waves != 16) { set_error("wg_waves must be 0, 4, 8 or 16"); return PIVOT_E_UNSUPPORTED; }
     if (d.row_slices != 0 && d.row_slices != 1 && d.row_slices != 2 && d.row_slices != 4 && d.row_slices != 8) { set_error("row_slices must be 0, 1, 2, 4 or 8"); return PIVOT_E_UNSUPPORTED; }
 
