@@ -208,7 +208,7 @@ def test_error_paths_return_codes():
     assert code(wdtype=7) == B.PIVOT_E_UNSUPPORTED
     assert code(layout=9) == B.PIVOT_E_UNSUPPORTED
     assert code(act=5) == B.PIVOT_E_UNSUPPORTED
-    assert code(flags=8) == B.PIVOT_E_UNSUPPORTED
+    assert code(flags=16) == B.PIVOT_E_UNSUPPORTED
     assert code(chunk_tiles=-2) == B.PIVOT_E_SHAPE
     # shapes the device kernels do not cover are refused before any GPU call
     assert code(device=0) == B.PIVOT_E_UNSUPPORTED            # 4x4 tiles
