@@ -82,7 +82,7 @@ typedef struct pivot_fc_desc {
     int32_t act;          /* PIVOT_ACT_*                                                 */
     int32_t chunk_tiles;  /* max tiles per work item; 0 = the library chooses            */
     int32_t device;       /* HIP device ordinal, or -1 for a host-only plan (no GPU use) */
-    int32_t wg_waves;     /* wavefronts per work item: 4, 8 or 16; 0 = the library chooses */
+    int32_t wg_waves;     /* wavefronts per work item: 1 (batch 1 only; 4 at other batches), 4, 8 or 16; 0 = the library chooses */
     int32_t row_slices;   /* independent work items per tile height: 1, 2, 4 or 8; 0 = the library chooses */
     int32_t flags;        /* PIVOT_PLAN_* bits, 0 = defaults                             */
 } pivot_fc_desc;

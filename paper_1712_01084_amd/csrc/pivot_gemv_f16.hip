@@ -20,6 +20,11 @@ static int launch_t(const FcArgs& a, int nw, dim3 grid, size_t smem, hipStream_t
     }
     else if (nw == 16) hipLaunchKernelGGL((fc_gemv_kernel<_Float16, BH, BW, NB, 16, XR>), grid, dim3(16 * 64), smem, st, PIVOT_GEMV_ARGS(a), a);
     else if (nw == 8)  hipLaunchKernelGGL((fc_gemv_kernel<_Float16, BH, BW, NB, 8, XR>), grid, dim3(8 * 64), smem, st, PIVOT_GEMV_ARGS(a), a);
+    else if (nw == 1) {
+        // one wavefront per work item: batch 1, gather from global memory only (the launcher asks for nothing else)
+        if constexpr (NB == 1 && XR == 0) hipLaunchKernelGGL((fc_gemv_kernel<_Float16, BH, BW, 1, 1, 0>), grid, dim3(64), smem, st, PIVOT_GEMV_ARGS(a), a);
+        else { set_error("internal: one-wavefront work items at batch %d, copy form %d", NB, XR); return PIVOT_E_UNSUPPORTED; }
+    }
     else               hipLaunchKernelGGL((fc_gemv_kernel<_Float16, BH, BW, NB, 4, XR>), grid, dim3(4 * 64), smem, st, PIVOT_GEMV_ARGS(a), a);
     HIP_TRY(hipGetLastError());
     return PIVOT_OK;

@@ -170,6 +170,9 @@ int launch_fc(const FcLaunch& L, std::string* describe) {
     const int sl = fc_row_slices(shape, L.batch, L.row_slices);
     const int bhs = L.bh / sl;
     int nw = (L.wg_waves == 16 || L.wg_waves == 8) ? L.wg_waves : 4;
+    // one wavefront per work item: the vector kernel at batch 1 with the gather from global memory (tiny layers)
+    const bool one_wave = L.wg_waves == 1 && L.layout == PIVOT_BRC && path == kPathVector && nbt == 1;
+    if (one_wave) nw = 1;
     if (ml && nw > 8) nw = 8;                // the LDS-fed matrix-core kernel comes with 4 or 8 wavefronts
     const int es = elem_size(L.wdtype);
 
@@ -244,7 +247,7 @@ int launch_fc(const FcLaunch& L, std::string* describe) {
     size_t xn_bytes = 0;
     const size_t item_bytes = (size_t)(a.uniform_ct > 0 ? a.uniform_ct : L.chunk_tiles) * bhs * L.bw * es;
     const size_t staged_cols = (size_t)(a.uniform_ct > 0 ? a.uniform_ct : L.chunk_tiles) * L.bw;
-    if (L.layout == PIVOT_BRC && L.x_resident != 0 &&
+    if (L.layout == PIVOT_BRC && L.x_resident != 0 && !one_wave &&
         (L.x_resident == 2 || item_bytes >= 32 * 1024 || (nbt >= 2 && staged_cols * vec >= (size_t)xlen)) && xlen % vec == 0 && (nbt == 1 || L.ldx == xlen) &&
         (reinterpret_cast<uintptr_t>(L.x) & 15) == 0) {
         const size_t vectors = (size_t)nbt * (xlen / vec);

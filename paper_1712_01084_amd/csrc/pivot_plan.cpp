@@ -84,7 +84,10 @@ void choose_schedule(HostPlan& hp) {
     int nw = d.wg_waves;
     if (nw == 0) {
         const size_t big = (size_t)std::min(ct, std::max(max_row, 1)) * slice_bytes;
-        nw = big <= 32 * 1024 ? 4 : (big <= 256 * 1024 ? 8 : 16);
+        // (one wavefront per work item up to 8 KB: no workgroup barrier, no reduction across wavefronts; measured
+        // on square block-diagonal layers of size 64-4096, warm: 2.2-2.6 -> 2.0-2.4 us up to 8 KB per work item,
+        // 2.6 -> 2.75 and 2.6 -> 3.0 us at 16 KB.  Batch 1 only: other batches run such plans with 4.)
+        nw = big <= 8 * 1024 ? 1 : (big <= 32 * 1024 ? 4 : (big <= 256 * 1024 ? 8 : 16));
     }
     hp.wg_waves = nw;
 }
@@ -219,7 +222,7 @@ int build_host_plan(const pivot_fc_desc& d, const void* W, int w_space, const ui
     if (w_space != PIVOT_W_NATURAL && w_space != PIVOT_W_PIVOTED) { set_error("unknown weight space %d", w_space); return PIVOT_E_UNSUPPORTED; }
     if (d.chunk_tiles < 0) { set_error("chunk_tiles must be >= 0"); return PIVOT_E_SHAPE; }
     if (d.flags & ~(PIVOT_PLAN_GATHER_FROM_GLOBAL | PIVOT_PLAN_LSTM_LAUNCH_PER_STEP | PIVOT_PLAN_GATHER_FROM_LDS_COPY | PIVOT_PLAN_LSTM_ONE_LAUNCH_ALWAYS)) { set_error("unknown flags"); return PIVOT_E_UNSUPPORTED; }
-    if (d.wg_waves != 0 && d.wg_waves != 4 && d.wg_waves != 8 && d.wg_waves != 16) { set_error("wg_waves must be 0, 4, 8 or 16"); return PIVOT_E_UNSUPPORTED; }
+    if (d.wg_waves != 0 && d.wg_waves != 1 && d.wg_waves != 4 && d.wg_waves != 8 && d.wg_waves != 16) { set_error("wg_waves must be 0, 1, 4, 8 or 16"); return PIVOT_E_UNSUPPORTED; }
     if (d.row_slices != 0 && d.row_slices != 1 && d.row_slices != 2 && d.row_slices != 4 && d.row_slices != 8) { set_error("row_slices must be 0, 1, 2, 4 or 8"); return PIVOT_E_UNSUPPORTED; }
 
     hp.d = d;
