@@ -102,7 +102,9 @@ def test_config4_full(eliminated, seed):
 @pytest.mark.parametrize("bh,bw,dims", [(32, 32, (300, 200, 136, 70)), (16, 16, (100, 90, 50)), (8, 64, (260, 72, 40, 24, 130)),
                                         (64, 16, (150, 190, 64)), (16, 32, (96, 64, 48)),
                                         (32, 32, (200, 256, 64, 256, 40)),     # workgroups 2-7 have no item in the narrow layer
-                                        (32, 32, (64, 2048, 40)), (16, 16, (40, 1500, 1200, 30))])   # later layers whose wavefronts stage more than 64 elements
+                                        (32, 32, (64, 2048, 40)), (16, 16, (40, 1500, 1200, 30)),    # later layers whose wavefronts stage more than 64 elements
+                                        (16, 16, (100, 32, 300)),              # most workgroups have no item in the first layer
+                                        (16, 32, (64, 300, 40, 130))])         # ... none in the middle layer
 @pytest.mark.parametrize("wdtype", [WL.F32, WL.F16])
 def test_one_launch_chain_batch1(wdtype, eliminated, bh, bw, dims):
     # chains whose work items are whole block rows run at batch 1 in ONE launch: intermediates travel as
