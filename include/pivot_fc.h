@@ -209,8 +209,8 @@ int    pivot_workspace_init(void* ws_dev, size_t ws_bytes, void* stream);
  *          fit in 48 KB (beyond batch 16: and the launch rows together
  *          stage at most 5120 columns per work item), else (batch >= 8)
  *          from a copy of x in block order made by one small extra kernel.
- *          Batch 9..16 with at most 4096 input columns, from a quarter of
- *          them staged per work item on: all 16 rows of x are copied into
+ *          Batch 5..16 with at most 4096 input columns, from a quarter of
+ *          them staged per work item on: the rows of x are copied into
  *          LDS and the fragments gathered from there (fastest when x is
  *          16-byte aligned, K a multiple of 8 and ldx == K; anything else
  *          gives the same results through an element-wise copy).

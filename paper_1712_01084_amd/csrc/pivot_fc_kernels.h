@@ -1029,7 +1029,7 @@ __global__ void __launch_bounds__(NW * 64) fc_mfma_lds_kernel(PIVOT_GEMV_PARAMS,
 }
 
 // ---------------------------------------------------------------------------
-// batch 9..16, fp16 weights: matrix cores with the B fragments gathered from a
+// batch 5..16, fp16 weights: matrix cores with the B fragments gathered from a
 // copy of x in LDS (Listing 1: the group fetch through P_col, done where the
 // fragment is formed).  Staging the x-segments of 16 batch rows element by
 // element costs a work item more than streaming its weights (16 rows x tiles x

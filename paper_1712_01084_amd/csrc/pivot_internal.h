@@ -126,8 +126,9 @@ enum { kPathVector = 0, kPathMfmaLds = 1, kPathMfmaGather = 2, kPathMfmaXrow = 3
 // What decides the path besides the batch.  `lds_tiles`: HostPlan::lds_tiles() (0 rules the LDS-fed matrix-core
 // kernel out); `chunk_tiles`, `xrow_len`: the plan's chunk size and HostPlan::xrow_len() (0 rules out the
 // matrix-core kernel that gathers its fragments from a copy of x in LDS).
-struct FcShape { int layout, wdtype, bh, bw, lds_tiles, chunk_tiles, xrow_len; };
-inline FcShape fc_shape(const HostPlan& h) { return FcShape{h.d.layout, h.d.wdtype, h.d.bh, h.d.bw, h.lds_tiles(), h.chunk_tiles, h.xrow_len()}; }
+struct FcShape { int layout, wdtype, bh, bw, lds_tiles, chunk_tiles, xrow_len, mean_tiles; };   // mean_tiles: kept tiles per work item, rounded up
+inline int mean_tiles_of(int T, int nchunks) { return nchunks > 0 ? (T + nchunks - 1) / nchunks : 0; }
+inline FcShape fc_shape(const HostPlan& h) { return FcShape{h.d.layout, h.d.wdtype, h.d.bh, h.d.bw, h.lds_tiles(), h.chunk_tiles, h.xrow_len(), mean_tiles_of(h.T, h.nchunks)}; }
 int    fc_path(const FcShape& s, int batch);
 int    fc_batch_tile(const FcShape& s, int batch);
 bool   fc_uses_matrix_cores(const FcShape& s, int batch);   // the form that needs x in block order

@@ -42,25 +42,36 @@ static int mfma_lds_rows(int batch) { return batch <= 4 ? 4 : 8; }
 // 50 %, 14.2 -> 12.4 dense; batch 16: 7.3 -> 6.1 at 5 %, 11.0 -> 9.5 at 25 %).  Letting it take up to 136 KB of
 // LDS (one workgroup per compute unit) for 16 staged rows at 50 % and dense was measured too: 13.5 -> 13.2 us and
 // 14.5 -> 15.4 us, so longer rows stay with the block-order form.
-//   kPathMfmaXrow    fp16, batch 9-16: MFMA with the B fragments gathered from a copy of the 16 rows of x in LDS
+//   kPathMfmaXrow    fp16, batch 5-16: MFMA with the B fragments gathered from a copy of the rows of x in LDS
 // At batch 9-16 the staging itself bounds the LDS-fed form (16 rows x staged columns two-byte gathers per work
 // item, repeated by every row slice, and the weights streamed once per launch row of 8); gathering where the
 // fragment is formed needs one copy of x per work item instead, whatever the number of staged columns.  The copy
 // costs a work item 1.5-2.3 us (4096 columns: 128 KB through one compute unit's memory pipeline before its first
 // MFMA), the gathers 0.2-0.9 us, so the form is taken from a quarter of the columns staged per work item on
 // (4096x4096, 64x16 tiles, batch 16, cold: 8.3 -> 7.1 us at 25 % kept, 12.5 -> 9.1 at 50 %, 14.9 -> 12.7 dense;
-// at 10 % it would lose, 6.0 -> 6.3, at 5 % 4.8 -> 6.3).
+// at 10 % it would lose, 6.0 -> 6.3, at 5 % 4.8 -> 6.3).  Batch 5-8 takes it under the same rule (only the rows
+// that exist are copied; same matrix, batch 8: 6.5 -> 6.1 us at 25 %, 9.65 -> 8.1 at 50 %, 12.45 -> 11.7 dense,
+// batch 5 the same within 0.1 us; warm 0.2 us slower at 25 %, 0.3-0.45 faster above); at batch 4 it loses
+// (5.6 -> 6.0, 7.7 -> 7.9, 9.8 -> 11.1).
 int fc_path(const FcShape& s, int batch) {
     const int layout = s.layout, wdtype = s.wdtype, bh = s.bh, bw = s.bw, lds_tiles = s.lds_tiles;
     // the matrix-core kernels read A fragments from row-major (BRC) tiles only
     if (layout != PIVOT_BRC || mfma_kind(wdtype, bh, bw) < 0 || batch < 3) return kPathVector;
-    if (batch > 8 && batch <= 16 && s.xrow_len > 0 && s.chunk_tiles > 0) {
+    if (batch >= 5 && batch <= 16 && s.xrow_len > 0 && s.chunk_tiles > 0) {
         // 16 rows of x (each with 16 zeroed bytes behind it) and the work item's gather indices in LDS; a lane
         // copies at most 8 vectors of a row, a thread at most 4 int4 of indices
         const size_t vecs = ((size_t)s.xrow_len + 7) / 8;
         const size_t cols = ((size_t)s.chunk_tiles + 1) * bw;
         const size_t lds = 16 * (vecs * 16 + 16) + cols * 4;
-        if (vecs <= 512 && cols <= 8192 && lds <= 156 * 1024 && cols * 4 >= (size_t)s.xrow_len) return kPathMfmaXrow;
+        // "a quarter of the columns staged per work item": at batch 5-8 of the AVERAGE work item.  With a few
+        // long block rows among many short ones most work items copy all of x for a handful of tiles, which the
+        // 8-row LDS-fed form does not: 8192x3072, 16x32 tiles, per-row counts from 96 down to 2, batch 8, x
+        // already in block order (a step of the recurrent layer): 11.0 -> 12.0 us.  (With x in natural order the
+        // copy wins on that matrix too, 12.0 -> 10.4 us, and on 4096x4096 with the same profile it loses at batch
+        // 16 and wins at batch 5-8; the path does not depend on where x comes from, and batch 9-16 keeps the rule
+        // it was measured with.)
+        const size_t rule_cols = batch <= 8 ? ((size_t)s.mean_tiles + 1) * bw : cols;
+        if (vecs <= 512 && cols <= 8192 && lds <= 156 * 1024 && rule_cols * 4 >= (size_t)s.xrow_len) return kPathMfmaXrow;
     }
     if (lds_tiles > 0) {
         const int rows = mfma_lds_rows(batch);
@@ -162,7 +173,7 @@ static std::string kernel_name(const char* fmt, A... args) {
 }
 
 int launch_fc(const FcLaunch& L, std::string* describe) {
-    const FcShape shape{L.layout, L.wdtype, L.bh, L.bw, L.lds_tiles, L.chunk_tiles, L.xrow_len};
+    const FcShape shape{L.layout, L.wdtype, L.bh, L.bw, L.lds_tiles, L.chunk_tiles, L.xrow_len, mean_tiles_of(L.T, L.nchunks)};
     const int path = fc_path(shape, L.batch);
     const bool mc = path == kPathMfmaGather, ml = path == kPathMfmaLds, mx = path == kPathMfmaXrow;
     const int nbt = fc_batch_tile(shape, L.batch);

@@ -1,4 +1,4 @@
-// Matrix-core layer kernel whose B fragments are gathered from a copy of x in LDS (fp16 weights, batch 9..16):
+// Matrix-core layer kernel whose B fragments are gathered from a copy of x in LDS (fp16 weights, batch 5..16):
 // instantiations and dispatch.
 #include "pivot_fc_kernels.h"
 

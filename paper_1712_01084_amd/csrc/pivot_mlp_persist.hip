@@ -440,7 +440,7 @@ const void* chain_kernel_for(int wdtype, int bw, bool short_items) {
 // Row slices of a layer inside the chain kernel: the plan's own choice, lowered until a slice holds at least
 // one 1 KB wave-load and 8 rows (the same rule as the layer kernel's).
 int chain_slices(const HostPlan& hp) {
-    return fc_row_slices(FcShape{hp.d.layout, hp.d.wdtype, hp.d.bh, hp.d.bw, hp.chunk_tiles, hp.chunk_tiles, 0}, 1, hp.row_slices);
+    return fc_row_slices(FcShape{hp.d.layout, hp.d.wdtype, hp.d.bh, hp.d.bw, hp.chunk_tiles, hp.chunk_tiles, 0, 0}, 1, hp.row_slices);
 }
 
 // True if no wavefront of an item of this layer stages more than 64 elements: its groups (wave, wave + 8, ...)

@@ -57,7 +57,7 @@ void choose_schedule(HostPlan& hp) {
         const int rpw = 64 / std::max(1, d.bw / vec);
         sl = 1;
         while (sl < 8 && hp.nbr * sl < 256 && d.bh / (sl * 2) >= rpw &&
-               fc_row_slices(FcShape{d.layout, d.wdtype, d.bh, d.bw, 0, 0, 0}, 1, sl * 2) == sl * 2) sl *= 2;
+               fc_row_slices(FcShape{d.layout, d.wdtype, d.bh, d.bw, 0, 0, 0, 0}, 1, sl * 2) == sl * 2) sl *= 2;
         // Still fewer work items than compute units, block rows that will stay whole (under 256 KB per work item)
         // and enough left per work item (16 KB): shorter slices, where a wave-load takes the same rows of several
         // consecutive tiles.  Measured on 4096x4096 with 64x16 fp16 tiles (64 block rows: 128 -> 256 work items):
@@ -65,9 +65,9 @@ void choose_schedule(HostPlan& hp) {
         // (1024x1024, 16x16 tiles) it costs 0.1 us, and where rows get cut anyway (dense) it costs 0.3 us cold.
         const size_t row_bytes = (size_t)max_row * tile_bytes;
         while (sl < 8 && hp.nbr * sl < 256 && row_bytes / sl < 256 * 1024 && row_bytes / (sl * 2) >= 16 * 1024 &&
-               fc_row_slices(FcShape{d.layout, d.wdtype, d.bh, d.bw, 0, 0, 0}, 1, sl * 2) == sl * 2) sl *= 2;
+               fc_row_slices(FcShape{d.layout, d.wdtype, d.bh, d.bw, 0, 0, 0, 0}, 1, sl * 2) == sl * 2) sl *= 2;
     }
-    if (d.device >= 0) sl = fc_row_slices(FcShape{d.layout, d.wdtype, d.bh, d.bw, 0, 0, 0}, 1, sl);
+    if (d.device >= 0) sl = fc_row_slices(FcShape{d.layout, d.wdtype, d.bh, d.bw, 0, 0, 0, 0}, 1, sl);
     hp.row_slices = sl;
 
     const size_t slice_bytes = std::max<size_t>(1, tile_bytes / sl);

@@ -125,14 +125,15 @@ def test_fp16_16_column_tiles_in_16_row_slices_pair_their_tiles(bh, sl, batch):
     G.check_fc(p, row_slices=sl)
 
 
-@pytest.mark.parametrize("batch", [9, 12, 16])
+@pytest.mark.parametrize("batch", [5, 8, 9, 12, 16])
 @pytest.mark.parametrize("bh,bw,K", [(64, 16, 1024), (64, 16, 1000), (32, 32, 4096), (16, 64, 333), (64, 64, 2048)])
-def test_fp16_batch_9_to_16_gathers_fragments_from_a_copy_of_x(bh, bw, K, batch):
-    # batch 9..16: all 16 rows of x are copied into LDS and every lane gathers the eight values of its B fragment
+def test_fp16_batch_5_to_16_gathers_fragments_from_a_copy_of_x(bh, bw, K, batch):
+    # batch 5..16: the rows of x are copied into LDS and every lane gathers the eight values of its B fragment
     # from there.  Rows that are whole aligned vectors are copied with 16-byte loads, anything else (K not a
     # multiple of 8, a row stride above K, an x that starts off a 16-byte boundary) element by element; rows past
     # the batch are never read from memory; whole and split block rows, every row-slice form, an empty block row
-    p = WL.gen_fc(3 * bh + 7, K, bh, bw, 0.3, seed=300 + batch + bh, wdtype=WL.F16, batch=batch, act=WL.ACT_RELU)
+    # (batch 5..8 takes this form from a quarter of the columns per AVERAGE work item on, hence the denser mask)
+    p = WL.gen_fc(3 * bh + 7, K, bh, bw, 0.3 if batch > 8 else 0.5, seed=300 + batch + bh, wdtype=WL.F16, batch=batch, act=WL.ACT_RELU)
     p.tile_mask[1, :] = 0
     plan = G.dev_plan(p)
     try:
