@@ -77,6 +77,19 @@ void choose_schedule(HostPlan& hp) {
         int parts = std::max(1, (max_row + cap - 1) / cap);
         while ((size_t)hp.nbr * sl * parts < 256 && (size_t)max_row * slice_bytes / parts >= 256 * 1024) parts *= 2;
         ct = std::max(1, (max_row + parts - 1) / parts);
+        // Strongly skewed masks (the longest block row at least four times the average one): the few long rows set
+        // the launch time while most work items are short, so long rows are cut in spite of the hand-over, into
+        // pieces of twice the average row, kept between 32 and 96 KB per work item.  Measured with per-row counts
+        // following a Zipf profile, cold, batch 1 / batch 4 (8 for fp16), whole rows -> pieces: 8192x3072 16x32
+        // fp16 5.95 -> 5.6 / 12.0 -> 7.9 us (a step of the launch-per-step recurrent form 11.0 -> 8.9);
+        // 4096x4096 32x32 fp32 8.7 -> 6.6 / 14.2 -> 9.1; 2048x8192 16x16 fp32 8.4 -> 7.0 / 15.8 -> 10.5;
+        // 4096x9216 32x32 fp32 9.5 -> 8.4 / 16.6 -> 13.3 (pieces of 32 KB there: 11.6 / 14.4).  Warm launches at
+        // batch 1 lose up to 0.7 us to the hand-over.
+        if (hp.nbr > 0 && (long long)max_row * hp.nbr >= 4LL * hp.T) {
+            const int lo = (int)std::max<size_t>(1, (32 * 1024) / slice_bytes), hi = (int)std::max<size_t>(1, (96 * 1024) / slice_bytes);
+            const int want = std::min(hi, std::max(lo, 2 * ((hp.T + hp.nbr - 1) / hp.nbr)));
+            if (want < ct) ct = want;
+        }
     }
     if (d.device >= 0) ct = std::min(ct, max_chunk_tiles(d));
     build_schedule(hp, ct);
