@@ -109,6 +109,12 @@ int fc_row_slices(const FcShape& s, int batch, int want) {
     const int layout = s.layout, wdtype = s.wdtype, bh = s.bh, bw = s.bw;
     if (layout != PIVOT_BRC) return 1;       // a row slice is contiguous only in row-major tiles
     int sl = want < 1 ? 1 : want;
+    // The LDS-fed matrix-core kernel beyond 8 batch rows (several launch rows of 8): every row slice of a block
+    // row stages the same x-segments again, so at most two slices (4096x4096, 64x16 tiles, cold, four slices ->
+    // two: 10 % kept, batch 12 / 16 / 24 / 32 / 64: 5.9 -> 5.4, 5.9 -> 5.4, 7.2 -> 6.4, 8.45 -> 7.1, 12.8 -> 10.3
+    // us; 25 % kept, batch 24 / 32: 10.8 -> 9.3, 12.7 -> 10.2; one slice: 6.6 at batch 16; up to batch 8 four
+    // slices are the faster, 4.9 against 5.3 us).
+    if (sl > 2 && batch > 8 && fc_path(s, batch) == kPathMfmaLds) sl = 2;
     while (sl > 1) {
         bool ok = (bh % sl == 0);
         const int bhs = bh / sl;
