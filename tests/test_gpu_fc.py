@@ -157,6 +157,27 @@ def test_fp16_batch_5_to_16_gathers_fragments_from_a_copy_of_x(bh, bw, K, batch)
     G.check_fc(p, row_slices=4)
 
 
+@pytest.mark.parametrize("batch", [1, 3, 8, 16])
+@pytest.mark.parametrize("M,K,bh,bw,wdtype,frac", [(2048, 3072, 16, 32, WL.F16, 0.125), (1024, 4096, 32, 32, WL.F32, 0.125),
+                                                     (4096, 2048, 64, 16, WL.F16, 0.125), (512, 4096, 8, 8, WL.F32, 0.2)])
+def test_skewed_masks_cut_long_block_rows(M, K, bh, bw, wdtype, frac, batch):
+    # per-row tile counts following a Zipf profile (the longest block row at least four times the average one):
+    # the library cuts long rows into pieces of twice the average row (32..96 KB per work item), so these layers
+    # run with hand-overs between the pieces of a row at every batch size and through every kernel family
+    p = WL.gen_fc(M, K, bh, bw, frac, seed=400 + bh + batch, wdtype=wdtype, batch=batch, mask="zipf", act=WL.ACT_RELU)
+    cnt = p.tile_mask.sum(axis=1)
+    assert cnt.max() >= 4 * cnt.mean()
+    plan = G.dev_plan(p)
+    try:
+        v = B.pivot_fc_plan_host_view(plan)
+        es = 4 if wdtype == WL.F32 else 2
+        piece = v["chunk_tiles"] * (bh // v["row_slices"]) * bw * es
+        assert v["chunk_tiles"] < cnt.max() and 32 * 1024 <= piece <= 96 * 1024, (v["chunk_tiles"], piece)
+    finally:
+        B.pivot_fc_plan_destroy(plan)
+    G.check_fc(p)
+
+
 @pytest.mark.parametrize("batch", [16, 33, 64])
 def test_fp16_long_rows_use_the_block_order_copy(batch):
     # work items too long for the LDS-fed form (8 batch rows of 4096 staged columns exceed its 48 KB; at batch 64
