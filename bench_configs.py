@@ -176,7 +176,7 @@ def time_lstm(lp, name, per_step=False):
                            p.bias, act=p.act, device=0,
                            flags=B.PIVOT_PLAN_LSTM_LAUNCH_PER_STEP if per_step else B.PIVOT_PLAN_LSTM_ONE_LAUNCH_ALWAYS)
     # (ONE_LAUNCH_ALWAYS: the one-step sequences below are to time the one-launch form's first step; left to itself
-    # pivot_lstm_run takes the launch-per-step form for sequences of fewer than 6 steps)
+    # pivot_lstm_run takes the launch-per-step form for sequences of fewer than 4 steps)
     steps, batch = lp.xs.shape[0], lp.xs.shape[1]
     xsd = torch.from_numpy(lp.xs).cuda()
     hd = torch.zeros((batch, lp.H), device="cuda")

@@ -103,7 +103,7 @@ typedef struct pivot_fc_desc {
  * per step instead (for measurements and as the reference of the parity test). */
 #define PIVOT_PLAN_LSTM_LAUNCH_PER_STEP 2
 /* ... and this one keeps the one-launch form (where the plan allows it) also for sequences of fewer than
- * 6 steps, which pivot_lstm_run otherwise runs with a launch per step (for measurements and tests). */
+ * 4 steps, which pivot_lstm_run otherwise runs with a launch per step (for measurements and tests). */
 #define PIVOT_PLAN_LSTM_ONE_LAUNCH_ALWAYS 8
 
 typedef struct pivot_fc_plan pivot_fc_plan_t;
@@ -342,12 +342,12 @@ int    pivot_mlp_status_word(const pivot_mlp_plan_t* plan, const uint32_t** word
  * the device while it runs; a wait that does not end within 2^18 polls gives
  * up, every workgroup leaves, h/c are left unwritten and the status word
  * reads 1.  Every other plan (or
- * PIVOT_PLAN_LSTM_LAUNCH_PER_STEP), and every sequence of fewer than 6 steps,
+ * PIVOT_PLAN_LSTM_LAUNCH_PER_STEP), and every sequence of fewer than 4 steps,
  * runs one layer launch and one cell launch per step (the one-launch form
  * loads every kept tile into registers first: a first step from weights that
- * are not in cache costs it 28 us on the 8192x3072 workload against 18 us with
- * launches per step, every further step 6.8 against 8.9 us: it is ahead from
- * the sixth step on).  pivot_lstm_status synchronises the stream and returns the status
+ * are not in cache costs it 23 us on the 8192x3072 workload against 18 us with
+ * launches per step, every further step 6.8 against 9.1 us: it is ahead from
+ * the fourth step on).  pivot_lstm_status synchronises the stream and returns the status
  * word of the last pivot_lstm_run on this workspace (0 = completed).
  */
 size_t pivot_lstm_workspace_bytes(const pivot_fc_plan_t* plan, int H, int I, int steps, int batch);

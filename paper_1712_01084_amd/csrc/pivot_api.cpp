@@ -557,10 +557,11 @@ int pivot_lstm_run(const pivot_fc_plan_t* plan, int H, int I, const void* xs_dev
     float* z = reinterpret_cast<float*>(ws + m.z_off);
     char* xg = ws + m.xg_off;
     int rc;
-    // (fewer than 6 steps: loading every tile into registers first does not pay yet)
-    if (!(h.d.flags & PIVOT_PLAN_LSTM_LAUNCH_PER_STEP) && (steps >= 6 || (h.d.flags & PIVOT_PLAN_LSTM_ONE_LAUNCH_ALWAYS)) && lstm_persist_supported(h, H, batch, plan->device, nullptr, nullptr)) {
+    // (fewer than 4 steps: loading every tile into registers first does not pay yet)
+    if (!(h.d.flags & PIVOT_PLAN_LSTM_LAUNCH_PER_STEP) && (steps >= 4 || (h.d.flags & PIVOT_PLAN_LSTM_ONE_LAUNCH_ALWAYS)) && lstm_persist_supported(h, H, batch, plan->device, nullptr, nullptr)) {
         // one launch for the whole sequence
-        if ((rc = launch_fill_zero(ws + m.ctl_off, m.xg_off - m.ctl_off, stream)) != PIVOT_OK) return rc;   // control words + partials
+        // control words + the partial buffers this sequence will use
+        if ((rc = launch_fill_zero(ws + m.ctl_off, (m.part_off - m.ctl_off) + lstm_persist_used_partial_bytes(h, batch, steps), stream)) != PIVOT_OK) return rc;
         LstmPersistLaunch P{};
         P.hp = &h;
         P.vals = plan->dev.vals; P.col_idx = plan->dev.col_idx; P.row_ptr = plan->dev.row_ptr;

@@ -186,6 +186,7 @@ struct LstmPersistLaunch {
 };
 bool   lstm_persist_supported(const HostPlan& hp, int H, int batch, int device, int* grid_out, int* L_out);
 size_t lstm_persist_partial_bytes(const HostPlan& hp, int batch);
+size_t lstm_persist_used_partial_bytes(const HostPlan& hp, int batch, int steps);
 constexpr size_t kLstmCtlBytes = 2048;
 int    launch_lstm_persist(const LstmPersistLaunch& P);
 

@@ -471,6 +471,13 @@ bool lstm_persist_supported(const HostPlan& hp, int H, int batch, int device, in
 }
 
 size_t lstm_persist_partial_bytes(const HostPlan& hp, int batch) { return align_up((size_t)kPBuf * hp.T * batch * 16 * 8, 256); }
+// The part of them a sequence of `steps` steps uses (step t: buffer t % kPBuf) and that therefore has to be zero
+// before the launch: a short sequence clears one buffer per step instead of all eight (6 MB each on the
+// 8192x3072 workload at batch 8).
+size_t lstm_persist_used_partial_bytes(const HostPlan& hp, int batch, int steps) {
+    const size_t nbuf = steps < kPBuf ? (steps > 0 ? steps : 1) : kPBuf;
+    return std::min(lstm_persist_partial_bytes(hp, batch), align_up(nbuf * hp.T * batch * 16 * 8, 256));
+}
 
 int launch_lstm_persist(const LstmPersistLaunch& P) {
     int G = 0, L = 0;

@@ -296,7 +296,7 @@ def _check_lstm_steps(lp, record, tol, per_step=False, windows=(), window_len=12
     h_end, c_end, rec = O.oracle_lstm(Wd, p.bias, lp.xs, lp.h0, lp.c0, lp.H, state_dtype=sd,
                                       record=tuple(record) + tuple(windows))
     # (ONE_LAUNCH_ALWAYS: the single steps and the short windows below are to exercise the one-launch kernel too,
-    # which the library otherwise takes from 6 steps on)
+    # which the library otherwise takes from 4 steps on)
     plan = G.dev_plan(p, flags=B.PIVOT_PLAN_LSTM_LAUNCH_PER_STEP if per_step else B.PIVOT_PLAN_LSTM_ONE_LAUNCH_ALWAYS)
     try:
         H = lp.H
@@ -365,23 +365,23 @@ def test_lstm_one_launch_ragged_shapes(H, I, batch, frac):
 
 
 def test_lstm_short_sequences_take_the_launch_per_step_form():
-    # fewer than 6 steps: the library runs a launch per step even where the one-launch form exists (same bits as
+    # fewer than 4 steps: the library runs a launch per step even where the one-launch form exists (same bits as
     # the plan that asks for launches per step); PIVOT_PLAN_LSTM_ONE_LAUNCH_ALWAYS keeps the one-launch kernel,
-    # whose fixed summation order is another one (same values within the tolerance); from 6 steps on the default
+    # whose fixed summation order is another one (same values within the tolerance); from 4 steps on the default
     # is the one-launch form
     lp = WL.config5(seed=9, batch=8, H=256, I=128, steps=8, frac=0.25)
     res = {}
     for name, flags in (("default", 0), ("per_step", B.PIVOT_PLAN_LSTM_LAUNCH_PER_STEP), ("one_launch", B.PIVOT_PLAN_LSTM_ONE_LAUNCH_ALWAYS)):
         plan = G.dev_plan(lp.fc, flags=flags)
         try:
-            res[name] = {n: _lstm_gpu(lp, plan, lp.xs[:n], lp.h0, lp.c0, want_z=True) for n in (1, 2, 5, 6)}
+            res[name] = {n: _lstm_gpu(lp, plan, lp.xs[:n], lp.h0, lp.c0, want_z=True) for n in (1, 2, 3, 4)}
         finally:
             B.pivot_fc_plan_destroy(plan)
-    for n in (1, 2, 5):
+    for n in (1, 2, 3):
         for a, b in zip(res["default"][n], res["per_step"][n]):
             assert np.array_equal(a, b), n
         assert np.abs(res["default"][n][0] - res["one_launch"][n][0]).max() < 2e-3
-    for a, b in zip(res["default"][6], res["one_launch"][6]):
+    for a, b in zip(res["default"][4], res["one_launch"][4]):
         assert np.array_equal(a, b)
 
 
