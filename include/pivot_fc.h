@@ -80,7 +80,11 @@ typedef struct pivot_fc_desc {
     int32_t wdtype;       /* PIVOT_F32 or PIVOT_F16                                      */
     int32_t layout;       /* PIVOT_BRC / BCR / CBR                                       */
     int32_t act;          /* PIVOT_ACT_*                                                 */
-    int32_t chunk_tiles;  /* max tiles per work item; 0 = the library chooses            */
+    int32_t chunk_tiles;  /* max tiles per work item; 0 = the library chooses: whole block rows
+                           * unless LDS forces a cut, a work item would stream 256 KB or more while
+                           * compute units idle, or the longest block row has at least four times
+                           * the average number of tiles (then pieces of twice the average row,
+                           * 32..96 KB per work item)                                     */
     int32_t device;       /* HIP device ordinal, or -1 for a host-only plan (no GPU use) */
     int32_t wg_waves;     /* wavefronts per work item: 1 (batch 1 only; 4 at other batches), 4, 8 or 16; 0 = the library chooses */
     int32_t row_slices;   /* independent work items per tile height: 1, 2, 4 or 8; 0 = the library chooses */
